@@ -1,0 +1,193 @@
+"""ctypes front end of the float64 CPU oracle (oracle/leoam_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by
+bench.py's cpu_baseline leg.  The product package never imports it and it never
+imports the product package.
+
+Inputs are numpy arrays or CPU torch tensors in their stored dtype (fp32, fp16,
+bf16); they are widened exactly to double inside the C code.  Outputs are numpy
+arrays: doubles for attention, float32 scores (the double sum rounded once, the
+precision the selection is taken in), int32 selections.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "leoam_oracle.c")
+_LIB = os.path.join(_HERE, "libleoam_oracle.so")
+_lib = None
+
+F32, F16, BF16, F64 = 0, 1, 2, 3
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, OpenMP over (sequence, head))."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared", "-std=c11", _SRC, "-lm", "-o", _LIB]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.orc_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().orc_num_threads())
+
+
+def set_threads(n: int) -> None:
+    _load().orc_set_threads(ctypes.c_int(n))
+
+
+def _as_numpy(x) -> Tuple[np.ndarray, int]:
+    """Return (contiguous numpy view of the stored bits, dtype tag)."""
+    try:
+        import torch
+        if isinstance(x, torch.Tensor):
+            x = x.detach().cpu().contiguous()
+            if x.dtype == torch.bfloat16:
+                return x.view(torch.int16).numpy().view(np.uint16), BF16
+            x = x.numpy()
+    except ImportError:  # pragma: no cover
+        pass
+    x = np.ascontiguousarray(x)
+    if x.dtype == np.float32:
+        return x, F32
+    if x.dtype == np.float16:
+        return x.view(np.uint16), F16
+    if x.dtype == np.float64:
+        return x, F64
+    raise TypeError(f"unsupported dtype {x.dtype}")
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _i32(x) -> np.ndarray:
+    try:
+        import torch
+        if isinstance(x, torch.Tensor):
+            x = x.detach().cpu().numpy()
+    except ImportError:  # pragma: no cover
+        pass
+    return np.ascontiguousarray(x, dtype=np.int32)
+
+
+def widen(x) -> np.ndarray:
+    """Exact float64 copy of a stored fp32/fp16/bf16 array."""
+    a, tag = _as_numpy(x)
+    out = np.empty(a.shape, dtype=np.float64)
+    _load().orc_widen(_ptr(a), ctypes.c_int(tag), ctypes.c_size_t(0), ctypes.c_size_t(a.size), _ptr(out))
+    return out
+
+
+def abstract_build(K, chunk_off, n_chunks) -> np.ndarray:
+    """Sec. 4.3 abstract: float64 [B,Hkv,c_max,2,D]; [..,0,:]=kmax, [..,1,:]=kmin.
+    Rows of unused chunks are NaN."""
+    a, tag = _as_numpy(K)
+    B, Hkv, N, D = a.shape
+    off = _i32(chunk_off)
+    nc = _i32(n_chunks)
+    c_max = off.shape[1] - 1
+    _check_boundaries(off, nc, N)
+    out = np.full((B, Hkv, c_max, 2, D), np.nan, dtype=np.float64)
+    rc = _load().orc_abstract_build(tag, B, Hkv, N, D, _ptr(a), _ptr(off), _ptr(nc), c_max, _ptr(out))
+    assert rc == 0
+    return out
+
+
+def _check_boundaries(off: np.ndarray, nc: np.ndarray, N: int) -> None:
+    for b in range(off.shape[0]):
+        row = off[b, : nc[b] + 1]
+        if row[0] != 0 or row[-1] != N or np.any(np.diff(row) <= 0):
+            raise ValueError(f"chunk boundaries of sequence {b} do not tile [0,{N})")
+
+
+def chunk_score(q, abstract, n_chunks, want_lower: bool = False, want_f64: bool = False):
+    """Sec. 4.1/4.3 bounds.  q [B,Hq,D]; abstract float64 [B,Hkv,c_max,2,D].
+    Returns ub float32 [B,Hkv,c_max] (and lb, ub64, lb64 on request)."""
+    qd = widen(q) if not (isinstance(q, np.ndarray) and q.dtype == np.float64) else np.ascontiguousarray(q)
+    ab = np.ascontiguousarray(abstract, dtype=np.float64)
+    B, Hq, D = qd.shape
+    _, Hkv, c_max, two, D2 = ab.shape
+    assert two == 2 and D2 == D and Hq % Hkv == 0
+    nc = _i32(n_chunks)
+    ub = np.empty((B, Hkv, c_max), dtype=np.float32)
+    lb = np.empty((B, Hkv, c_max), dtype=np.float32)
+    ub64 = np.empty((B, Hkv, c_max), dtype=np.float64)
+    lb64 = np.empty((B, Hkv, c_max), dtype=np.float64)
+    rc = _load().orc_chunk_score(B, Hq, Hkv, D, _ptr(qd), _ptr(ab), _ptr(nc), c_max, _ptr(ub), _ptr(lb),
+                                 _ptr(ub64), _ptr(lb64))
+    assert rc == 0
+    res = [ub]
+    if want_lower:
+        res.append(lb)
+    if want_f64:
+        res += [ub64, lb64] if want_lower else [ub64]
+    return res[0] if len(res) == 1 else tuple(res)
+
+
+def topk_select(score, chunk_off, n_chunks, max_chunks: int, token_budget: int, k_max: int,
+                want_margin: bool = False):
+    """Sec. 4.2/6.1 selection.  Returns (sel_idx [B,Hkv,k_max], sel_count, sel_tokens[, margin])."""
+    s = np.ascontiguousarray(score, dtype=np.float32)
+    B, Hkv, c_max = s.shape
+    off = _i32(chunk_off)
+    nc = _i32(n_chunks)
+    assert off.shape == (B, c_max + 1)
+    sel = np.empty((B, Hkv, k_max), dtype=np.int32)
+    cnt = np.empty((B, Hkv), dtype=np.int32)
+    tok = np.empty((B, Hkv), dtype=np.int32)
+    mar = np.empty((B, Hkv), dtype=np.float64)
+    rc = _load().orc_topk_select(B, Hkv, _ptr(s), _ptr(off), _ptr(nc), c_max, int(max_chunks), int(token_budget),
+                                 int(k_max), _ptr(sel), _ptr(cnt), _ptr(tok), _ptr(mar))
+    if rc != 0:
+        raise ValueError("k_max too small for the selection")
+    return (sel, cnt, tok, mar) if want_margin else (sel, cnt, tok)
+
+
+def sparse_attention(q, K, V, chunk_off, sel_idx, sel_count, scale: Optional[float] = None):
+    """Eq. (1) over the selected chunks.  Returns (out float64 [B,Hq,D], lse float64 [B,Hq])."""
+    ka, tag = _as_numpy(K)
+    va, tag_v = _as_numpy(V)
+    assert tag == tag_v and ka.shape == va.shape
+    B, Hkv, N, D = ka.shape
+    qd = widen(q) if not (isinstance(q, np.ndarray) and q.dtype == np.float64) else np.ascontiguousarray(q)
+    Hq = qd.shape[1]
+    off = _i32(chunk_off)
+    c_max = off.shape[1] - 1
+    sel = _i32(sel_idx)
+    cnt = _i32(sel_count)
+    k_max = sel.shape[2]
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    out = np.empty((B, Hq, D), dtype=np.float64)
+    lse = np.empty((B, Hq), dtype=np.float64)
+    fn = _load().orc_sparse_attention
+    rc = fn(tag, B, Hq, Hkv, N, D, _ptr(qd), _ptr(ka), _ptr(va), _ptr(off), c_max, _ptr(sel), _ptr(cnt), k_max,
+            ctypes.c_double(scale), _ptr(out), _ptr(lse))
+    assert rc == 0
+    return out, lse
+
+
+def decode_step(q, K, V, chunk_off, n_chunks, max_chunks, token_budget, k_max, abstract=None):
+    """The whole per-step path in the paper's order: (abstract) -> score -> select -> attention."""
+    if abstract is None:
+        abstract = abstract_build(K, chunk_off, n_chunks)
+    ub = chunk_score(q, abstract, n_chunks)
+    sel, cnt, tok = topk_select(ub, chunk_off, n_chunks, max_chunks, token_budget, k_max)
+    out, lse = sparse_attention(q, K, V, chunk_off, sel, cnt)
+    return dict(abstract=abstract, score=ub, sel_idx=sel, sel_count=cnt, sel_tokens=tok, out=out, lse=lse)

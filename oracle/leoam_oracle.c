@@ -1,0 +1,302 @@
+/*
+ * Float64 CPU oracle for the chunked sparse-attention decode step.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the
+ * tests, the smoke check and the benchmark's cpu_baseline leg compare the HIP
+ * library against.  Nothing in the product path may call it, and it shares no
+ * code, header, table or helper with the HIP sources.
+ *
+ * Each function follows one passage of the paper (arXiv 2506.20187):
+ *   orc_abstract_build   Sec. 4.3 "KV abstract extraction": the element-wise
+ *                        maximum and minimum key vectors of a chunk.
+ *   orc_chunk_score      Sec. 4.1 (chunk importance = upper bound of token
+ *                        importance inside the chunk) and Sec. 4.3 (upper and
+ *                        lower bounds from the abstract and the query).
+ *   orc_topk_select      Sec. 4.2 (priority queue ordered by upper bound,
+ *                        read from the front) and Sec. 6.1 (load only the
+ *                        most important share of the cache).
+ *   orc_sparse_attention Sec. 2.1 Eq. (1), restricted to the selected tokens.
+ *
+ * All floating-point work is done in double.  Stored fp32/fp16/bf16 inputs
+ * are widened exactly.  Pinned by tests/test_oracle_*.py; no function here is
+ * "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORC_F32 = 0, ORC_F16 = 1, ORC_BF16 = 2, ORC_F64 = 3 };
+
+int orc_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void orc_set_threads(int n) {
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+/* IEEE binary16 -> double, exact, including subnormals. */
+static double half_to_double(uint16_t h) {
+    int sign = (h >> 15) & 1;
+    int e = (h >> 10) & 0x1f;
+    int m = h & 0x3ff;
+    double v;
+    if (e == 0) {
+        v = ldexp((double)m, -24);
+    } else if (e == 31) {
+        v = m ? NAN : INFINITY;
+    } else {
+        v = ldexp((double)(m | 0x400), e - 25);
+    }
+    return sign ? -v : v;
+}
+
+/* bfloat16 is the upper half of a binary32. */
+static double bf16_to_double(uint16_t b) {
+    uint32_t u = ((uint32_t)b) << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+static inline double widen(const void *p, int dtype, size_t i) {
+    switch (dtype) {
+    case ORC_F32: return (double)((const float *)p)[i];
+    case ORC_F16: return half_to_double(((const uint16_t *)p)[i]);
+    case ORC_BF16: return bf16_to_double(((const uint16_t *)p)[i]);
+    default: return ((const double *)p)[i];
+    }
+}
+
+/* widen n elements starting at element index `start` */
+void orc_widen(const void *src, int dtype, size_t start, size_t n, double *dst) {
+    for (size_t i = 0; i < n; ++i) dst[i] = widen(src, dtype, start + i);
+}
+
+/*
+ * Sec. 4.3: abstract of chunk c of (b,h) = (kmax, kmin) with
+ *   kmax[d] = max over t in [off[c], off[c+1]) of K[b,h,t,d], kmin likewise.
+ * K: [B,Hkv,N,D] of `dtype`.  chunk_off: [B, c_max+1].  n_chunks: [B].
+ * abs_out: double [B,Hkv,c_max,2,D]; [..,0,:] = kmax, [..,1,:] = kmin.
+ * Rows of chunks >= n_chunks[b] are left untouched.
+ */
+int orc_abstract_build(int dtype, int B, int Hkv, int N, int D, const void *K, const int32_t *chunk_off,
+                       const int32_t *n_chunks, int c_max, double *abs_out) {
+    int bh;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (bh = 0; bh < B * Hkv; ++bh) {
+        int b = bh / Hkv;
+        const int32_t *off = chunk_off + (size_t)b * (c_max + 1);
+        for (int c = 0; c < n_chunks[b]; ++c) {
+            double *kmax = abs_out + (((size_t)bh * c_max + c) * 2 + 0) * D;
+            double *kmin = abs_out + (((size_t)bh * c_max + c) * 2 + 1) * D;
+            for (int d = 0; d < D; ++d) {
+                kmax[d] = -INFINITY;
+                kmin[d] = INFINITY;
+            }
+            for (int t = off[c]; t < off[c + 1]; ++t) {
+                size_t row = ((size_t)bh * N + t) * D;
+                for (int d = 0; d < D; ++d) {
+                    double x = widen(K, dtype, row + d);
+                    if (x > kmax[d]) kmax[d] = x;
+                    if (x < kmin[d]) kmin[d] = x;
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+/*
+ * Sec. 4.1 / 4.3: bounds on q.k over the tokens of a chunk from its abstract:
+ *   U_j[c] = sum_d max(q_j[d]*kmax[d], q_j[d]*kmin[d])   (upper)
+ *   L_j[c] = sum_d min(q_j[d]*kmax[d], q_j[d]*kmin[d])   (lower)
+ * For grouped-query attention the kv head's chunk score is the largest U over
+ * the query heads of its group and the smallest L.
+ * The stored score is the double sum rounded once to float, with -0 turned
+ * into +0.  ub64/lb64 (nullable) receive the unrounded double values.
+ * q: double [B,Hq,D]; abstract: double [B,Hkv,c_max,2,D].
+ * Scores of chunks >= n_chunks[b] are set to -inf (ub) / +inf (lb).
+ */
+int orc_chunk_score(int B, int Hq, int Hkv, int D, const double *q, const double *abstract,
+                    const int32_t *n_chunks, int c_max, float *ub, float *lb, double *ub64, double *lb64) {
+    int G = Hq / Hkv;
+    int bh;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (bh = 0; bh < B * Hkv; ++bh) {
+        int b = bh / Hkv, h = bh % Hkv;
+        for (int c = 0; c < c_max; ++c) {
+            size_t o = (size_t)bh * c_max + c;
+            if (c >= n_chunks[b]) {
+                if (ub) ub[o] = -INFINITY;
+                if (lb) lb[o] = INFINITY;
+                if (ub64) ub64[o] = -INFINITY;
+                if (lb64) lb64[o] = INFINITY;
+                continue;
+            }
+            const double *kmax = abstract + (o * 2 + 0) * D;
+            const double *kmin = abstract + (o * 2 + 1) * D;
+            double best_u = -INFINITY, best_l = INFINITY;
+            for (int g = 0; g < G; ++g) {
+                const double *qj = q + ((size_t)b * Hq + (size_t)h * G + g) * D;
+                double u = 0.0, l = 0.0;
+                for (int d = 0; d < D; ++d) {
+                    double a = qj[d] * kmax[d], z = qj[d] * kmin[d];
+                    u += (a > z) ? a : z;
+                    l += (a < z) ? a : z;
+                }
+                if (u > best_u) best_u = u;
+                if (l < best_l) best_l = l;
+            }
+            if (ub) ub[o] = (float)best_u + 0.0f;
+            if (lb) lb[o] = (float)best_l + 0.0f;
+            if (ub64) ub64[o] = best_u;
+            if (lb64) lb64[o] = best_l;
+        }
+    }
+    return 0;
+}
+
+typedef struct {
+    float s;
+    int32_t id;
+} orc_item;
+
+static int item_cmp(const void *a, const void *b) {
+    const orc_item *x = (const orc_item *)a, *y = (const orc_item *)b;
+    if (x->s > y->s) return -1;
+    if (x->s < y->s) return 1;
+    return (x->id > y->id) - (x->id < y->id);
+}
+
+static int int_cmp(const void *a, const void *b) {
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/*
+ * Sec. 4.2 / 6.1: order the chunks of (b,h) by score, highest first, equal
+ * scores by lowest chunk index; read the list from the front and keep chunks
+ * while the count stays <= max_chunks and the token total <= token_budget;
+ * stop at the first chunk that does not fit.  A limit <= 0 is "no limit".
+ * sel_idx: [B,Hkv,k_max], the kept chunk ids in ascending order, rest -1.
+ * margin (nullable, [B,Hkv]): score of the last kept chunk minus score of the
+ * first one left out (inf when nothing is left out or nothing is kept).
+ * Returns -1 if some row would keep more than k_max chunks.
+ */
+int orc_topk_select(int B, int Hkv, const float *score, const int32_t *chunk_off, const int32_t *n_chunks,
+                    int c_max, int max_chunks, int token_budget, int k_max, int32_t *sel_idx,
+                    int32_t *sel_count, int32_t *sel_tokens, double *margin) {
+    int rc = 0;
+    int bh;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (bh = 0; bh < B * Hkv; ++bh) {
+        int b = bh / Hkv;
+        int C = n_chunks[b];
+        const int32_t *off = chunk_off + (size_t)b * (c_max + 1);
+        orc_item *it = (orc_item *)malloc(sizeof(orc_item) * (size_t)(C > 0 ? C : 1));
+        for (int c = 0; c < C; ++c) {
+            it[c].s = score[(size_t)bh * c_max + c];
+            it[c].id = c;
+        }
+        qsort(it, (size_t)C, sizeof(orc_item), item_cmp);
+        int kept = 0;
+        long tokens = 0;
+        for (int i = 0; i < C; ++i) {
+            int sz = off[it[i].id + 1] - off[it[i].id];
+            if (max_chunks > 0 && kept + 1 > max_chunks) break;
+            if (token_budget > 0 && tokens + sz > token_budget) break;
+            kept += 1;
+            tokens += sz;
+        }
+        int32_t *row = sel_idx + (size_t)bh * k_max;
+        for (int i = 0; i < k_max; ++i) row[i] = -1;
+        if (kept > k_max) {
+#pragma omp critical
+            rc = -1;
+            kept = 0;
+            tokens = 0;
+        }
+        for (int i = 0; i < kept; ++i) row[i] = it[i].id;
+        qsort(row, (size_t)kept, sizeof(int32_t), int_cmp);
+        sel_count[bh] = kept;
+        sel_tokens[bh] = (int32_t)tokens;
+        if (margin) margin[bh] = (kept > 0 && kept < C) ? (double)it[kept - 1].s - (double)it[kept].s : INFINITY;
+        free(it);
+    }
+    return rc;
+}
+
+/*
+ * Sec. 2.1 Eq. (1) over the tokens T of the kept chunks, for query head j of
+ * kv head h = j / G:
+ *   z_t = scale * (q_j . K[h,t]),  p = softmax_T(z),  out_j = sum_T p_t V[h,t],
+ *   lse_j = log sum_T exp(z_t).
+ * Nothing kept: out_j = 0, lse_j = -inf.
+ * q: double [B,Hq,D]; K,V: [B,Hkv,N,D] of `dtype`; out: double [B,Hq,D];
+ * lse: double [B,Hq] (nullable).
+ */
+int orc_sparse_attention(int dtype, int B, int Hq, int Hkv, int N, int D, const double *q, const void *K,
+                         const void *V, const int32_t *chunk_off, int c_max, const int32_t *sel_idx,
+                         const int32_t *sel_count, int k_max, double scale, double *out, double *lse) {
+    int G = Hq / Hkv;
+    int bj;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (bj = 0; bj < B * Hq; ++bj) {
+        int b = bj / Hq, j = bj % Hq, h = j / G;
+        size_t bh = (size_t)b * Hkv + h;
+        const int32_t *off = chunk_off + (size_t)b * (c_max + 1);
+        const int32_t *row = sel_idx + bh * k_max;
+        const double *qj = q + (size_t)bj * D;
+        double *o = out + (size_t)bj * D;
+        int cnt = sel_count[bh];
+        long T = 0;
+        for (int i = 0; i < cnt; ++i) T += off[row[i] + 1] - off[row[i]];
+        for (int d = 0; d < D; ++d) o[d] = 0.0;
+        if (T == 0) {
+            if (lse) lse[bj] = -INFINITY;
+            continue;
+        }
+        double *z = (double *)malloc(sizeof(double) * (size_t)T);
+        long n = 0;
+        double m = -INFINITY;
+        for (int i = 0; i < cnt; ++i) {
+            for (int t = off[row[i]]; t < off[row[i] + 1]; ++t) {
+                size_t base = (bh * N + t) * D;
+                double dot = 0.0;
+                for (int d = 0; d < D; ++d) dot += qj[d] * widen(K, dtype, base + d);
+                z[n] = scale * dot;
+                if (z[n] > m) m = z[n];
+                ++n;
+            }
+        }
+        double denom = 0.0;
+        for (long i = 0; i < T; ++i) {
+            z[i] = exp(z[i] - m);
+            denom += z[i];
+        }
+        n = 0;
+        for (int i = 0; i < cnt; ++i) {
+            for (int t = off[row[i]]; t < off[row[i] + 1]; ++t) {
+                size_t base = (bh * N + t) * D;
+                double p = z[n++] / denom;
+                for (int d = 0; d < D; ++d) o[d] += p * widen(V, dtype, base + d);
+            }
+        }
+        if (lse) lse[bj] = m + log(denom);
+        free(z);
+    }
+    return 0;
+}
