@@ -1,0 +1,251 @@
+#!/usr/bin/env python3
+"""Benchmark of the chunked sparse-attention decode step on one MI355X.
+
+A "step" is one pass of the per-decode-step hot path -- chunk_score ->
+chunk_topk_select -> sparse_chunk_attention_decode -- over every resident
+layer of the workload, inputs already in HBM.  kv_chunk_abstract_build is the
+prefill-time call; it is timed on its own and reported under "abstract_build".
+
+Prints ONE JSON line.  `value` is the algorithmic KV traffic of the step
+(abstracts read + scores written and re-read + kept K/V rows read + q in + out
+written; never the dense cache the method avoids) divided by the wall time.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# resident layers per workload (every layer of c1/c2 fits; c3 keeps a spread of
+# eight layers x sixteen sequences = 64 GiB of K/V so that one pass touches far
+# more than any cache holds)
+RESIDENT = {
+    "c1": list(range(32)),
+    "c2": list(range(32)),
+    "c3": [0, 1, 2, 7, 15, 23, 30, 31],
+}
+ELEM = {"f32": 4, "f16": 2, "bf16": 2}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c3", choices=sorted(RESIDENT))
+    ap.add_argument("--layers", type=int, default=0, help="use only the first n resident layers (0 = all)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-reps", type=int, default=5, help="passes of the per-kernel timing loops")
+    return ap.parse_args()
+
+
+def algorithmic_bytes(layer, case, elem):
+    """Bytes one layer-step has to move, by part (see module docstring)."""
+    import torch
+    hkv, d, g = case.hkv, case.d, case.g
+    chunks = int(case.n_chunks.sum().item()) * hkv                  # (b,h,c) triples
+    kept_tokens = int(layer.sel_tokens.sum().item())                # over (b,h)
+    parts = {
+        "abstract": chunks * 2 * d * elem,
+        "score_wr_rd": chunks * 4 * 2,
+        "kv": kept_tokens * 2 * d * elem,
+        "q_out": case.batch * case.hq * d * (elem + 4),
+    }
+    parts["total"] = sum(parts.values())
+    parts["kept_tokens"] = kept_tokens
+    parts["chunks"] = chunks
+    return parts
+
+
+def time_calls(fn, reps, torch):
+    """Average wall time of fn() in ms over `reps` calls, HIP events on the current stream."""
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    fn()
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(reps):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) / reps
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build is a one-GPU path; run it with --gpus 1 "
+              "(sharding by (sequence, kv head) is described in DESIGN.md, not implemented)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import gen
+    import paper_2506_20187_amd as L
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    B = L.binding
+    cfg = gen.CONFIGS[args.workload]
+    layer_ids = RESIDENT[args.workload]
+    if args.layers > 0:
+        layer_ids = layer_ids[: args.layers]
+    elem = ELEM[cfg["dtype"]]
+
+    t0 = time.time()
+    layers, cases = [], []
+    for lid in layer_ids:
+        case = gen.make_case(args.workload, layer=lid, device="cuda")
+        lay = L.DecodeLayer(case.K, case.V, case.chunk_off, case.n_chunks, case.hq, case.k_max, case.max_chunks,
+                            case.token_budget)
+        layers.append(lay)
+        cases.append(case)
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+    print(f"# generated {len(layers)} resident layers of {args.workload} in {gen_s:.1f} s", file=sys.stderr, flush=True)
+
+    # ---- prefill-time abstract build, timed on its own -----------------------
+    def build_all():
+        for lay in layers:
+            lay.build_abstract()
+    ab_ms = time_calls(build_all, 2, torch)
+    k_bytes = sum(c.K.numel() * elem for c in cases)
+    ab_out_bytes = sum(int(c.n_chunks.sum().item()) * c.hkv * 2 * c.d * elem for c in cases)
+
+    # ---- the timed step ----------------------------------------------------------
+    def step():
+        for lay, case in zip(layers, cases):
+            lay.step(case.q)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t1
+    ms_per_step = wall * 1e3 / args.steps
+    us_per_layer = ms_per_step * 1e3 / len(layers)
+
+    parts = [algorithmic_bytes(lay, case, elem) for lay, case in zip(layers, cases)]
+    step_bytes = sum(p["total"] for p in parts)
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ---- per-kernel timing (HIP events on the launch stream) ----------------------
+    def only_score():
+        for lay, case in zip(layers, cases):
+            B.chunk_score(lay.shape, case.q, lay.abstract, lay.n_chunks, lay.score, None)
+
+    def only_select():
+        for lay in layers:
+            B.chunk_topk_select(lay.shape, lay.score, lay.chunk_off, lay.n_chunks, lay.max_chunks, lay.token_budget,
+                                lay.sel_idx, lay.sel_count, lay.sel_tokens)
+
+    def only_attention():
+        for lay, case in zip(layers, cases):
+            B.sparse_chunk_attention_decode(lay.shape, case.q, lay.K, lay.V, lay.chunk_off, lay.n_chunks, lay.sel_idx,
+                                            lay.sel_count, lay.scale, lay.out, lay.lse, lay.workspace)
+
+    nl = len(layers)
+    score_us = time_calls(only_score, args.kernel_reps, torch) * 1e3 / nl
+    select_us = time_calls(only_select, args.kernel_reps, torch) * 1e3 / nl
+    attn_us = time_calls(only_attention, args.kernel_reps, torch) * 1e3 / nl
+    kv_bytes = sum(p["kv"] + p["q_out"] for p in parts) / nl
+    abs_bytes = sum(p["abstract"] + p["score_wr_rd"] // 2 for p in parts) / nl
+    attn_gbs = kv_bytes / (attn_us * 1e-6) / 1e9
+    score_gbs = abs_bytes / (score_us * 1e-6) / 1e9
+
+    # ---- plain copy of known size: the "what does this box stream" reference ------
+    nbytes = 1 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    copy_ms = time_calls(lambda: B.leoam_copy_probe(dst, src, nbytes), 10, torch)
+    copy_gbs = 2 * nbytes / (copy_ms * 1e-3) / 1e9
+    del src, dst
+
+    out = {
+        "metric": "decode-step sparse-attn algorithmic KV GB/s (score+select+attention) at 128K ctx"
+        if cfg["n_ctx"] == 131072 else "decode-step sparse-attn algorithmic KV GB/s (score+select+attention)",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "us_per_layer_step": round(us_per_layer, 2),
+        "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 1),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg["dtype"],
+        "data": "synthetic",
+        "config": {
+            "workload": f"{args.workload}: batch {cfg['batch']}, {cfg['hq']} q / {cfg['hkv']} kv heads, head_dim 128, "
+                        f"ctx {cfg['n_ctx']}, {cfg['dtype']} K/V, token budget {cfg['token_budget']}",
+            "resident_layers": layer_ids,
+            "layer_steps_per_step": nl,
+            "bytes_per_layer_step": int(step_bytes / nl),
+            "kept_tokens_per_layer_step": int(sum(p["kept_tokens"] for p in parts) / nl),
+            "chunks_per_layer_step": int(sum(p["chunks"] for p in parts) / nl),
+        },
+        "kernels_us_per_layer_step": {"chunk_score": round(score_us, 2), "chunk_topk_select": round(select_us, 2),
+                                      "sparse_chunk_attention_decode": round(attn_us, 2)},
+        "roofline": {
+            "kernel": "sparse_attention_kernel (+ merge)",
+            "bound": "hbm",
+            "achieved": round(attn_gbs, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(attn_gbs / HBM_PEAK_GBS, 4),
+            "traffic": None,
+            "bytes_per_launch": int(kv_bytes),
+            "us_per_launch": round(attn_us, 2),
+        },
+        "roofline_chunk_score": {"bound": "hbm", "achieved": round(score_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                 "frac": round(score_gbs / HBM_PEAK_GBS, 4), "bytes_per_launch": int(abs_bytes),
+                                 "us_per_launch": round(score_us, 2)},
+        "abstract_build": {"GBps_of_K_streamed": round((k_bytes + ab_out_bytes) / (ab_ms * 1e-3) / 1e9, 1),
+                           "ms_per_layer": round(ab_ms / nl, 3)},
+        "copy_probe_GBps": round(copy_gbs, 1),
+    }
+
+    # ---- the oracle on the host cores, bounded sample --------------------------------
+    if not args.no_cpu_baseline:
+        import oracle
+        lay, case = layers[0], cases[0]
+        nseq = min(case.batch, 4)
+        Kc, Vc, qc = case.K[:nseq].cpu(), case.V[:nseq].cpu(), case.q[:nseq].cpu()
+        off, nc = case.chunk_off[:nseq].cpu(), case.n_chunks[:nseq].cpu()
+        ab = np.nan_to_num(oracle.abstract_build(Kc, off, nc))          # prefill-time, not timed
+        reps, cpu_s = 0, 0.0
+        while reps < 3 or (cpu_s < 10.0 and reps < 200):
+            t = time.perf_counter()
+            ub = oracle.chunk_score(qc, ab, nc)
+            sel, cnt, tok = oracle.topk_select(ub, off, nc, case.max_chunks, case.token_budget, case.k_max)
+            oracle.sparse_attention(qc, Kc, Vc, off, sel, cnt)
+            cpu_s += time.perf_counter() - t
+            reps += 1
+        sample_bytes = (int(nc.sum()) * case.hkv * (2 * case.d * elem + 8) + int(tok.sum()) * 2 * case.d * elem
+                        + nseq * case.hq * case.d * (elem + 4))
+        out["cpu_baseline"] = {
+            "value": round(sample_bytes / (cpu_s / reps) / 1e9, 3),
+            "unit": "GB/s",
+            "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"{nseq} of {case.batch} sequences of layer {case.layer}, score+select+attention, "
+                      f"{reps} repetitions, {cpu_s:.1f} s of CPU time",
+            "ms_per_layer_step_per_sequence": round(cpu_s / reps / nseq * 1e3, 3),
+        }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,154 @@
+/*
+ * leoam.h - C ABI of the MI355X (gfx950) chunked sparse-attention decode path.
+ *
+ * One decode step of one transformer layer, following arXiv 2506.20187
+ * (LeoAM), with every KV tier held in one GPU's HBM:
+ *
+ *   kv_chunk_abstract_build        Sec. 4.3: per chunk, the element-wise maximum
+ *                                  and minimum key vectors (the "KV abstract").
+ *   chunk_score                    Sec. 4.1 / 4.3: chunk importance = upper bound
+ *                                  of q.k over the chunk, from abstract + query.
+ *   chunk_topk_select              Sec. 4.2 / 6.1: order chunks by upper bound,
+ *                                  keep the front of the list under a budget.
+ *   sparse_chunk_attention_decode  Sec. 2.1 Eq. (1) over the kept chunks only.
+ *
+ * Conventions (all entry points)
+ *   - Every pointer except `const leoam_shape*` is a DEVICE pointer owned by the
+ *     caller.  The library allocates nothing and keeps no state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
+ *     enqueue kernels and return; nothing synchronises.  Outputs are valid once
+ *     the stream reaches that point.
+ *   - Return value: LEOAM_OK or a negative leoam_status.  Faults that the host
+ *     can see (null pointer, unsupported shape or dtype, workspace too small)
+ *     are reported before anything is enqueued.  Faults in device-resident data
+ *     (boundaries that do not tile the context, chunk ids out of range) cannot be
+ *     seen without a sync: kernels clamp such values so that no access leaves
+ *     the buffers, and leoam_validate_boundaries() is there for checking.
+ *   - Layouts are row-major and contiguous:
+ *       K, V       [batch, n_kv_heads, n_ctx, head_dim]   kv_dtype
+ *       q          [batch, n_q_heads, head_dim]            kv_dtype
+ *       abstract   [batch, n_kv_heads, c_max, 2, head_dim] abstract_dtype
+ *                  ([..,0,:] = kmax, [..,1,:] = kmin)
+ *       chunk_off  [batch, c_max + 1] int32, row b = 0 = off[0] < off[1] < ... <
+ *                  off[n_chunks[b]] = n_ctx; entries past that are ignored
+ *       n_chunks   [batch] int32, 0 <= n_chunks[b] <= c_max
+ *       score      [batch, n_kv_heads, c_max] float
+ *       sel_idx    [batch, n_kv_heads, k_max] int32
+ *       out        [batch, n_q_heads, head_dim] float
+ *     Chunk boundaries belong to a (sequence, layer) and are shared by its
+ *     heads; abstracts, scores and selections are per (sequence, kv head).
+ *     Query head j belongs to kv head j / (n_q_heads / n_kv_heads).
+ *   - Same inputs give bit-identical outputs (no floating-point atomics).
+ */
+#ifndef LEOAM_H
+#define LEOAM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LEOAM_OK = 0,
+    LEOAM_E_INVALID_ARG = -1,    /* null pointer, non-positive size, Hq % Hkv != 0 */
+    LEOAM_E_BAD_BOUNDARIES = -2, /* only from leoam_validate_boundaries */
+    LEOAM_E_UNSUPPORTED = -3,    /* head_dim != 128, group size not in {1,2,4,8}, dtype combination, c_max > 16384 */
+    LEOAM_E_WORKSPACE = -4,      /* workspace missing or too small */
+    LEOAM_E_HIP = -6             /* a HIP call or launch failed */
+} leoam_status;
+
+typedef enum { LEOAM_F32 = 0, LEOAM_F16 = 1, LEOAM_BF16 = 2 } leoam_dtype;
+
+typedef struct {
+    int32_t batch;          /* B  >= 1 */
+    int32_t n_q_heads;      /* Hq, multiple of n_kv_heads, Hq/Hkv in {1,2,4,8} */
+    int32_t n_kv_heads;     /* Hkv >= 1 */
+    int32_t head_dim;       /* D, must be 128 */
+    int32_t n_ctx;          /* N, tokens per sequence (same for the whole batch) */
+    int32_t c_max;          /* row stride of per-chunk arrays, 1..16384 */
+    int32_t k_max;          /* row stride of sel_idx, 1..c_max; also caps the kept count */
+    int32_t kv_dtype;       /* leoam_dtype of K, V and q */
+    int32_t abstract_dtype; /* must equal kv_dtype */
+} leoam_shape;
+
+/*
+ * Sec. 4.3 "KV abstract extraction".  For every (b, h, c < n_chunks[b]):
+ *   abstract[b,h,c,0,d] = max over off[c] <= t < off[c+1] of K[b,h,t,d]
+ *   abstract[b,h,c,1,d] = min over the same tokens.
+ * Exact (a maximum of stored values); the sign of a zero result is unspecified.
+ * Rows of chunks >= n_chunks[b] are not written.  Token indices are clamped to
+ * [0, n_ctx]; an empty chunk gives (-inf, +inf).
+ */
+int kv_chunk_abstract_build(const leoam_shape* shape, const void* K, const int32_t* chunk_off,
+                            const int32_t* n_chunks, void* abstract, void* stream);
+
+/*
+ * Sec. 4.1 (chunk importance is the upper bound of the token importance in the
+ * chunk) and Sec. 4.3 (bounds from the abstract and the current query).  For
+ * every query head j of kv head h and every chunk c < n_chunks[b]:
+ *   U_j[c] = sum_d max(q_j[d]*kmax[d], q_j[d]*kmin[d])
+ *   L_j[c] = sum_d min(q_j[d]*kmax[d], q_j[d]*kmin[d])
+ *   score_ub[b,h,c] = max_j U_j[c],   score_lb[b,h,c] = min_j L_j[c]
+ * so score_lb <= q_j.k_t <= score_ub for every token t of the chunk and every
+ * head j of the group.  The sums are accumulated in double over exact products
+ * and rounded once to float; -0 is stored as +0.  Entries c >= n_chunks[b] are
+ * set to -inf (ub) and +inf (lb).  score_lb may be NULL.
+ */
+int chunk_score(const leoam_shape* shape, const void* q, const void* abstract, const int32_t* n_chunks,
+                float* score_ub, float* score_lb, void* stream);
+
+/*
+ * Sec. 4.2 (priority queue ordered by upper bound, read from the front) and
+ * Sec. 6.1 (only the most important share of the cache is loaded).  Per (b,h):
+ * order chunks by (score descending, chunk index ascending); keep the longest
+ * front of that list whose length is <= max_chunks and <= k_max and whose token
+ * total is <= token_budget; the walk stops at the first chunk that does not fit.
+ * max_chunks <= 0 and token_budget <= 0 mean "no limit".  Scores must be finite
+ * for c < n_chunks[b] (+0 and -0 compare equal).
+ *   sel_idx[b,h,0..count)  kept chunk ids in ascending order, rest of row = -1
+ *   sel_count[b,h]         number kept
+ *   sel_tokens[b,h]        their token total (nullable)
+ * workspace is not used by this call (pass NULL, 0).
+ */
+int chunk_topk_select(const leoam_shape* shape, const float* score_ub, const int32_t* chunk_off,
+                      const int32_t* n_chunks, int32_t max_chunks, int32_t token_budget, int32_t* sel_idx,
+                      int32_t* sel_count, int32_t* sel_tokens, void* workspace, size_t workspace_bytes,
+                      void* stream);
+
+/*
+ * Sec. 2.1 Eq. (1) restricted to the tokens T of the kept chunks.  For query
+ * head j of kv head h:  z_t = softmax_scale * (q_j . K[b,h,t]),
+ *   out[b,j,:] = sum_T softmax_T(z)_t * V[b,h,t,:],  lse[b,j] = log sum_T exp(z_t).
+ * Nothing kept: out = 0, lse = -inf.  lse may be NULL.  Ids in sel_idx outside
+ * [0, n_chunks) contribute no tokens.  The kept tokens are split across
+ * workgroups; the number of splits is the largest the workspace allows, up to
+ * what leoam_workspace_bytes() asks for, so a workspace of that size gives the
+ * intended launch.  Partial results are combined in a fixed order.
+ */
+int sparse_chunk_attention_decode(const leoam_shape* shape, const void* q, const void* K, const void* V,
+                                  const int32_t* chunk_off, const int32_t* n_chunks, const int32_t* sel_idx,
+                                  const int32_t* sel_count, float softmax_scale, float* out, float* lse,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace sparse_chunk_attention_decode wants when at most
+ * `max_tokens` tokens are kept per (b,h) (<= 0: n_ctx).  0 on a bad shape. */
+size_t leoam_workspace_bytes(const leoam_shape* shape, int32_t max_tokens);
+
+/* Debug helper: copies the boundary lists to the host (synchronises `stream`)
+ * and returns LEOAM_E_BAD_BOUNDARIES unless every row tiles [0, n_ctx). */
+int leoam_validate_boundaries(const leoam_shape* shape, const int32_t* chunk_off, const int32_t* n_chunks,
+                              void* stream);
+
+/* Plain device copy of `bytes` bytes (multiple of 16, 16-byte aligned): the
+ * known-size kernel that hardware byte counters are scaled against. */
+int leoam_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
+
+const char* leoam_status_string(int status);
+int leoam_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LEOAM_H */

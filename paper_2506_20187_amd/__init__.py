@@ -1,0 +1,13 @@
+"""MI355X-native chunked sparse-attention decode path (LeoAM hot path).
+
+The work is done by libleoam.so (hand-written HIP for gfx950, C ABI declared in
+include/leoam.h).  `binding` exposes the entry points under the same names;
+`DecodeLayer` is a small convenience holder of the per-layer buffers.
+"""
+from . import binding  # noqa: F401  (raises if the library is not built)
+from .binding import (  # noqa: F401
+    LeoamError, Shape, make_shape, kv_chunk_abstract_build, chunk_score, chunk_topk_select,
+    sparse_chunk_attention_decode, leoam_workspace_bytes, leoam_validate_boundaries, leoam_copy_probe,
+    status_string, version, default_scale,
+)
+from .layer import DecodeLayer  # noqa: F401

@@ -1,0 +1,140 @@
+"""Thin ctypes binding of libleoam.so: same names as the C entry points.
+
+Argument marshalling only.  Tensors are torch CUDA tensors (device memory and
+the current HIP stream come from torch; nothing else does).  If the library
+has not been built, importing this module raises: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libleoam.so")
+
+F32, F16, BF16 = 0, 1, 2
+_DTYPE_TAG = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
+
+OK = 0
+E_INVALID_ARG, E_BAD_BOUNDARIES, E_UNSUPPORTED, E_WORKSPACE, E_HIP = -1, -2, -3, -4, -6
+
+
+class LeoamError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+class Shape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("batch", "n_q_heads", "n_kv_heads", "head_dim", "n_ctx", "c_max",
+                                                "k_max", "kv_dtype", "abstract_dtype")]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(or python paper_2506_20187_amd/build.py) first")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    sp = ctypes.POINTER(Shape)
+    lib.kv_chunk_abstract_build.argtypes = [sp, vp, vp, vp, vp, vp]
+    lib.chunk_score.argtypes = [sp, vp, vp, vp, vp, vp, vp]
+    lib.chunk_topk_select.argtypes = [sp, vp, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.sparse_chunk_attention_decode.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, sz, vp]
+    lib.leoam_workspace_bytes.argtypes = [sp, i32]
+    lib.leoam_workspace_bytes.restype = sz
+    lib.leoam_validate_boundaries.argtypes = [sp, vp, vp, vp]
+    lib.leoam_copy_probe.argtypes = [vp, vp, sz, vp]
+    lib.leoam_status_string.argtypes = [ctypes.c_int]
+    lib.leoam_status_string.restype = ctypes.c_char_p
+    lib.leoam_version.restype = ctypes.c_int
+    for name in ("kv_chunk_abstract_build", "chunk_score", "chunk_topk_select", "sparse_chunk_attention_decode",
+                 "leoam_validate_boundaries", "leoam_copy_probe"):
+        getattr(lib, name).restype = ctypes.c_int
+    return lib
+
+
+_lib = _load()
+
+EXPORTS = ("kv_chunk_abstract_build", "chunk_score", "chunk_topk_select", "sparse_chunk_attention_decode",
+           "leoam_workspace_bytes", "leoam_validate_boundaries", "leoam_copy_probe", "leoam_status_string",
+           "leoam_version")
+
+
+def status_string(status: int) -> str:
+    return _lib.leoam_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(_lib.leoam_version())
+
+
+def make_shape(batch, n_q_heads, n_kv_heads, head_dim, n_ctx, c_max, k_max, dtype) -> Shape:
+    tag = _DTYPE_TAG[dtype] if isinstance(dtype, torch.dtype) else int(dtype)
+    return Shape(batch, n_q_heads, n_kv_heads, head_dim, n_ctx, c_max, k_max, tag, tag)
+
+
+def _p(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous CUDA tensor")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise LeoamError(status, where)
+
+
+def kv_chunk_abstract_build(shape: Shape, K, chunk_off, n_chunks, abstract, stream=None) -> None:
+    _check(_lib.kv_chunk_abstract_build(ctypes.byref(shape), _p(K), _p(chunk_off), _p(n_chunks), _p(abstract),
+                                        _stream(stream)), "kv_chunk_abstract_build")
+
+
+def chunk_score(shape: Shape, q, abstract, n_chunks, score_ub, score_lb=None, stream=None) -> None:
+    _check(_lib.chunk_score(ctypes.byref(shape), _p(q), _p(abstract), _p(n_chunks), _p(score_ub), _p(score_lb),
+                            _stream(stream)), "chunk_score")
+
+
+def chunk_topk_select(shape: Shape, score_ub, chunk_off, n_chunks, max_chunks: int, token_budget: int, sel_idx,
+                      sel_count, sel_tokens=None, workspace=None, stream=None) -> None:
+    nbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(_lib.chunk_topk_select(ctypes.byref(shape), _p(score_ub), _p(chunk_off), _p(n_chunks), int(max_chunks),
+                                  int(token_budget), _p(sel_idx), _p(sel_count), _p(sel_tokens), _p(workspace),
+                                  nbytes, _stream(stream)), "chunk_topk_select")
+
+
+def sparse_chunk_attention_decode(shape: Shape, q, K, V, chunk_off, n_chunks, sel_idx, sel_count, softmax_scale,
+                                  out, lse, workspace, stream=None) -> None:
+    nbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(_lib.sparse_chunk_attention_decode(ctypes.byref(shape), _p(q), _p(K), _p(V), _p(chunk_off), _p(n_chunks),
+                                              _p(sel_idx), _p(sel_count), ctypes.c_float(softmax_scale), _p(out),
+                                              _p(lse), _p(workspace), nbytes, _stream(stream)),
+           "sparse_chunk_attention_decode")
+
+
+def leoam_workspace_bytes(shape: Shape, max_tokens: int) -> int:
+    return int(_lib.leoam_workspace_bytes(ctypes.byref(shape), int(max_tokens)))
+
+
+def leoam_validate_boundaries(shape: Shape, chunk_off, n_chunks, stream=None) -> int:
+    return int(_lib.leoam_validate_boundaries(ctypes.byref(shape), _p(chunk_off), _p(n_chunks), _stream(stream)))
+
+
+def leoam_copy_probe(dst, src, nbytes: int, stream=None) -> None:
+    _check(_lib.leoam_copy_probe(_p(dst), _p(src), int(nbytes), _stream(stream)), "leoam_copy_probe")
+
+
+def default_scale(head_dim: int) -> float:
+    return 1.0 / math.sqrt(head_dim)

@@ -1,0 +1,145 @@
+// C ABI of the library (include/leoam.h): argument checks, then kernel launches
+// on the caller's stream.  Nothing here allocates or synchronises, except the
+// debug helper leoam_validate_boundaries.
+#include <vector>
+
+#include "leoam_dev.h"
+
+namespace leoam {
+hipError_t abstract_build_dispatch(const leoam_shape*, const void*, const int32_t*, const int32_t*, void*, hipStream_t);
+hipError_t chunk_score_dispatch(const leoam_shape*, const void*, const void*, const int32_t*, float*, float*, hipStream_t);
+hipError_t topk_select_dispatch(const leoam_shape*, const float*, const int32_t*, const int32_t*, int, int, int32_t*,
+                                int32_t*, int32_t*, hipStream_t);
+hipError_t attention_dispatch(const leoam_shape*, const void*, const void*, const void*, const int32_t*, const int32_t*,
+                              const int32_t*, const int32_t*, float, float*, float*, void*, size_t, hipStream_t);
+size_t attention_workspace_bytes(const leoam_shape*, int);
+int attention_max_sel();
+
+__global__ void copy_probe_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = src[i];
+}
+
+static int check_shape(const leoam_shape* s) {
+    if (!s) return LEOAM_E_INVALID_ARG;
+    if (s->batch < 1 || s->n_q_heads < 1 || s->n_kv_heads < 1 || s->n_ctx < 1 || s->c_max < 1 || s->k_max < 1)
+        return LEOAM_E_INVALID_ARG;
+    if (s->n_q_heads % s->n_kv_heads) return LEOAM_E_INVALID_ARG;
+    if (s->k_max > s->c_max) return LEOAM_E_INVALID_ARG;
+    if (s->head_dim != LEOAM_D) return LEOAM_E_UNSUPPORTED;
+    const int g = s->n_q_heads / s->n_kv_heads;
+    if (g != 1 && g != 2 && g != 4 && g != 8) return LEOAM_E_UNSUPPORTED;
+    if (s->kv_dtype != LEOAM_F32 && s->kv_dtype != LEOAM_F16 && s->kv_dtype != LEOAM_BF16) return LEOAM_E_UNSUPPORTED;
+    if (s->abstract_dtype != s->kv_dtype) return LEOAM_E_UNSUPPORTED;
+    if (s->c_max > 16384) return LEOAM_E_UNSUPPORTED;
+    if ((long long)s->batch * s->n_kv_heads > 65535 * 8) return LEOAM_E_UNSUPPORTED;
+    if (s->n_kv_heads > 65535 || s->batch > 65535) return LEOAM_E_UNSUPPORTED;
+    return LEOAM_OK;
+}
+
+static inline int from_hip(hipError_t e) { return e == hipSuccess ? LEOAM_OK : LEOAM_E_HIP; }
+}  // namespace leoam
+
+using namespace leoam;
+
+extern "C" {
+
+int kv_chunk_abstract_build(const leoam_shape* shape, const void* K, const int32_t* chunk_off,
+                            const int32_t* n_chunks, void* abstract, void* stream) {
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!K || !chunk_off || !n_chunks || !abstract) return LEOAM_E_INVALID_ARG;
+    return from_hip(abstract_build_dispatch(shape, K, chunk_off, n_chunks, abstract, (hipStream_t)stream));
+}
+
+int chunk_score(const leoam_shape* shape, const void* q, const void* abstract, const int32_t* n_chunks,
+                float* score_ub, float* score_lb, void* stream) {
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!q || !abstract || !n_chunks || !score_ub) return LEOAM_E_INVALID_ARG;
+    return from_hip(chunk_score_dispatch(shape, q, abstract, n_chunks, score_ub, score_lb, (hipStream_t)stream));
+}
+
+int chunk_topk_select(const leoam_shape* shape, const float* score_ub, const int32_t* chunk_off,
+                      const int32_t* n_chunks, int32_t max_chunks, int32_t token_budget, int32_t* sel_idx,
+                      int32_t* sel_count, int32_t* sel_tokens, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+    (void)workspace;
+    (void)workspace_bytes;
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!score_ub || !chunk_off || !n_chunks || !sel_idx || !sel_count) return LEOAM_E_INVALID_ARG;
+    return from_hip(topk_select_dispatch(shape, score_ub, chunk_off, n_chunks, max_chunks, token_budget, sel_idx,
+                                         sel_count, sel_tokens, (hipStream_t)stream));
+}
+
+int sparse_chunk_attention_decode(const leoam_shape* shape, const void* q, const void* K, const void* V,
+                                  const int32_t* chunk_off, const int32_t* n_chunks, const int32_t* sel_idx,
+                                  const int32_t* sel_count, float softmax_scale, float* out, float* lse,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!q || !K || !V || !chunk_off || !n_chunks || !sel_idx || !sel_count || !out) return LEOAM_E_INVALID_ARG;
+    if (shape->k_max > attention_max_sel()) return LEOAM_E_UNSUPPORTED;
+    const size_t one = (size_t)shape->batch * shape->n_q_heads * (LEOAM_D + 2) * sizeof(float);
+    if (!workspace || workspace_bytes < one) return LEOAM_E_WORKSPACE;
+    if (((uintptr_t)workspace & 15u) != 0) return LEOAM_E_WORKSPACE;
+    return from_hip(attention_dispatch(shape, q, K, V, chunk_off, n_chunks, sel_idx, sel_count, softmax_scale, out, lse,
+                                       workspace, workspace_bytes, (hipStream_t)stream));
+}
+
+size_t leoam_workspace_bytes(const leoam_shape* shape, int32_t max_tokens) {
+    if (check_shape(shape)) return 0;
+    return attention_workspace_bytes(shape, max_tokens);
+}
+
+int leoam_validate_boundaries(const leoam_shape* shape, const int32_t* chunk_off, const int32_t* n_chunks,
+                              void* stream) {
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!chunk_off || !n_chunks) return LEOAM_E_INVALID_ARG;
+    const size_t row = (size_t)shape->c_max + 1;
+    std::vector<int32_t> off(row * shape->batch), nc(shape->batch);
+    hipStream_t st = (hipStream_t)stream;
+    if (hipMemcpyAsync(off.data(), chunk_off, off.size() * sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return LEOAM_E_HIP;
+    if (hipMemcpyAsync(nc.data(), n_chunks, nc.size() * sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return LEOAM_E_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return LEOAM_E_HIP;
+    for (int b = 0; b < shape->batch; ++b) {
+        const int32_t* o = off.data() + row * b;
+        const int n = nc[b];
+        if (n < 1 || n > shape->c_max) return LEOAM_E_BAD_BOUNDARIES;
+        if (o[0] != 0 || o[n] != shape->n_ctx) return LEOAM_E_BAD_BOUNDARIES;
+        for (int c = 0; c < n; ++c)
+            if (o[c + 1] <= o[c]) return LEOAM_E_BAD_BOUNDARIES;
+    }
+    return LEOAM_OK;
+}
+
+int leoam_copy_probe(void* dst, const void* src, size_t bytes, void* stream) {
+    if (!dst || !src || (bytes & 15u) || ((uintptr_t)dst & 15u) || ((uintptr_t)src & 15u)) return LEOAM_E_INVALID_ARG;
+    if (bytes == 0) return LEOAM_OK;
+    const size_t n16 = bytes / 16;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    hipLaunchKernelGGL(copy_probe_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (uint4*)dst,
+                       (const uint4*)src, n16);
+    return from_hip(hipGetLastError());
+}
+
+const char* leoam_status_string(int status) {
+    switch (status) {
+    case LEOAM_OK: return "ok";
+    case LEOAM_E_INVALID_ARG: return "invalid argument";
+    case LEOAM_E_BAD_BOUNDARIES: return "chunk boundaries do not tile the context";
+    case LEOAM_E_UNSUPPORTED: return "unsupported shape or dtype";
+    case LEOAM_E_WORKSPACE: return "workspace missing, misaligned or too small";
+    case LEOAM_E_HIP: return "HIP error";
+    default: return "unknown status";
+    }
+}
+
+int leoam_version(void) { return 100; }
+
+}  // extern "C"

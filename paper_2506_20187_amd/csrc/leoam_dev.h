@@ -1,0 +1,105 @@
+// Device-side helpers shared by the gfx950 kernels: 16-byte row loads, storage
+// type unpacking, wave-level reductions.  64-wide wavefronts throughout.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/leoam.h"
+
+#define LEOAM_D 128
+#define LEOAM_WAVE 64
+
+namespace leoam {
+
+// ---- storage types ---------------------------------------------------------
+// A lane always moves 16 bytes of a row: EPL elements.
+struct F32 { static constexpr int kBytes = 4; static constexpr int kEpl = 4; static constexpr int kTag = LEOAM_F32; };
+struct F16 { static constexpr int kBytes = 2; static constexpr int kEpl = 8; static constexpr int kTag = LEOAM_F16; };
+struct BF16 { static constexpr int kBytes = 2; static constexpr int kEpl = 8; static constexpr int kTag = LEOAM_BF16; };
+
+template <typename T> struct Row {
+    static constexpr int kLanesPerRow = LEOAM_D / T::kEpl;            // 32 (fp32) or 16
+    static constexpr int kRowsPerLoad = LEOAM_WAVE / kLanesPerRow;    // 2 or 4
+    static constexpr int kRowBytes = LEOAM_D * T::kBytes;
+};
+
+__device__ __forceinline__ float bits_to_float(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t float_to_bits(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+// unpack the 16 bytes a lane holds into floats (exact widening)
+template <typename T> __device__ __forceinline__ void unpack(const uint4& v, float* x);
+
+template <> __device__ __forceinline__ void unpack<F32>(const uint4& v, float* x) {
+    x[0] = bits_to_float(v.x); x[1] = bits_to_float(v.y); x[2] = bits_to_float(v.z); x[3] = bits_to_float(v.w);
+}
+template <> __device__ __forceinline__ void unpack<BF16>(const uint4& v, float* x) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        x[2 * i] = bits_to_float(w[i] << 16);
+        x[2 * i + 1] = bits_to_float(w[i] & 0xffff0000u);
+    }
+}
+template <> __device__ __forceinline__ void unpack<F16>(const uint4& v, float* x) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        x[2 * i] = (float)__builtin_bit_cast(_Float16, (uint16_t)(w[i] & 0xffffu));
+        x[2 * i + 1] = (float)__builtin_bit_cast(_Float16, (uint16_t)(w[i] >> 16));
+    }
+}
+
+// pack floats that are exactly representable in T back into 16 bytes
+template <typename T> __device__ __forceinline__ uint4 pack(const float* x);
+template <> __device__ __forceinline__ uint4 pack<F32>(const float* x) {
+    return make_uint4(float_to_bits(x[0]), float_to_bits(x[1]), float_to_bits(x[2]), float_to_bits(x[3]));
+}
+template <> __device__ __forceinline__ uint4 pack<BF16>(const float* x) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = (float_to_bits(x[2 * i]) >> 16) | (float_to_bits(x[2 * i + 1]) & 0xffff0000u);
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+template <> __device__ __forceinline__ uint4 pack<F16>(const float* x) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        uint32_t lo = __builtin_bit_cast(uint16_t, (_Float16)x[2 * i]);
+        uint32_t hi = __builtin_bit_cast(uint16_t, (_Float16)x[2 * i + 1]);
+        w[i] = lo | (hi << 16);
+    }
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+__device__ __forceinline__ uint4 load16(const void* base, size_t byte_off) {
+    return *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(base) + byte_off);
+}
+__device__ __forceinline__ void store16(void* base, size_t byte_off, const uint4& v) {
+    *reinterpret_cast<uint4*>(reinterpret_cast<char*>(base) + byte_off) = v;
+}
+
+// ---- wave-level helpers ------------------------------------------------------
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (LEOAM_WAVE - 1)); }
+
+__device__ __forceinline__ float shfl_xor_f(float v, int mask) { return __shfl_xor(v, mask, LEOAM_WAVE); }
+__device__ __forceinline__ double shfl_xor_d(double v, int mask) { return __shfl_xor(v, mask, LEOAM_WAVE); }
+
+// DPP lane exchanges inside a 16-lane row.  Applied to values that are already
+// uniform inside the smaller groups these turn into xor-butterfly steps:
+//   0xB1 quad_perm [1,0,3,2]  (xor 1)        0x4E quad_perm [2,3,0,1]  (xor 2)
+//   0x141 row_half_mirror (lane i <-> 7-i)   0x140 row_mirror (lane i <-> 15-i)
+template <int kCtrl> __device__ __forceinline__ float dpp_f(float v) {
+    int x = __builtin_bit_cast(int, v);
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(x, x, kCtrl, 0xf, 0xf, false));
+}
+
+// sum over the 16 lanes of a DPP row; every lane of the row gets the total
+__device__ __forceinline__ float row16_sum(float v) {
+    v += dpp_f<0xB1>(v);
+    v += dpp_f<0x4E>(v);
+    v += dpp_f<0x141>(v);
+    v += dpp_f<0x140>(v);
+    return v;
+}
+
+}  // namespace leoam

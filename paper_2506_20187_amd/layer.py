@@ -1,0 +1,43 @@
+"""Buffer holder for one layer's decode step (allocation + call order only)."""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+
+
+class DecodeLayer:
+    """Owns abstract / score / selection / output / workspace buffers of one
+    layer and calls the four entry points in the paper's order.  All arithmetic
+    happens inside libleoam.so."""
+
+    def __init__(self, K: torch.Tensor, V: torch.Tensor, chunk_off: torch.Tensor, n_chunks: torch.Tensor,
+                 n_q_heads: int, k_max: int, max_chunks: int, token_budget: int):
+        batch, hkv, n_ctx, d = K.shape
+        self.K, self.V, self.chunk_off, self.n_chunks = K, V, chunk_off, n_chunks
+        self.max_chunks, self.token_budget = int(max_chunks), int(token_budget)
+        c_max = chunk_off.shape[1] - 1
+        self.shape = B.make_shape(batch, n_q_heads, hkv, d, n_ctx, c_max, k_max, K.dtype)
+        dev = K.device
+        self.abstract = torch.empty(batch, hkv, c_max, 2, d, dtype=K.dtype, device=dev)
+        self.score = torch.empty(batch, hkv, c_max, dtype=torch.float32, device=dev)
+        self.sel_idx = torch.empty(batch, hkv, k_max, dtype=torch.int32, device=dev)
+        self.sel_count = torch.empty(batch, hkv, dtype=torch.int32, device=dev)
+        self.sel_tokens = torch.empty(batch, hkv, dtype=torch.int32, device=dev)
+        self.out = torch.empty(batch, n_q_heads, d, dtype=torch.float32, device=dev)
+        self.lse = torch.empty(batch, n_q_heads, dtype=torch.float32, device=dev)
+        nbytes = B.leoam_workspace_bytes(self.shape, token_budget)
+        self.workspace = torch.empty(max(16, nbytes), dtype=torch.uint8, device=dev)
+        self.scale = B.default_scale(d)
+
+    def build_abstract(self, stream=None) -> None:
+        B.kv_chunk_abstract_build(self.shape, self.K, self.chunk_off, self.n_chunks, self.abstract, stream)
+
+    def step(self, q: torch.Tensor, stream=None) -> torch.Tensor:
+        s = self.shape
+        B.chunk_score(s, q, self.abstract, self.n_chunks, self.score, None, stream)
+        B.chunk_topk_select(s, self.score, self.chunk_off, self.n_chunks, self.max_chunks, self.token_budget,
+                            self.sel_idx, self.sel_count, self.sel_tokens, None, stream)
+        B.sparse_chunk_attention_decode(s, q, self.K, self.V, self.chunk_off, self.n_chunks, self.sel_idx,
+                                        self.sel_count, self.scale, self.out, self.lse, self.workspace, stream)
+        return self.out

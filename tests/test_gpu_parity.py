@@ -1,0 +1,332 @@
+"""GPU parity: libleoam.so (through its C ABI) against the float64 CPU oracle,
+element by element, on the same seeded inputs.
+
+Bars: abstracts, scores, kept chunk ids / counts / token totals bit-exact;
+attention outputs within 1e-5 (fp32) and 2e-3 (fp16, bf16) max-abs.
+"""
+import numpy as np
+import pytest
+import torch
+
+import gen
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "f16": 2e-3, "bf16": 2e-3}
+TDT = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+
+@pytest.fixture(scope="module")
+def L():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2506_20187_amd as lib
+    return lib
+
+
+def dev(x):
+    return x.cuda().contiguous() if isinstance(x, torch.Tensor) else torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def host_f64(t):
+    return t.detach().cpu().to(torch.float64).numpy()
+
+
+def random_boundaries(rng, B, N, sizes):
+    offs = []
+    for _ in range(B):
+        off = [0]
+        while off[-1] < N:
+            off.append(min(N, off[-1] + int(rng.choice(sizes))))
+        offs.append(np.asarray(off, dtype=np.int32))
+    return gen.pack_boundaries(offs, N)
+
+
+def gpu_abstract(L, K, packed, counts):
+    B, Hkv, N, D = K.shape
+    c_max = packed.shape[1] - 1
+    shape = L.make_shape(B, Hkv, Hkv, D, N, c_max, 1, K.dtype)
+    ab = torch.full((B, Hkv, c_max, 2, D), float("nan"), dtype=K.dtype, device="cuda")
+    L.kv_chunk_abstract_build(shape, dev(K), dev(packed), dev(counts), ab)
+    torch.cuda.synchronize()
+    return ab
+
+
+# ---------------------------------------------------------------------------
+# a1 abstract
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_abstract_exact(L, oracle, dtype):
+    rng = np.random.default_rng(10)
+    B, Hkv, N, D = 2, 3, 1037, 128
+    K = torch.from_numpy(rng.standard_normal((B, Hkv, N, D)).astype(np.float32)).to(TDT[dtype])
+    packed, counts, c_max = random_boundaries(rng, B, N, (1, 2, 3, 7, 16, 33, 70))
+    want = oracle.abstract_build(K, packed, counts)
+    got = host_f64(gpu_abstract(L, K, packed, counts))
+    for b in range(B):
+        n = counts[b]
+        assert np.array_equal(got[b, :, :n], want[b, :, :n])
+        assert np.isnan(got[b, :, n:]).all()        # rows of absent chunks are not written
+
+
+# ---------------------------------------------------------------------------
+# a2 score
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,G", [("f32", 1), ("f32", 4), ("f16", 1), ("f16", 2), ("bf16", 4), ("bf16", 8)])
+def test_score_exact(L, oracle, dtype, G):
+    rng = np.random.default_rng(20 + G)
+    B, Hkv, N, D = 2, 2, 3000, 128
+    K = torch.from_numpy(rng.standard_normal((B, Hkv, N, D)).astype(np.float32)).to(TDT[dtype])
+    q = torch.from_numpy(rng.standard_normal((B, Hkv * G, D)).astype(np.float32)).to(TDT[dtype])
+    packed, counts, c_max = random_boundaries(rng, B, N, (1, 4, 9, 16, 25))
+    ab64 = oracle.abstract_build(K, packed, counts)
+    ub, lb = oracle.chunk_score(q, np.nan_to_num(ab64), counts, want_lower=True)
+    ab = torch.from_numpy(np.nan_to_num(ab64)).to(TDT[dtype])           # exact: abstract values are key values
+    shape = L.make_shape(B, Hkv * G, Hkv, D, N, c_max, 1, TDT[dtype])
+    s_ub = torch.empty(B, Hkv, c_max, dtype=torch.float32, device="cuda")
+    s_lb = torch.empty_like(s_ub)
+    L.chunk_score(shape, dev(q), dev(ab), dev(counts), s_ub, s_lb)
+    s_only = torch.empty_like(s_ub)
+    L.chunk_score(shape, dev(q), dev(ab), dev(counts), s_only, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(s_ub.cpu().numpy(), ub)
+    assert np.array_equal(s_lb.cpu().numpy(), lb)
+    assert np.array_equal(s_only.cpu().numpy(), ub)
+
+
+# ---------------------------------------------------------------------------
+# a3 select
+# ---------------------------------------------------------------------------
+def gpu_select(L, score, packed, counts, max_chunks, budget, k_max, N):
+    B, Hkv, c_max = score.shape
+    shape = L.make_shape(B, Hkv, Hkv, 128, N, c_max, k_max, torch.float32)
+    sel = torch.full((B, Hkv, k_max), -7, dtype=torch.int32, device="cuda")
+    cnt = torch.full((B, Hkv), -7, dtype=torch.int32, device="cuda")
+    tok = torch.full((B, Hkv), -7, dtype=torch.int32, device="cuda")
+    L.chunk_topk_select(shape, dev(score), dev(packed), dev(counts), max_chunks, budget, sel, cnt, tok)
+    torch.cuda.synchronize()
+    return sel.cpu().numpy(), cnt.cpu().numpy(), tok.cpu().numpy()
+
+
+@pytest.mark.parametrize("C", [5, 130, 1024, 1500, 3000, 8192, 16384])
+def test_select_exact(L, oracle, C):
+    rng = np.random.default_rng(C)
+    B, Hkv = 2, 3
+    offs = []
+    for b in range(B):
+        n = C if b == 0 else max(1, C - int(rng.integers(0, C // 2 + 1)))
+        sizes = rng.integers(1, 40, size=n)
+        offs.append(np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32))
+    N = int(max(o[-1] for o in offs))
+    offs = [np.concatenate([o[:-1], [N]]).astype(np.int32) for o in offs]      # both rows end at N
+    packed, counts, c_max = gen.pack_boundaries(offs, N)
+    flavours = {
+        "normal": rng.standard_normal((B, Hkv, c_max)).astype(np.float32) * 30 + 200,
+        "ties": rng.integers(-3, 4, size=(B, Hkv, c_max)).astype(np.float32),
+        "wide": (rng.standard_normal((B, Hkv, c_max)) * 10.0 ** rng.integers(-20, 20, size=(B, Hkv, c_max))).astype(np.float32),
+        "flat": np.full((B, Hkv, c_max), -0.0, dtype=np.float32),
+    }
+    flavours["flat"][:, :, ::2] = 0.0
+    total = N
+    for name, score in flavours.items():
+        for max_chunks, budget in ((0, total // 10), (max(1, C // 7), 0), (max(1, C // 3), total // 5), (0, 0), (1, 0),
+                                   (0, 1), (0, total)):
+            k_max = c_max
+            want = oracle.topk_select(score, packed, counts, max_chunks, budget, k_max)
+            got = gpu_select(L, score, packed, counts, max_chunks, budget, k_max, N)
+            for w, g, what in zip(want, got, ("sel_idx", "sel_count", "sel_tokens")):
+                assert np.array_equal(w, g), f"{what} differs: C={C} {name} max_chunks={max_chunks} budget={budget}"
+
+
+def test_select_kmax_caps_the_count(L, oracle):
+    rng = np.random.default_rng(3)
+    C, N = 200, 200 * 8
+    off = gen.uniform_boundaries(N, 8)[None, :]
+    score = rng.standard_normal((1, 2, C)).astype(np.float32)
+    sel, cnt, tok = gpu_select(L, score, off, np.asarray([C], dtype=np.int32), 0, 0, 10, N)
+    want = oracle.topk_select(score, off, [C], 10, 0, 10)
+    assert np.array_equal(sel, want[0]) and np.array_equal(cnt, want[1]) and np.array_equal(tok, want[2])
+
+
+# ---------------------------------------------------------------------------
+# a4 attention
+# ---------------------------------------------------------------------------
+def gpu_attention(L, case_dtype, q, K, V, packed, counts, sel, cnt, k_max, max_tokens=0, ws_bytes=None):
+    B, Hkv, N, D = K.shape
+    Hq = q.shape[1]
+    c_max = packed.shape[1] - 1
+    shape = L.make_shape(B, Hq, Hkv, D, N, c_max, k_max, TDT[case_dtype])
+    out = torch.full((B, Hq, D), float("nan"), dtype=torch.float32, device="cuda")
+    lse = torch.full((B, Hq), float("nan"), dtype=torch.float32, device="cuda")
+    nbytes = L.leoam_workspace_bytes(shape, max_tokens) if ws_bytes is None else ws_bytes
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    L.sparse_chunk_attention_decode(shape, dev(q), dev(K), dev(V), dev(packed), dev(counts), dev(sel), dev(cnt),
+                                    L.default_scale(D), out, lse, ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("dtype,G", [("f32", 1), ("f32", 2), ("f16", 1), ("f16", 8), ("bf16", 4), ("bf16", 2)])
+def test_attention_random_selection(L, oracle, dtype, G):
+    rng = np.random.default_rng(40 + G)
+    B, Hkv, N, D = 2, 2, 2500, 128
+    K = torch.from_numpy(rng.standard_normal((B, Hkv, N, D)).astype(np.float32)).to(TDT[dtype])
+    V = torch.from_numpy(rng.standard_normal((B, Hkv, N, D)).astype(np.float32)).to(TDT[dtype])
+    q = torch.from_numpy(rng.standard_normal((B, Hkv * G, D)).astype(np.float32) * 1.5).to(TDT[dtype])
+    packed, counts, c_max = random_boundaries(rng, B, N, (1, 5, 16, 31, 64))
+    k_max = c_max
+    sel = np.full((B, Hkv, k_max), -1, dtype=np.int32)
+    cnt = np.zeros((B, Hkv), dtype=np.int32)
+    for b in range(B):
+        for h in range(Hkv):
+            n = int(rng.integers(1, counts[b]))
+            ids = np.sort(rng.choice(counts[b], size=n, replace=False))
+            sel[b, h, :n] = ids
+            cnt[b, h] = n
+    cnt[1, 1] = 0                                     # one head keeps nothing
+    want, want_lse = oracle.sparse_attention(q, K, V, packed, sel, cnt)
+    for ws_bytes in (None, B * Hkv * G * 130 * 4, 3 * B * Hkv * G * 130 * 4):      # default, 1 and 3 splits
+        got, got_lse = gpu_attention(L, dtype, q, K, V, packed, counts, sel, cnt, k_max, ws_bytes=ws_bytes)
+        assert np.abs(got - want).max() <= TOL[dtype]
+        fin = np.isfinite(want_lse)
+        assert np.array_equal(np.isneginf(got_lse), np.isneginf(want_lse))
+        assert np.abs(got_lse[fin] - want_lse[fin]).max() <= 1e-4
+        assert np.all(got[1, G:2 * G] == 0)
+
+
+def test_attention_select_all_is_dense(L, oracle):
+    g = torch.Generator().manual_seed(7)
+    B, Hkv, G, N, D = 1, 2, 4, 1111, 128
+    K = torch.randn(B, Hkv, N, D, generator=g).to(torch.bfloat16)
+    V = torch.randn(B, Hkv, N, D, generator=g).to(torch.bfloat16)
+    q = torch.randn(B, Hkv * G, D, generator=g).to(torch.bfloat16)
+    rng = np.random.default_rng(1)
+    packed, counts, c_max = random_boundaries(rng, B, N, (16, 32, 50))
+    sel = np.tile(np.arange(c_max, dtype=np.int32), (B, Hkv, 1))
+    cnt = np.tile(counts[:, None], (1, Hkv)).astype(np.int32)
+    got, _ = gpu_attention(L, "bf16", q, K, V, packed, counts, sel, cnt, c_max)
+    Kd = K.to(torch.float64).repeat_interleave(G, dim=1)
+    Vd = V.to(torch.float64).repeat_interleave(G, dim=1)
+    p = torch.softmax(torch.einsum("bjd,bjtd->bjt", q.to(torch.float64), Kd) / D ** 0.5, dim=-1)
+    dense = torch.einsum("bjt,bjtd->bjd", p, Vd).numpy()
+    assert np.abs(got - dense).max() <= TOL["bf16"]
+
+
+def test_attention_ignores_bad_ids(L, oracle):
+    g = torch.Generator().manual_seed(8)
+    B, Hkv, N, D = 1, 1, 256, 128
+    K = torch.randn(B, Hkv, N, D, generator=g)
+    V = torch.randn(B, Hkv, N, D, generator=g)
+    q = torch.randn(B, Hkv, D, generator=g)
+    off = gen.uniform_boundaries(N, 16)[None, :]
+    good = np.asarray([[[2, 5, -1, -1]]], dtype=np.int32)
+    bad = np.asarray([[[2, 99, 5, -3]]], dtype=np.int32)       # ids outside [0, 16) add no tokens
+    want, _ = oracle.sparse_attention(q, K, V, off, good, np.asarray([[2]], dtype=np.int32))
+    got, _ = gpu_attention(L, "f32", q, K, V, off, np.asarray([16], dtype=np.int32), bad, np.asarray([[4]], dtype=np.int32), 4)
+    assert np.abs(got - want).max() <= TOL["f32"]
+
+
+# ---------------------------------------------------------------------------
+# whole path on the paper-shaped configs
+# ---------------------------------------------------------------------------
+def run_path(L, case):
+    """abstract -> score -> select -> attention through the C ABI."""
+    layer = L.DecodeLayer(dev(case.K), dev(case.V), dev(case.chunk_off), dev(case.n_chunks), case.hq, case.k_max,
+                          case.max_chunks, case.token_budget)
+    assert L.leoam_validate_boundaries(layer.shape, layer.chunk_off, layer.n_chunks) == 0
+    layer.build_abstract()
+    layer.step(dev(case.q))
+    torch.cuda.synchronize()
+    return layer
+
+
+def check_path(L, oracle, case, seqs=None):
+    layer = run_path(L, case)
+    sl = slice(None) if seqs is None else seqs
+    K, V, q = case.K[sl].cpu(), case.V[sl].cpu(), case.q[sl].cpu()
+    off, nc = case.chunk_off[sl].cpu(), case.n_chunks[sl].cpu()
+    ab = oracle.abstract_build(K, off, nc)
+    got_ab = host_f64(layer.abstract[sl])
+    for b in range(ab.shape[0]):
+        assert np.array_equal(got_ab[b, :, : nc[b]], ab[b, :, : nc[b]]), "abstract"
+    ub, ub64 = oracle.chunk_score(q, np.nan_to_num(ab), nc, want_f64=True)
+    assert np.array_equal(layer.score[sl].cpu().numpy(), ub), "score"
+    sel, cnt, tok, margin = oracle.topk_select(ub, off, nc, case.max_chunks, case.token_budget, case.k_max, want_margin=True)
+    assert np.array_equal(layer.sel_count[sl].cpu().numpy(), cnt), "sel_count"
+    assert np.array_equal(layer.sel_idx[sl].cpu().numpy(), sel), "sel_idx"
+    assert np.array_equal(layer.sel_tokens[sl].cpu().numpy(), tok), "sel_tokens"
+    out, lse = oracle.sparse_attention(q, K, V, off, sel, cnt)
+    err = np.abs(host_f64(layer.out[sl]) - out).max()
+    assert err <= TOL[case.dtype], f"attention max-abs error {err}"
+    assert np.abs(host_f64(layer.lse[sl]) - lse).max() <= 1e-3
+    return dict(err=err, tokens=tok, margin=margin)
+
+
+def test_path_c0(L, oracle):
+    case = gen.make_case("c0")
+    res = check_path(L, oracle, case)
+    assert np.all(res["tokens"] == 512)
+
+
+@pytest.mark.parametrize("layer", [0, 31])
+def test_path_c1_reduced(L, oracle, layer):
+    case = gen.make_case("c1", layer=layer, n_ctx=8192 + 37, hq=8, hkv=8, token_budget=1024)
+    check_path(L, oracle, case)
+
+
+@pytest.mark.parametrize("layer", [0, 17, 31])
+def test_path_c2_reduced(L, oracle, layer):
+    case = gen.make_case("c2", layer=layer, n_ctx=16384 + 5, hq=8, hkv=2, token_budget=2048)
+    check_path(L, oracle, case)
+
+
+def test_path_c3_reduced_batch(L, oracle):
+    case = gen.make_case("c3", layer=9, batch=3, n_ctx=8192 + 100, hq=8, hkv=2, token_budget=1024)
+    check_path(L, oracle, case)
+
+
+def test_path_empty_selection(L, oracle):
+    case = gen.make_case("c2", layer=3, n_ctx=4096, hq=4, hkv=1, token_budget=8)     # every chunk has >= 16 tokens
+    layer = run_path(L, case)
+    assert int(layer.sel_count.abs().sum()) == 0
+    assert torch.all(layer.sel_idx == -1)
+    assert torch.all(layer.out == 0) and torch.all(torch.isneginf(layer.lse))
+
+
+@pytest.mark.parametrize("cfg,layer", [("c1", 5), ("c2", 0), ("c2", 31)])
+def test_path_full_size_layer(L, oracle, cfg, layer):
+    """One layer at the full shape of the benchmarked configuration, generated in HBM."""
+    case = gen.make_case(cfg, layer=layer, device="cuda")
+    check_path(L, oracle, case)
+
+
+def test_path_c3_full_shape_sampled(L, oracle):
+    """Batch-16 128K layer in the launch configuration bench.py times; the oracle
+    checks two of the sixteen sequences end to end."""
+    case = gen.make_case("c3", layer=30, device="cuda")
+    check_path(L, oracle, case, seqs=slice(5, 7))
+
+
+# ---------------------------------------------------------------------------
+# error paths (host-visible faults are refused before any launch)
+# ---------------------------------------------------------------------------
+def test_error_codes(L):
+    t = torch.zeros(16, device="cuda")
+    ok = L.make_shape(1, 8, 8, 128, 64, 4, 4, torch.float32)
+    for bad, code in ((L.make_shape(1, 8, 8, 64, 64, 4, 4, torch.float32), -3),
+                      (L.make_shape(1, 9, 8, 128, 64, 4, 4, torch.float32), -1),
+                      (L.make_shape(1, 24, 8, 128, 64, 4, 4, torch.float32), -3),
+                      (L.make_shape(1, 8, 8, 128, 64, 4, 5, torch.float32), -1),
+                      (L.make_shape(1, 8, 8, 128, 64, 20000, 4, torch.float32), -3),
+                      (L.make_shape(0, 8, 8, 128, 64, 4, 4, torch.float32), -1)):
+        with pytest.raises(L.LeoamError) as e:
+            L.chunk_score(bad, t, t, t, t)
+        assert e.value.status == code
+    with pytest.raises(L.LeoamError) as e:
+        L.chunk_score(ok, None, t, t, t)
+    assert e.value.status == -1
+    with pytest.raises(L.LeoamError) as e:
+        L.sparse_chunk_attention_decode(ok, t, t, t, t, t, t, t, 1.0, t, None, torch.zeros(8, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == -4
+    off = torch.tensor([[0, 10, 5, 64, 64]], dtype=torch.int32, device="cuda")
+    assert L.leoam_validate_boundaries(ok, off, torch.tensor([3], dtype=torch.int32, device="cuda")) == -2
+    torch.cuda.synchronize()
