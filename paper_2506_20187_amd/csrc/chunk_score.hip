@@ -6,98 +6,152 @@
 //          = sum_d max(q_j[d],0)*kmax[d] + min(q_j[d],0)*kmin[d]     (kmax >= kmin)
 //   L_j[c] = sum_d min(q_j[d],0)*kmax[d] + max(q_j[d],0)*kmin[d]
 //
-// The abstract of one (b,h) is a contiguous run of rows kmax(0),kmin(0),kmax(1),...
-// A wave-wide 16-byte-per-lane load covers 1 KiB of it: 2 chunks (16-bit) or one
-// (fp32).  Lanes on a kmax row multiply by max(q,0), lanes on a kmin row by
-// min(q,0), so one fused multiply-add per (element, query head) is all the
-// arithmetic.  Products of two stored values are exact in double; they are
-// accumulated in double and rounded once to float, which makes the score (and
-// the selection taken from it) independent of this kernel's summation layout up
-// to double rounding.
+// Products of two stored values are exact in double; they are accumulated in
+// double and rounded once to float, so the score (and the selection taken from
+// it) does not depend on this kernel's summation layout beyond double rounding.
+//
+// The double-precision contraction runs on the matrix cores:
+// v_mfma_f64_4x4x4 multiplies four independent 4x4 blocks per instruction,
+//   D_blk[i][j] += sum_k A_blk[i][k] * B_blk[k][j],
+// operands one double per lane with lane = 16*k + 4*blk + i (A), 16*k + 4*blk + j
+// (B), result lane = 16*i + 4*blk + j.  Here i = query head of the group (4 per
+// pass), j = an abstract row, k = 4 of the 128 channels.  Sixteen abstract rows
+// (8 chunks: their 8 kmax rows in blocks 0-1, their 8 kmin rows in blocks 2-3)
+// are contracted per instruction; blocks 0-1 carry max(q,0) as A, blocks 2-3
+// carry min(q,0), which is exactly the split of the bound above.  No cross-lane
+// reduction over channels is needed; one add joins the kmax and kmin halves and
+// two exchanges take the maximum over the heads.
+//
+// HBM-bound: a row set is 4 KiB of contiguous abstract; a lane fetches 16 bytes
+// per load, four lanes cover 64 contiguous bytes of a row, four loads the row.
 #include "leoam_dev.h"
 
 namespace leoam {
 
 constexpr int kScoreWaves = 4;
-constexpr int kScoreUnroll = 4;   // wave-wide loads in flight per iteration
+constexpr int kSetsPerIter = 2;    // independent row sets (accumulator chains) per wave iteration
+constexpr int kRowsPerSet = 16;    // abstract rows per MFMA = 8 chunks
+constexpr int kChunksPerSet = 8;
 
-// sum over the lanes [base, base + kSpan) the lane belongs to; kSpan is a power of two
-template <int kSpan> __device__ __forceinline__ double span_sum(double v) {
-#pragma unroll
-    for (int m = 1; m < kSpan; m <<= 1) v += shfl_xor_d(v, m);
-    return v;
+__device__ __forceinline__ double dpp_ror8_d(double v) {
+    // value of the lane 8 places away inside the 16-lane row (rotation by 8 is its own inverse)
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)u, 0x128, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)(u >> 32), 0x128, 0xf, 0xf, false);
+    return __builtin_bit_cast(double, ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
 }
 
+// kHeadSets = ceil(G / 4); heads beyond G contribute nothing.
 template <typename T, int G, bool kLower>
 __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
     const char* __restrict__ q, const char* __restrict__ abstract, const int32_t* __restrict__ n_chunks,
     float* __restrict__ score_ub, float* __restrict__ score_lb, int c_max, int n_kv_heads) {
-    constexpr int LPR = Row<T>::kLanesPerRow;
-    constexpr int RPL = Row<T>::kRowsPerLoad;
-    constexpr int CPL = RPL / 2;                 // chunks per wave-wide load
-    constexpr int EPL = T::kEpl;
+    constexpr int EPL = T::kEpl;                       // elements per 16-byte load
     constexpr int ROWB = Row<T>::kRowBytes;
+    constexpr int NLOAD = ROWB / 64;                   // 16-byte loads per lane per row: 4 (16-bit) or 8 (fp32)
+    constexpr int NSTEP = NLOAD * EPL;                 // MFMA steps per row set = 32
+    constexpr int HS = (G + 3) / 4;                    // passes over the heads
 
     const int b = blockIdx.z, h = blockIdx.y;
     const int wave = threadIdx.x / LEOAM_WAVE, lane = lane_id();
-    const int C = min(n_chunks[b], c_max);
+    const int C = min(max(n_chunks[b], 0), c_max);
     const size_t bh = (size_t)b * n_kv_heads + h;
     const char* Abh = abstract + bh * (size_t)c_max * 2 * ROWB;
-    const int row = lane / LPR;                  // row inside a load: even = kmax, odd = kmin
-    const bool on_min = row & 1;
-    const int slot = row >> 1;                   // chunk inside a load
-    const int col = (lane % LPR) * EPL;
 
-    // this lane's share of the clamped queries, in double
-    double qu[G][EPL], ql[kLower ? G : 1][EPL];
+    // B-operand role of this lane: abstract row r of the set, channel quarter kq
+    const int r = lane & 15, kq = lane >> 4;
+    const int chunk_in_set = r & 7, is_min_row = r >> 3;
+    const int row_off = (2 * chunk_in_set + is_min_row) * ROWB + 16 * kq;   // + 64 * load
+    // A-operand role: head a_head of the pass, block a_blk, channel quarter kq
+    const int a_head = lane & 3, a_blk = (lane >> 2) & 3;
+    const bool a_min = a_blk >= 2;                                          // blocks 2,3 hold kmin rows
+
+    // A operands: clamped query values for every step, in double
+    double qa[HS][NSTEP], qb[kLower ? HS : 1][kLower ? NSTEP : 1];
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        const size_t qrow = ((size_t)b * n_kv_heads * G + (size_t)h * G + g) * ROWB;
-        float x[EPL];
-        unpack<T>(load16(q, qrow + (size_t)col * T::kBytes), x);
+    for (int s = 0; s < HS; ++s) {
+        const int head = 4 * s + a_head;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-            const float pos = fmaxf(x[e], 0.f), neg = fminf(x[e], 0.f);
-            qu[g][e] = (double)(on_min ? neg : pos);
-            if (kLower) ql[g][e] = (double)(on_min ? pos : neg);
+        for (int i = 0; i < NLOAD; ++i) {
+            float x[EPL];
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) x[e] = 0.f;
+            if (head < G) {
+                const size_t qrow = ((size_t)b * n_kv_heads * G + (size_t)h * G + head) * ROWB;
+                unpack<T>(load16(q, qrow + 64 * i + 16 * kq), x);
+            }
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+                const float pos = fmaxf(x[e], 0.f), neg = fminf(x[e], 0.f);
+                qa[s][i * EPL + e] = (double)(a_min ? neg : pos);
+                if (kLower) qb[s][i * EPL + e] = (double)(a_min ? pos : neg);
+            }
         }
     }
 
-    const int n_loads = (C + CPL - 1) / CPL;
-    const int stride = gridDim.x * kScoreWaves * kScoreUnroll;
-    for (int l0 = (blockIdx.x * kScoreWaves + wave) * kScoreUnroll; l0 < n_loads; l0 += stride) {
-        uint4 v[kScoreUnroll];
+    const int n_sets = (C + kChunksPerSet - 1) / kChunksPerSet;
+    const int stride = gridDim.x * kScoreWaves * kSetsPerIter;
+    for (int s0 = (blockIdx.x * kScoreWaves + wave) * kSetsPerIter; s0 < n_sets; s0 += stride) {
+        uint4 v[kSetsPerIter][NLOAD];
 #pragma unroll
-        for (int u = 0; u < kScoreUnroll; ++u) {
-            const int c = (l0 + u) * CPL + slot;
-            v[u] = make_uint4(0, 0, 0, 0);
-            if (c < C) v[u] = load16(Abh, (size_t)(l0 + u) * (LEOAM_WAVE * 16) + (size_t)lane * 16);
+        for (int u = 0; u < kSetsPerIter; ++u) {
+            const int c = (s0 + u) * kChunksPerSet + chunk_in_set;
+            const size_t base = (size_t)(s0 + u) * (kRowsPerSet * ROWB) + row_off;
+#pragma unroll
+            for (int i = 0; i < NLOAD; ++i) {
+                v[u][i] = make_uint4(0, 0, 0, 0);
+                if (c < C) v[u][i] = load16(Abh, base + 64 * i);
+            }
         }
+        double ua[kSetsPerIter][HS], la[kSetsPerIter][kLower ? HS : 1];
 #pragma unroll
-        for (int u = 0; u < kScoreUnroll; ++u) {
-            const int c = (l0 + u) * CPL + slot;
-            float x[EPL];
-            unpack<T>(v[u], x);
-            double xd[EPL];
+        for (int u = 0; u < kSetsPerIter; ++u)
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) xd[e] = (double)x[e];
-            double ub = -INFINITY, lb = INFINITY;
+            for (int s = 0; s < HS; ++s) {
+                ua[u][s] = 0.0;
+                if (kLower) la[u][s] = 0.0;
+            }
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                double a = 0.0;
+        for (int i = 0; i < NLOAD; ++i) {
+            float x[kSetsPerIter][EPL];
 #pragma unroll
-                for (int e = 0; e < EPL; ++e) a = fma(qu[g][e], xd[e], a);
-                a = span_sum<2 * LPR>(a);
-                ub = fmax(ub, a);
-                if (kLower) {
-                    double z = 0.0;
+            for (int u = 0; u < kSetsPerIter; ++u) unpack<T>(v[u][i], x[u]);
 #pragma unroll
-                    for (int e = 0; e < EPL; ++e) z = fma(ql[g][e], xd[e], z);
-                    z = span_sum<2 * LPR>(z);
-                    lb = fmin(lb, z);
+            for (int e = 0; e < EPL; ++e) {
+#pragma unroll
+                for (int u = 0; u < kSetsPerIter; ++u) {
+                    const double xd = (double)x[u][e];
+#pragma unroll
+                    for (int s = 0; s < HS; ++s) {
+                        ua[u][s] = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[s][i * EPL + e], xd, ua[u][s], 0, 0, 0);
+                        if (kLower)
+                            la[u][s] = __builtin_amdgcn_mfma_f64_4x4x4f64(qb[s][i * EPL + e], xd, la[u][s], 0, 0, 0);
+                    }
                 }
             }
-            if ((lane % (2 * LPR)) == 0 && c < C) {
+        }
+        // result lane = 16*head + row; rows r and r+8 are the kmax and kmin halves of chunk r&7
+#pragma unroll
+        for (int u = 0; u < kSetsPerIter; ++u) {
+            double ub = -INFINITY, lb = INFINITY;
+#pragma unroll
+            for (int s = 0; s < HS; ++s) {
+                const bool real = (4 * s + kq) < G;                   // result row group kq = head of the pass
+                const double us = ua[u][s] + dpp_ror8_d(ua[u][s]);
+                ub = fmax(ub, real ? us : -INFINITY);
+                if (kLower) {
+                    const double ls = la[u][s] + dpp_ror8_d(la[u][s]);
+                    lb = fmin(lb, real ? ls : INFINITY);
+                }
+            }
+            ub = fmax(ub, shfl_xor_d(ub, 16));
+            ub = fmax(ub, shfl_xor_d(ub, 32));
+            if (kLower) {
+                lb = fmin(lb, shfl_xor_d(lb, 16));
+                lb = fmin(lb, shfl_xor_d(lb, 32));
+            }
+            const int c = (s0 + u) * kChunksPerSet + lane;
+            if (lane < kChunksPerSet && c < C) {
                 score_ub[bh * c_max + c] = (float)ub + 0.0f;
                 if (kLower) score_lb[bh * c_max + c] = (float)lb + 0.0f;
             }
@@ -113,9 +167,9 @@ __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
 template <typename T, int G>
 static hipError_t launch_score(const leoam_shape* s, const void* q, const void* abstract, const int32_t* n_chunks,
                                float* ub, float* lb, hipStream_t stream) {
-    constexpr int CPL = Row<T>::kRowsPerLoad / 2;
-    const int loads = (s->c_max + CPL - 1) / CPL;
-    int gx = (loads + kScoreWaves * kScoreUnroll - 1) / (kScoreWaves * kScoreUnroll);
+    const int sets = (s->c_max + kChunksPerSet - 1) / kChunksPerSet;
+    const int per_block = kScoreWaves * kSetsPerIter;
+    int gx = (sets + per_block - 1) / per_block;
     if (gx < 1) gx = 1;
     dim3 grid(gx, s->n_kv_heads, s->batch), block(kScoreWaves * LEOAM_WAVE);
     if (lb)

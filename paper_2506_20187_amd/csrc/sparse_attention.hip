@@ -10,6 +10,8 @@
 // keeps an online-softmax state (m, l, acc[D]) per query head of the group, and
 // writes one partial per range.  A second kernel combines the partials in range
 // order, so results do not depend on scheduling.
+#include <type_traits>
+
 #include "leoam_dev.h"
 
 namespace leoam {
@@ -250,6 +252,264 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_kernel(
     }
 }
 
+
+// ---------------------------------------------------------------------------
+// 16-bit keys/values: q K^T on the matrix cores.
+//
+// v_mfma_f32_16x16x32 (bf16 / f16): D[i][j] += sum_k A[i][k] B[k][j], A lane =
+// (i = lane%16, k = 8*(lane/16)..+8), B lane = (j = lane%16, same k), D lane =
+// (j = lane%16, i = 4*(lane/16)..+4).  Here i = a token of a 16-token tile, j =
+// a query head of the group (columns >= G are zero), k = 32 of the 128 channels:
+// four instructions give the 16 x G logits of a tile straight from the 16-byte
+// K loads (lane = token, four lanes cover 64 contiguous bytes of its row), with
+// no unpacking and no cross-lane reduction.  The logits of token 4*grp+r, head h
+// land in lane 16*grp+h, register r.  P V stays on the vector ALU in fp32 (P is
+// never rounded to 16 bits): lane group grp streams the V rows of tokens
+// 4*grp+0..3, so the weight it needs is a broadcast inside its own 16-lane row
+// (DPP row_newbcast), not a shuffle.
+// ---------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+template <typename T> __device__ __forceinline__ f32x4_t mfma_16x16x32(const uint4& a, const uint4& b, f32x4_t c);
+template <> __device__ __forceinline__ f32x4_t mfma_16x16x32<BF16>(const uint4& a, const uint4& b, f32x4_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+template <> __device__ __forceinline__ f32x4_t mfma_16x16x32<F16>(const uint4& a, const uint4& b, f32x4_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+}
+
+// value held by lane kSrc of this lane's 16-lane row
+template <int kSrc> __device__ __forceinline__ float row_bcast(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x150 + kSrc, 0xf, 0xf, true));
+}
+
+template <int kBegin, int kEnd, typename F> __device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (kBegin < kEnd) {
+        f(std::integral_constant<int, kBegin>{});
+        static_for<kBegin + 1, kEnd>(f);
+    }
+}
+
+constexpr int kMfmaTiles = 2;                         // 16-token tiles per wave iteration
+constexpr int kMfmaTile = kAttWaves * kMfmaTiles * 16; // tokens per workgroup iteration (= 128)
+
+template <typename T, int G>
+__global__ __launch_bounds__(kAttThreads) void sparse_attention_mfma_kernel(
+    const char* __restrict__ q, const char* __restrict__ K, const char* __restrict__ V,
+    const int32_t* __restrict__ chunk_off, const int32_t* __restrict__ n_chunks, const int32_t* __restrict__ sel_idx,
+    const int32_t* __restrict__ sel_count, float scale_log2, float* __restrict__ partial, int n_splits, int c_max,
+    int k_max, int n_kv_heads, int n_ctx) {
+    constexpr int ROWB = LEOAM_D * 2;
+    constexpr int EPL = 8;
+    constexpr int TILE = kMfmaTile;
+
+    extern __shared__ int32_t dyn[];                   // start[k_max] | prefix[k_max + 1]
+    __shared__ int32_t phys[TILE];
+    __shared__ float xw[kAttWaves][G][kPartStride];
+    __shared__ int32_t sh_total;
+
+    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid / LEOAM_WAVE;
+    const int grp = lane >> 4, c16 = lane & 15;
+    const size_t bh = (size_t)b * n_kv_heads + h;
+    const int C = min(max(n_chunks[b], 0), c_max);
+    const int cnt = min(max(sel_count[bh], 0), k_max);
+    const int32_t* off = chunk_off + (size_t)b * (c_max + 1);
+    const int32_t* sel = sel_idx + bh * (size_t)k_max;
+    int32_t* start = dyn;
+    int32_t* prefix = dyn + k_max;
+
+    // ---- kept chunks -> token prefix (same as the vector kernel) ---------------
+    for (int i = tid; i < cnt; i += kAttThreads) {
+        const int id = sel[i];
+        int t0 = 0, sz = 0;
+        if (id >= 0 && id < C) {
+            t0 = min(max(off[id], 0), n_ctx);
+            sz = min(max(off[id + 1], t0), n_ctx) - t0;
+        }
+        start[i] = t0;
+        prefix[i + 1] = sz;
+    }
+    if (tid == 0) prefix[0] = 0;
+    __syncthreads();
+    if (wave == 0) {
+        const int per = (cnt + LEOAM_WAVE - 1) / LEOAM_WAVE;
+        const int i0 = 1 + lane * per, i1 = min(cnt + 1, i0 + per);
+        int s = 0;
+        for (int i = i0; i < i1; ++i) s += prefix[i];
+        int incl = s;
+#pragma unroll
+        for (int d = 1; d < LEOAM_WAVE; d <<= 1) {
+            const int o = __shfl_up(incl, d, LEOAM_WAVE);
+            if (lane >= d) incl += o;
+        }
+        int run = incl - s;
+        for (int i = i0; i < i1; ++i) {
+            run += prefix[i];
+            prefix[i] = run;
+        }
+        if (lane == LEOAM_WAVE - 1) sh_total = incl;
+    }
+    __syncthreads();
+    const int total = sh_total;
+    int per_split = (total + n_splits - 1) / n_splits;
+    per_split = ((per_split + TILE - 1) / TILE) * TILE;
+    const int r0 = min(total, split * per_split), r1 = min(total, r0 + per_split);
+
+    // ---- B operand: the group's queries (column = head), zero beyond G ----------
+    uint4 qb[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        qb[s] = make_uint4(0, 0, 0, 0);
+        if (c16 < G) {
+            const size_t qrow = ((size_t)b * n_kv_heads * G + (size_t)h * G + c16) * ROWB;
+            qb[s] = load16(q, qrow + 64 * s + 16 * grp);
+        }
+    }
+
+    const char* Kbh = K + bh * (size_t)n_ctx * ROWB;
+    const char* Vbh = V + bh * (size_t)n_ctx * ROWB;
+
+    // lanes (grp, head) carry the softmax state of `head`; every lane carries the
+    // accumulators of all heads for the V rows of its group and its 8 columns
+    float m_run = -INFINITY, l_run = 0.f;
+    float acc[G][EPL];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+
+    for (int tb = r0; tb < r1; tb += TILE) {
+        __syncthreads();
+        for (int i = tid; i < TILE; i += kAttThreads) {
+            const int x = tb + i;
+            int p = -1;
+            if (x < r1) {
+                int lo = 0, hi = cnt;          // largest k with prefix[k] <= x
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (prefix[mid] <= x) lo = mid; else hi = mid;
+                }
+                p = start[lo] + (x - prefix[lo]);
+            }
+            phys[i] = p;
+        }
+        __syncthreads();
+
+        const int wbase = wave * (kMfmaTiles * 16);
+        uint4 kk[kMfmaTiles][4], vv[kMfmaTiles][4];
+#pragma unroll
+        for (int u = 0; u < kMfmaTiles; ++u) {
+            const int krow = phys[wbase + u * 16 + c16];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                kk[u][s] = make_uint4(0, 0, 0, 0);
+                if (krow >= 0) kk[u][s] = load16(Kbh, (size_t)krow * ROWB + 64 * s + 16 * grp);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int vrow = phys[wbase + u * 16 + 4 * grp + i];
+                vv[u][i] = make_uint4(0, 0, 0, 0);
+                if (vrow >= 0) vv[u][i] = load16(Vbh, (size_t)vrow * ROWB + 16 * c16);
+            }
+        }
+        // logits: z[u][r] = token (wbase + 16u + 4grp + r), head c16
+        float z[kMfmaTiles][4];
+        float mloc = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < kMfmaTiles; ++u) {
+            f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 4; ++s) sacc = mfma_16x16x32<T>(kk[u][s], qb[s], sacc);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const bool ok = (tb + wbase + u * 16 + 4 * grp + r) < r1;
+                z[u][r] = ok ? sacc[r] * scale_log2 : -INFINITY;
+                mloc = fmaxf(mloc, z[u][r]);
+            }
+        }
+        mloc = fmaxf(mloc, shfl_xor_f(mloc, 16));
+        mloc = fmaxf(mloc, shfl_xor_f(mloc, 32));
+        const float m_new = fmaxf(m_run, mloc);
+        const float corr = exp2_or_zero(m_run, m_new);
+        const bool changed = (c16 < G) && (m_new > m_run);
+        m_run = m_new;
+        float psum = 0.f;
+#pragma unroll
+        for (int u = 0; u < kMfmaTiles; ++u)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                z[u][r] = exp2_or_zero(z[u][r], m_new);     // now the weight
+                psum += z[u][r];
+            }
+        l_run = l_run * corr + psum;
+        if (__ballot(changed) != 0ull) {
+            // head g's correction factor sits in lane g of every row
+            static_for<0, G>([&](auto gc) {
+                constexpr int g = decltype(gc)::value;
+                const float cg = row_bcast<g>(corr);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[g][e] *= cg;
+            });
+        }
+#pragma unroll
+        for (int u = 0; u < kMfmaTiles; ++u)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float x[EPL];
+                unpack<T>(vv[u][i], x);
+                static_for<0, G>([&](auto gc) {
+                    constexpr int g = decltype(gc)::value;
+                    const float p = row_bcast<g>(z[u][i]);
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p, x[e], acc[g][e]);
+                });
+            }
+    }
+
+    // ---- fold the four lane groups (same m everywhere in the wave) ---------------
+    l_run += shfl_xor_f(l_run, 16);
+    l_run += shfl_xor_f(l_run, 32);
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+            acc[g][e] += shfl_xor_f(acc[g][e], 16);
+            acc[g][e] += shfl_xor_f(acc[g][e], 32);
+        }
+    if (grp == 0) {
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) xw[wave][g][c16 * EPL + e] = acc[g][e];
+        if (c16 < G) {
+            xw[wave][c16][LEOAM_D] = m_run;
+            xw[wave][c16][LEOAM_D + 1] = l_run;
+        }
+    }
+    __syncthreads();
+    float* part = partial + ((size_t)b * n_kv_heads * G + (size_t)h * G) * n_splits * kPartStride;
+    for (int i = tid; i < G * kPartStride; i += kAttThreads) {
+        const int g = i / kPartStride, d = i % kPartStride;
+        float m = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kAttWaves; ++w) m = fmaxf(m, xw[w][g][LEOAM_D]);
+        float v = 0.f;
+        if (d == LEOAM_D) {
+            v = m;
+        } else {
+#pragma unroll
+            for (int w = 0; w < kAttWaves; ++w) {
+                const float a = exp2_or_zero(xw[w][g][LEOAM_D], m);
+                v += a * (d < LEOAM_D ? xw[w][g][d] : xw[w][g][LEOAM_D + 1]);
+            }
+        }
+        part[((size_t)g * n_splits + split) * kPartStride + d] = v;
+    }
+}
+
 // out[b,j,:] = sum_s 2^(m_s - m) o_s / sum_s 2^(m_s - m) l_s, splits in index order
 __global__ __launch_bounds__(LEOAM_D) void attention_merge_kernel(const float* __restrict__ partial, int n_splits,
                                                                  float* __restrict__ out, float* __restrict__ lse) {
@@ -296,9 +556,14 @@ static hipError_t launch_attention(const leoam_shape* s, const void* q, const vo
                                    int n_splits, hipStream_t stream) {
     dim3 grid(n_splits, s->n_kv_heads, s->batch);
     const size_t dyn = (size_t)(2 * s->k_max + 1) * sizeof(int32_t);
-    hipLaunchKernelGGL((sparse_attention_kernel<T, G>), grid, dim3(kAttThreads), dyn, stream, (const char*)q,
-                       (const char*)K, (const char*)V, chunk_off, n_chunks, sel_idx, sel_count, scale * kLog2e, ws,
-                       n_splits, s->c_max, s->k_max, s->n_kv_heads, s->n_ctx);
+    if constexpr (T::kBytes == 2)
+        hipLaunchKernelGGL((sparse_attention_mfma_kernel<T, G>), grid, dim3(kAttThreads), dyn, stream, (const char*)q,
+                           (const char*)K, (const char*)V, chunk_off, n_chunks, sel_idx, sel_count, scale * kLog2e, ws,
+                           n_splits, s->c_max, s->k_max, s->n_kv_heads, s->n_ctx);
+    else
+        hipLaunchKernelGGL((sparse_attention_kernel<T, G>), grid, dim3(kAttThreads), dyn, stream, (const char*)q,
+                           (const char*)K, (const char*)V, chunk_off, n_chunks, sel_idx, sel_count, scale * kLog2e, ws,
+                           n_splits, s->c_max, s->k_max, s->n_kv_heads, s->n_ctx);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(attention_merge_kernel, dim3(s->batch * s->n_q_heads), dim3(LEOAM_D), 0, stream, ws, n_splits, out,
