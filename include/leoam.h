@@ -122,10 +122,14 @@ int chunk_topk_select(const leoam_shape* shape, const float* score_ub, const int
  * head j of kv head h:  z_t = softmax_scale * (q_j . K[b,h,t]),
  *   out[b,j,:] = sum_T softmax_T(z)_t * V[b,h,t,:],  lse[b,j] = log sum_T exp(z_t).
  * Nothing kept: out = 0, lse = -inf.  lse may be NULL.  Ids in sel_idx outside
- * [0, n_chunks) contribute no tokens.  The kept tokens are split across
- * workgroups; the number of splits is the largest the workspace allows, up to
- * what leoam_workspace_bytes() asks for, so a workspace of that size gives the
- * intended launch.  Partial results are combined in a fixed order.
+ * [0, n_chunks) contribute no tokens.  k_max must be <= 8192 here.
+ * The kept tokens are split across workgroups; every split leaves a partial
+ * (m, l, acc[D]) in the workspace and a second small kernel combines them in
+ * split order, so results do not depend on scheduling.  Workspace: 16-byte
+ * aligned, contents irrelevant on entry.  The number of splits is the largest
+ * the workspace allows, up to what leoam_workspace_bytes() asks for, so a
+ * workspace of that size gives the intended launch.  Calls that share a
+ * workspace must not overlap.
  */
 int sparse_chunk_attention_decode(const leoam_shape* shape, const void* q, const void* K, const void* V,
                                   const int32_t* chunk_off, const int32_t* n_chunks, const int32_t* sel_idx,

@@ -29,7 +29,6 @@
 namespace leoam {
 
 constexpr int kScoreWaves = 4;
-constexpr int kSetsPerIter = 2;    // independent row sets (accumulator chains) per wave iteration
 constexpr int kRowsPerSet = 16;    // abstract rows per MFMA = 8 chunks
 constexpr int kChunksPerSet = 8;
 
@@ -66,6 +65,25 @@ __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
     const int a_head = lane & 3, a_blk = (lane >> 2) & 3;
     const bool a_min = a_blk >= 2;                                          // blocks 2,3 hold kmin rows
 
+    const int n_sets = (C + kChunksPerSet - 1) / kChunksPerSet;
+    const int stride = gridDim.x * kScoreWaves;
+
+    auto fetch = [&](int set, uint4* v) {
+        const int c = set * kChunksPerSet + chunk_in_set;
+        const size_t base = (size_t)set * (kRowsPerSet * ROWB) + row_off;
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) {
+            v[i] = make_uint4(0, 0, 0, 0);
+            if (c < c_max) v[i] = load16(Abh, base + 64 * i);      // rows past n_chunks exist in the buffer; their results are dropped
+        }
+    };
+
+    // software pipeline: the next row set is in flight while this one is contracted;
+    // the first fetch goes out before the queries are converted
+    uint4 cur[NLOAD], nxt[NLOAD];
+    int set = blockIdx.x * kScoreWaves + wave;
+    fetch(set, cur);
+
     // A operands: clamped query values for every step, in double
     double qa[HS][NSTEP], qb[kLower ? HS : 1][kLower ? NSTEP : 1];
 #pragma unroll
@@ -89,71 +107,63 @@ __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
         }
     }
 
-    const int n_sets = (C + kChunksPerSet - 1) / kChunksPerSet;
-    const int stride = gridDim.x * kScoreWaves * kSetsPerIter;
-    for (int s0 = (blockIdx.x * kScoreWaves + wave) * kSetsPerIter; s0 < n_sets; s0 += stride) {
-        uint4 v[kSetsPerIter][NLOAD];
+    auto consume = [&](int set, const uint4* v) {
+        // two interleaved accumulator chains per head pass (even / odd steps)
+        double ua[HS][2], la[kLower ? HS : 1][2];
 #pragma unroll
-        for (int u = 0; u < kSetsPerIter; ++u) {
-            const int c = (s0 + u) * kChunksPerSet + chunk_in_set;
-            const size_t base = (size_t)(s0 + u) * (kRowsPerSet * ROWB) + row_off;
-#pragma unroll
-            for (int i = 0; i < NLOAD; ++i) {
-                v[u][i] = make_uint4(0, 0, 0, 0);
-                if (c < C) v[u][i] = load16(Abh, base + 64 * i);
-            }
+        for (int s = 0; s < HS; ++s) {
+            ua[s][0] = ua[s][1] = 0.0;
+            if (kLower) la[s][0] = la[s][1] = 0.0;
         }
-        double ua[kSetsPerIter][HS], la[kSetsPerIter][kLower ? HS : 1];
-#pragma unroll
-        for (int u = 0; u < kSetsPerIter; ++u)
-#pragma unroll
-            for (int s = 0; s < HS; ++s) {
-                ua[u][s] = 0.0;
-                if (kLower) la[u][s] = 0.0;
-            }
 #pragma unroll
         for (int i = 0; i < NLOAD; ++i) {
-            float x[kSetsPerIter][EPL];
-#pragma unroll
-            for (int u = 0; u < kSetsPerIter; ++u) unpack<T>(v[u][i], x[u]);
+            float x[EPL];
+            unpack<T>(v[i], x);
 #pragma unroll
             for (int e = 0; e < EPL; ++e) {
+                const double xd = (double)x[e];
 #pragma unroll
-                for (int u = 0; u < kSetsPerIter; ++u) {
-                    const double xd = (double)x[u][e];
-#pragma unroll
-                    for (int s = 0; s < HS; ++s) {
-                        ua[u][s] = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[s][i * EPL + e], xd, ua[u][s], 0, 0, 0);
-                        if (kLower)
-                            la[u][s] = __builtin_amdgcn_mfma_f64_4x4x4f64(qb[s][i * EPL + e], xd, la[u][s], 0, 0, 0);
-                    }
+                for (int s = 0; s < HS; ++s) {
+                    ua[s][e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[s][i * EPL + e], xd, ua[s][e & 1], 0, 0, 0);
+                    if (kLower)
+                        la[s][e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(qb[s][i * EPL + e], xd, la[s][e & 1], 0, 0, 0);
                 }
             }
         }
         // result lane = 16*head + row; rows r and r+8 are the kmax and kmin halves of chunk r&7
+        double ub = -INFINITY, lb = INFINITY;
 #pragma unroll
-        for (int u = 0; u < kSetsPerIter; ++u) {
-            double ub = -INFINITY, lb = INFINITY;
-#pragma unroll
-            for (int s = 0; s < HS; ++s) {
-                const bool real = (4 * s + kq) < G;                   // result row group kq = head of the pass
-                const double us = ua[u][s] + dpp_ror8_d(ua[u][s]);
-                ub = fmax(ub, real ? us : -INFINITY);
-                if (kLower) {
-                    const double ls = la[u][s] + dpp_ror8_d(la[u][s]);
-                    lb = fmin(lb, real ? ls : INFINITY);
-                }
-            }
-            ub = fmax(ub, shfl_xor_d(ub, 16));
-            ub = fmax(ub, shfl_xor_d(ub, 32));
+        for (int s = 0; s < HS; ++s) {
+            const bool real = (4 * s + kq) < G;                   // result row group kq = head of the pass
+            const double u1 = ua[s][0] + ua[s][1];
+            const double us = u1 + dpp_ror8_d(u1);
+            ub = fmax(ub, real ? us : -INFINITY);
             if (kLower) {
-                lb = fmin(lb, shfl_xor_d(lb, 16));
-                lb = fmin(lb, shfl_xor_d(lb, 32));
+                const double l1 = la[s][0] + la[s][1];
+                const double ls = l1 + dpp_ror8_d(l1);
+                lb = fmin(lb, real ? ls : INFINITY);
             }
-            const int c = (s0 + u) * kChunksPerSet + lane;
-            if (lane < kChunksPerSet && c < C) {
-                score_ub[bh * c_max + c] = (float)ub + 0.0f;
-                if (kLower) score_lb[bh * c_max + c] = (float)lb + 0.0f;
+        }
+        ub = fmax(ub, shfl_xor_d(ub, 16));
+        ub = fmax(ub, shfl_xor_d(ub, 32));
+        if (kLower) {
+            lb = fmin(lb, shfl_xor_d(lb, 16));
+            lb = fmin(lb, shfl_xor_d(lb, 32));
+        }
+        const int c = set * kChunksPerSet + lane;
+        if (lane < kChunksPerSet && c < C) {
+            score_ub[bh * c_max + c] = (float)ub + 0.0f;
+            if (kLower) score_lb[bh * c_max + c] = (float)lb + 0.0f;
+        }
+    };
+
+    {
+        for (; set < n_sets; set += 2 * stride) {
+            fetch(set + stride, nxt);
+            consume(set, cur);
+            if (set + stride < n_sets) {
+                fetch(set + 2 * stride, cur);
+                consume(set + stride, nxt);
             }
         }
     }
@@ -167,9 +177,13 @@ __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
 template <typename T, int G>
 static hipError_t launch_score(const leoam_shape* s, const void* q, const void* abstract, const int32_t* n_chunks,
                                float* ub, float* lb, hipStream_t stream) {
+    // about four resident workgroups per compute unit in total; every wave then
+    // walks several row sets with the next one prefetched
     const int sets = (s->c_max + kChunksPerSet - 1) / kChunksPerSet;
-    const int per_block = kScoreWaves * kSetsPerIter;
-    int gx = (sets + per_block - 1) / per_block;
+    const int units = s->batch * s->n_kv_heads;
+    int gx = (1024 + units - 1) / units;
+    const int gx_max = (sets + kScoreWaves - 1) / kScoreWaves;
+    if (gx > gx_max) gx = gx_max;
     if (gx < 1) gx = 1;
     dim3 grid(gx, s->n_kv_heads, s->batch), block(kScoreWaves * LEOAM_WAVE);
     if (lb)

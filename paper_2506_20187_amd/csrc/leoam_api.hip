@@ -13,6 +13,7 @@ hipError_t topk_select_dispatch(const leoam_shape*, const float*, const int32_t*
 hipError_t attention_dispatch(const leoam_shape*, const void*, const void*, const void*, const int32_t*, const int32_t*,
                               const int32_t*, const int32_t*, float, float*, float*, void*, size_t, hipStream_t);
 size_t attention_workspace_bytes(const leoam_shape*, int);
+size_t attention_min_workspace_bytes(const leoam_shape*);
 int attention_max_sel();
 
 __global__ void copy_probe_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
@@ -81,8 +82,7 @@ int sparse_chunk_attention_decode(const leoam_shape* shape, const void* q, const
     if (rc) return rc;
     if (!q || !K || !V || !chunk_off || !n_chunks || !sel_idx || !sel_count || !out) return LEOAM_E_INVALID_ARG;
     if (shape->k_max > attention_max_sel()) return LEOAM_E_UNSUPPORTED;
-    const size_t one = (size_t)shape->batch * shape->n_q_heads * (LEOAM_D + 2) * sizeof(float);
-    if (!workspace || workspace_bytes < one) return LEOAM_E_WORKSPACE;
+    if (!workspace || workspace_bytes < attention_min_workspace_bytes(shape)) return LEOAM_E_WORKSPACE;
     if (((uintptr_t)workspace & 15u) != 0) return LEOAM_E_WORKSPACE;
     return from_hip(attention_dispatch(shape, q, K, V, chunk_off, n_chunks, sel_idx, sel_count, softmax_scale, out, lse,
                                        workspace, workspace_bytes, (hipStream_t)stream));

@@ -32,6 +32,76 @@ __device__ __forceinline__ float exp2_or_zero(float x, float m) {
 // floats per partial: D accumulators + m + l
 constexpr int kPartStride = LEOAM_D + 2;
 
+
+// Cross-wave combine of the workgroup's online-softmax states into the partial
+// of this split.  xw[w][g] = (acc[D], m, l) of wave w, head g, log2 domain.
+// (Combining the splits in the same launch would need a device-scope release /
+// acquire per workgroup; on this part that is an L2 write-back and invalidate
+// per fence and costs far more than the small second kernel below.)
+template <int G>
+__device__ __forceinline__ void finish_split(float (*xw)[G][kPartStride], float* __restrict__ partial, int b, int h,
+                                             int split, int n_splits, int n_kv_heads) {
+    const int tid = threadIdx.x;
+    const size_t bh = (size_t)b * n_kv_heads + h;
+    __syncthreads();
+    float* part = partial + bh * G * (size_t)n_splits * kPartStride;
+    for (int i = tid; i < G * kPartStride; i += kAttThreads) {
+        const int g = i / kPartStride, d = i % kPartStride;
+        float m = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kAttWaves; ++w) m = fmaxf(m, xw[w][g][LEOAM_D]);
+        float v = 0.f;
+        if (d == LEOAM_D) {
+            v = m;
+        } else {
+#pragma unroll
+            for (int w = 0; w < kAttWaves; ++w) {
+                const float a = exp2_or_zero(xw[w][g][LEOAM_D], m);
+                v += a * (d < LEOAM_D ? xw[w][g][d] : xw[w][g][LEOAM_D + 1]);
+            }
+        }
+        part[((size_t)g * n_splits + split) * kPartStride + d] = v;
+    }
+}
+
+// out[b,j,:] = sum_s 2^(m_s - m) o_s / sum_s 2^(m_s - m) l_s, splits in index
+// order.  One workgroup per (b, query head); every load is issued before any is
+// used, so the kernel costs one memory round trip.
+constexpr int kMergeMaxSplits = 16;      // splits handled per register batch
+__global__ __launch_bounds__(LEOAM_D) void attention_merge_kernel(const float* __restrict__ partial, int n_splits,
+                                                                 float* __restrict__ out, float* __restrict__ lse) {
+    const size_t bj = blockIdx.x;
+    const int d = threadIdx.x;
+    const float* part = partial + bj * (size_t)n_splits * kPartStride;
+    float m = -INFINITY, o = 0.f, l = 0.f;
+    for (int s0 = 0; s0 < n_splits; s0 += kMergeMaxSplits) {
+        float ms[kMergeMaxSplits], ls[kMergeMaxSplits], os[kMergeMaxSplits];
+#pragma unroll
+        for (int i = 0; i < kMergeMaxSplits; ++i) {
+            const int s = s0 + i;
+            const bool ok = s < n_splits;
+            ms[i] = ok ? part[(size_t)s * kPartStride + LEOAM_D] : -INFINITY;
+            ls[i] = ok ? part[(size_t)s * kPartStride + LEOAM_D + 1] : 0.f;
+            os[i] = ok ? part[(size_t)s * kPartStride + d] : 0.f;
+        }
+        float mb = m;
+#pragma unroll
+        for (int i = 0; i < kMergeMaxSplits; ++i) mb = fmaxf(mb, ms[i]);
+        const float c = exp2_or_zero(m, mb);
+        o *= c;
+        l *= c;
+        m = mb;
+#pragma unroll
+        for (int i = 0; i < kMergeMaxSplits; ++i) {
+            const float a = exp2_or_zero(ms[i], m);
+            o += a * os[i];
+            l += a * ls[i];
+        }
+    }
+    out[bj * LEOAM_D + d] = (l > 0.f) ? o / l : 0.f;
+    if (lse && d == 0) lse[bj] = (l > 0.f) ? (m + log2f(l)) * kLn2 : -INFINITY;
+}
+
 template <typename T, int G>
 __global__ __launch_bounds__(kAttThreads) void sparse_attention_kernel(
     const char* __restrict__ q, const char* __restrict__ K, const char* __restrict__ V,
@@ -231,25 +301,7 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_kernel(
             }
         }
     }
-    __syncthreads();
-    float* part = partial + (((size_t)b * n_kv_heads * G + (size_t)h * G) * n_splits + 0) * kPartStride;
-    for (int i = tid; i < G * kPartStride; i += kAttThreads) {
-        const int g = i / kPartStride, d = i % kPartStride;
-        float m = -INFINITY;
-#pragma unroll
-        for (int w = 0; w < kAttWaves; ++w) m = fmaxf(m, xw[w][g][LEOAM_D]);
-        float v = 0.f;
-        if (d == LEOAM_D) {
-            v = m;
-        } else {
-#pragma unroll
-            for (int w = 0; w < kAttWaves; ++w) {
-                const float a = exp2_or_zero(xw[w][g][LEOAM_D], m);
-                v += a * (d < LEOAM_D ? xw[w][g][d] : xw[w][g][LEOAM_D + 1]);
-            }
-        }
-        part[((size_t)g * n_splits + split) * kPartStride + d] = v;
-    }
+    finish_split<G>(xw, partial, b, h, split, n_splits, n_kv_heads);
 }
 
 
@@ -292,8 +344,14 @@ template <int kBegin, int kEnd, typename F> __device__ __forceinline__ void stat
     }
 }
 
-constexpr int kMfmaTiles = 2;                         // 16-token tiles per wave iteration
-constexpr int kMfmaTile = kAttWaves * kMfmaTiles * 16; // tokens per workgroup iteration (= 128)
+constexpr int kMfmaWaveBlock = 256;                   // tokens a wave maps to rows at a time
+constexpr int kMfmaGranule = kAttWaves * 16;           // a split is a multiple of this many tokens
+
+// one 16-token tile of a wave: K operand (4 x 16 B per lane) and V rows (4 x 16 B per lane)
+struct KvTile {
+    uint4 k[4];
+    uint4 v[4];
+};
 
 template <typename T, int G>
 __global__ __launch_bounds__(kAttThreads) void sparse_attention_mfma_kernel(
@@ -303,10 +361,9 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_mfma_kernel(
     int k_max, int n_kv_heads, int n_ctx) {
     constexpr int ROWB = LEOAM_D * 2;
     constexpr int EPL = 8;
-    constexpr int TILE = kMfmaTile;
 
     extern __shared__ int32_t dyn[];                   // start[k_max] | prefix[k_max + 1]
-    __shared__ int32_t phys[TILE];
+    __shared__ int32_t rows[kAttWaves][kMfmaWaveBlock];
     __shared__ float xw[kAttWaves][G][kPartStride];
     __shared__ int32_t sh_total;
 
@@ -321,9 +378,23 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_mfma_kernel(
     int32_t* start = dyn;
     int32_t* prefix = dyn + k_max;
 
+    // ---- B operand: the group's queries (column = head), zero beyond G ----------
+    uint4 qb[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        qb[s] = make_uint4(0, 0, 0, 0);
+        if (c16 < G) {
+            const size_t qrow = ((size_t)b * n_kv_heads * G + (size_t)h * G + c16) * ROWB;
+            qb[s] = load16(q, qrow + 64 * s + 16 * grp);
+        }
+    }
+
     // ---- kept chunks -> token prefix (same as the vector kernel) ---------------
-    for (int i = tid; i < cnt; i += kAttThreads) {
+    // (the loop bound does not depend on loaded data, so these loads go out
+    // together with the loads of the counts and of the queries)
+    for (int i = tid; i < k_max; i += kAttThreads) {
         const int id = sel[i];
+        if (i >= cnt) continue;
         int t0 = 0, sz = 0;
         if (id >= 0 && id < C) {
             t0 = min(max(off[id], 0), n_ctx);
@@ -354,23 +425,17 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_mfma_kernel(
     }
     __syncthreads();
     const int total = sh_total;
+    // the split's range, then this wave's contiguous share of it; from here on the
+    // four waves are independent streams until the final merge
     int per_split = (total + n_splits - 1) / n_splits;
-    per_split = ((per_split + TILE - 1) / TILE) * TILE;
+    per_split = ((per_split + kMfmaGranule - 1) / kMfmaGranule) * kMfmaGranule;
     const int r0 = min(total, split * per_split), r1 = min(total, r0 + per_split);
+    const int per_wave = per_split / kAttWaves;
+    const int w0 = min(r1, r0 + wave * per_wave), w1 = min(r1, w0 + per_wave);
 
-    // ---- B operand: the group's queries (column = head), zero beyond G ----------
-    uint4 qb[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        qb[s] = make_uint4(0, 0, 0, 0);
-        if (c16 < G) {
-            const size_t qrow = ((size_t)b * n_kv_heads * G + (size_t)h * G + c16) * ROWB;
-            qb[s] = load16(q, qrow + 64 * s + 16 * grp);
-        }
-    }
-
-    const char* Kbh = K + bh * (size_t)n_ctx * ROWB;
-    const char* Vbh = V + bh * (size_t)n_ctx * ROWB;
+    const char* Kbh = K + bh * (size_t)n_ctx * ROWB + 16 * grp;        // + row*ROWB + 64*s
+    const char* Vbh = V + bh * (size_t)n_ctx * ROWB + 16 * c16;        // + row*ROWB
+    int32_t* my_rows = rows[wave];
 
     // lanes (grp, head) carry the softmax state of `head`; every lane carries the
     // accumulators of all heads for the V rows of its group and its 8 columns
@@ -381,54 +446,33 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_mfma_kernel(
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
 
-    for (int tb = r0; tb < r1; tb += TILE) {
-        __syncthreads();
-        for (int i = tid; i < TILE; i += kAttThreads) {
-            const int x = tb + i;
-            int p = -1;
-            if (x < r1) {
-                int lo = 0, hi = cnt;          // largest k with prefix[k] <= x
-                while (hi - lo > 1) {
-                    const int mid = (lo + hi) >> 1;
-                    if (prefix[mid] <= x) lo = mid; else hi = mid;
-                }
-                p = start[lo] + (x - prefix[lo]);
-            }
-            phys[i] = p;
+    auto fetch = [&](int t, KvTile& kv) {
+        // tile t of the current block: K row of token 16t + c16, V rows of tokens 16t + 4grp + i
+        const int krow = my_rows[16 * t + c16];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            kv.k[s] = make_uint4(0, 0, 0, 0);
+            if (krow >= 0) kv.k[s] = load16(Kbh, (size_t)krow * ROWB + 64 * s);
         }
-        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int vrow = my_rows[16 * t + 4 * grp + i];
+            kv.v[i] = make_uint4(0, 0, 0, 0);
+            if (vrow >= 0) kv.v[i] = load16(Vbh, (size_t)vrow * ROWB);
+        }
+    };
 
-        const int wbase = wave * (kMfmaTiles * 16);
-        uint4 kk[kMfmaTiles][4], vv[kMfmaTiles][4];
+    auto consume = [&](const KvTile& kv, int n_valid) {
+        // logits z[r] = token 4grp + r of the tile, head c16
+        f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int u = 0; u < kMfmaTiles; ++u) {
-            const int krow = phys[wbase + u * 16 + c16];
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                kk[u][s] = make_uint4(0, 0, 0, 0);
-                if (krow >= 0) kk[u][s] = load16(Kbh, (size_t)krow * ROWB + 64 * s + 16 * grp);
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int vrow = phys[wbase + u * 16 + 4 * grp + i];
-                vv[u][i] = make_uint4(0, 0, 0, 0);
-                if (vrow >= 0) vv[u][i] = load16(Vbh, (size_t)vrow * ROWB + 16 * c16);
-            }
-        }
-        // logits: z[u][r] = token (wbase + 16u + 4grp + r), head c16
-        float z[kMfmaTiles][4];
+        for (int s = 0; s < 4; ++s) sacc = mfma_16x16x32<T>(kv.k[s], qb[s], sacc);
+        float z[4];
         float mloc = -INFINITY;
 #pragma unroll
-        for (int u = 0; u < kMfmaTiles; ++u) {
-            f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < 4; ++s) sacc = mfma_16x16x32<T>(kk[u][s], qb[s], sacc);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const bool ok = (tb + wbase + u * 16 + 4 * grp + r) < r1;
-                z[u][r] = ok ? sacc[r] * scale_log2 : -INFINITY;
-                mloc = fmaxf(mloc, z[u][r]);
-            }
+        for (int r = 0; r < 4; ++r) {
+            z[r] = (4 * grp + r < n_valid) ? sacc[r] * scale_log2 : -INFINITY;
+            mloc = fmaxf(mloc, z[r]);
         }
         mloc = fmaxf(mloc, shfl_xor_f(mloc, 16));
         mloc = fmaxf(mloc, shfl_xor_f(mloc, 32));
@@ -438,12 +482,10 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_mfma_kernel(
         m_run = m_new;
         float psum = 0.f;
 #pragma unroll
-        for (int u = 0; u < kMfmaTiles; ++u)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                z[u][r] = exp2_or_zero(z[u][r], m_new);     // now the weight
-                psum += z[u][r];
-            }
+        for (int r = 0; r < 4; ++r) {
+            z[r] = exp2_or_zero(z[r], m_new);     // now the weight
+            psum += z[r];
+        }
         l_run = l_run * corr + psum;
         if (__ballot(changed) != 0ull) {
             // head g's correction factor sits in lane g of every row
@@ -455,18 +497,60 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_mfma_kernel(
             });
         }
 #pragma unroll
-        for (int u = 0; u < kMfmaTiles; ++u)
+        for (int i = 0; i < 4; ++i) {
+            float x[EPL];
+            unpack<T>(kv.v[i], x);
+            static_for<0, G>([&](auto gc) {
+                constexpr int g = decltype(gc)::value;
+                const float p = row_bcast<g>(z[i]);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                float x[EPL];
-                unpack<T>(vv[u][i], x);
-                static_for<0, G>([&](auto gc) {
-                    constexpr int g = decltype(gc)::value;
-                    const float p = row_bcast<g>(z[u][i]);
-#pragma unroll
-                    for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p, x[e], acc[g][e]);
-                });
+                for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p, x[e], acc[g][e]);
+            });
+        }
+    };
+
+    for (int blk = w0; blk < w1; blk += kMfmaWaveBlock) {
+        const int nb = min(kMfmaWaveBlock, w1 - blk);
+        // token position in the kept list -> row in the cache, for the whole block
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");      // earlier reads of my_rows are done
+        {
+            // a lane maps kMfmaWaveBlock/64 consecutive positions: one search, then a walk
+            constexpr int PER = kMfmaWaveBlock / LEOAM_WAVE;
+            const int i0 = lane * PER;
+            int lo = 0;
+            if (i0 < nb) {
+                const int x = blk + i0;
+                int hi = cnt;                  // largest k with prefix[k] <= x
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (prefix[mid] <= x) lo = mid; else hi = mid;
+                }
             }
+#pragma unroll
+            for (int j = 0; j < PER; ++j) {
+                int p = -1;
+                if (i0 + j < nb) {
+                    const int x = blk + i0 + j;
+                    while (prefix[lo + 1] <= x) ++lo;      // ends: prefix[cnt] = total > x
+                    p = start[lo] + (x - prefix[lo]);
+                }
+                my_rows[i0 + j] = p;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");      // table visible to the whole wave
+        __builtin_amdgcn_wave_barrier();
+
+        const int n_tiles = (nb + 15) >> 4;
+        KvTile cur, nxt;
+        fetch(0, cur);
+        for (int t = 0; t < n_tiles; t += 2) {
+            if (t + 1 < n_tiles) fetch(t + 1, nxt);
+            consume(cur, nb - 16 * t);
+            if (t + 1 < n_tiles) {
+                if (t + 2 < n_tiles) fetch(t + 2, cur);
+                consume(nxt, nb - 16 * (t + 1));
+            }
+        }
     }
 
     // ---- fold the four lane groups (same m everywhere in the wave) ---------------
@@ -489,43 +573,7 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_mfma_kernel(
             xw[wave][c16][LEOAM_D + 1] = l_run;
         }
     }
-    __syncthreads();
-    float* part = partial + ((size_t)b * n_kv_heads * G + (size_t)h * G) * n_splits * kPartStride;
-    for (int i = tid; i < G * kPartStride; i += kAttThreads) {
-        const int g = i / kPartStride, d = i % kPartStride;
-        float m = -INFINITY;
-#pragma unroll
-        for (int w = 0; w < kAttWaves; ++w) m = fmaxf(m, xw[w][g][LEOAM_D]);
-        float v = 0.f;
-        if (d == LEOAM_D) {
-            v = m;
-        } else {
-#pragma unroll
-            for (int w = 0; w < kAttWaves; ++w) {
-                const float a = exp2_or_zero(xw[w][g][LEOAM_D], m);
-                v += a * (d < LEOAM_D ? xw[w][g][d] : xw[w][g][LEOAM_D + 1]);
-            }
-        }
-        part[((size_t)g * n_splits + split) * kPartStride + d] = v;
-    }
-}
-
-// out[b,j,:] = sum_s 2^(m_s - m) o_s / sum_s 2^(m_s - m) l_s, splits in index order
-__global__ __launch_bounds__(LEOAM_D) void attention_merge_kernel(const float* __restrict__ partial, int n_splits,
-                                                                 float* __restrict__ out, float* __restrict__ lse) {
-    const size_t bj = blockIdx.x;
-    const int d = threadIdx.x;
-    const float* part = partial + bj * (size_t)n_splits * kPartStride;
-    float m = -INFINITY;
-    for (int s = 0; s < n_splits; ++s) m = fmaxf(m, part[(size_t)s * kPartStride + LEOAM_D]);
-    float o = 0.f, l = 0.f;
-    for (int s = 0; s < n_splits; ++s) {
-        const float a = exp2_or_zero(part[(size_t)s * kPartStride + LEOAM_D], m);
-        o += a * part[(size_t)s * kPartStride + d];
-        l += a * part[(size_t)s * kPartStride + LEOAM_D + 1];
-    }
-    out[bj * LEOAM_D + d] = (l > 0.f) ? o / l : 0.f;
-    if (lse && d == 0) lse[bj] = (l > 0.f) ? (m + log2f(l)) * kLn2 : -INFINITY;
+    finish_split<G>(xw, partial, b, h, split, n_splits, n_kv_heads);
 }
 
 static inline size_t part_bytes_per_split(const leoam_shape* s) {
@@ -534,11 +582,11 @@ static inline size_t part_bytes_per_split(const leoam_shape* s) {
 
 int attention_recommended_splits(const leoam_shape* s, int max_tokens) {
     if (max_tokens <= 0 || max_tokens > s->n_ctx) max_tokens = s->n_ctx;
-    const int rpl = (s->kv_dtype == LEOAM_F32) ? 2 : 4;
-    const int tile = kAttWaves * rpl * kAttRows;
-    const int by_tokens = (max_tokens + tile - 1) / tile;
+    // smallest range a workgroup takes: one tile per lane group (fp32) / one 16-token tile per wave
+    const int granule = (s->kv_dtype == LEOAM_F32) ? kAttWaves * 2 * kAttRows : kMfmaGranule;
+    const int by_tokens = (max_tokens + granule - 1) / granule;
     const int units = s->batch * s->n_kv_heads;
-    int want = (2048 + units - 1) / units;       // ~8 workgroups per compute unit in total
+    int want = (768 + units - 1) / units;        // about three resident workgroups per compute unit
     if (want > by_tokens) want = by_tokens;
     if (want > kAttMaxSplits) want = kAttMaxSplits;
     if (want < 1) want = 1;
@@ -549,13 +597,16 @@ size_t attention_workspace_bytes(const leoam_shape* s, int max_tokens) {
     return part_bytes_per_split(s) * (size_t)attention_recommended_splits(s, max_tokens);
 }
 
+size_t attention_min_workspace_bytes(const leoam_shape* s) { return part_bytes_per_split(s); }
+
 template <typename T, int G>
 static hipError_t launch_attention(const leoam_shape* s, const void* q, const void* K, const void* V,
                                    const int32_t* chunk_off, const int32_t* n_chunks, const int32_t* sel_idx,
-                                   const int32_t* sel_count, float scale, float* out, float* lse, float* ws,
+                                   const int32_t* sel_count, float scale, float* out, float* lse, void* workspace,
                                    int n_splits, hipStream_t stream) {
     dim3 grid(n_splits, s->n_kv_heads, s->batch);
     const size_t dyn = (size_t)(2 * s->k_max + 1) * sizeof(int32_t);
+    float* ws = (float*)workspace;
     if constexpr (T::kBytes == 2)
         hipLaunchKernelGGL((sparse_attention_mfma_kernel<T, G>), grid, dim3(kAttThreads), dyn, stream, (const char*)q,
                            (const char*)K, (const char*)V, chunk_off, n_chunks, sel_idx, sel_count, scale * kLog2e, ws,
@@ -574,7 +625,7 @@ static hipError_t launch_attention(const leoam_shape* s, const void* q, const vo
 template <typename T>
 static hipError_t attention_by_group(const leoam_shape* s, const void* q, const void* K, const void* V,
                                      const int32_t* chunk_off, const int32_t* n_chunks, const int32_t* sel_idx,
-                                     const int32_t* sel_count, float scale, float* out, float* lse, float* ws,
+                                     const int32_t* sel_count, float scale, float* out, float* lse, void* ws,
                                      int n_splits, hipStream_t stream) {
 #define LEOAM_ATT(GG) \
     launch_attention<T, GG>(s, q, K, V, chunk_off, n_chunks, sel_idx, sel_count, scale, out, lse, ws, n_splits, stream)
@@ -597,7 +648,7 @@ hipError_t attention_dispatch(const leoam_shape* s, const void* q, const void* K
     const size_t cap = (size_t)attention_recommended_splits(s, s->n_ctx);
     if (n > cap) n = cap;
     const int n_splits = (int)n;
-    float* ws = (float*)workspace;
+    void* ws = workspace;
     switch (s->kv_dtype) {
     case LEOAM_F32:
         return attention_by_group<F32>(s, q, K, V, chunk_off, n_chunks, sel_idx, sel_count, scale, out, lse, ws, n_splits, stream);

@@ -22,6 +22,7 @@ namespace leoam {
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / LEOAM_WAVE;
 constexpr int kBins = 256;
+constexpr int kMaxCand = 1024;   // chunks of the cut sub-range that are ranked pairwise
 
 // float -> uint32 whose unsigned order is the float order (-0 == +0)
 __device__ __forceinline__ uint32_t order_key(float s) {
@@ -77,7 +78,8 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(
     __shared__ uint64_t hist[kBins];
     __shared__ uint64_t wave_sums[kSelWaves];
     __shared__ uint32_t red_min[kSelWaves], red_max[kSelWaves];
-    __shared__ uint32_t sh_lo, sh_hi, sh_done;
+    __shared__ uint32_t sh_lo, sh_hi, sh_done, sh_nbin, sh_ncand;
+    __shared__ uint64_t cand_ki[kMaxCand], cand_tot[kMaxCand];
     __shared__ uint64_t sh_above;
 
     const int bh = blockIdx.x, b = bh / n_kv_heads;
@@ -133,9 +135,8 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(
         hi = max(hi, red_max[w]);
     }
 
-    // thr: keys above it are kept outright; ties on it are kept while they fit
-    uint32_t thr = 0;
     uint64_t above = 0;
+    bool use_cand = false;
     bool take_all = (C == 0) || fits((uint32_t)(grand >> 32), (uint32_t)grand, max_cnt, max_tok);
 
     if (!take_all) {
@@ -166,13 +167,14 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(
                 const uint64_t wave_total = __shfl(incl, LEOAM_WAVE - 1, LEOAM_WAVE);
                 uint64_t run = above + (wave_total - incl);        // totals of bins above this lane's bins
                 int first_bad = -1;                                // highest bin whose inclusion breaks the fit
-                uint64_t above_bad = 0;
+                uint64_t above_bad = 0, in_bad = 0;
 #pragma unroll
                 for (int k = 3; k >= 0; --k) {
                     const uint64_t with = run + hb[k];
                     if (first_bad < 0 && !fits((uint32_t)(with >> 32), (uint32_t)with, max_cnt, max_tok)) {
                         first_bad = 4 * lane + k;
                         above_bad = run;
+                        in_bad = hb[k];
                     }
                     run = with;
                 }
@@ -188,6 +190,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(
                     sh_hi = nhi;
                     sh_above = above_bad;
                     sh_done = (sh == 0) ? 1u : 0u;
+                    sh_nbin = (uint32_t)(in_bad >> 32);                // chunks inside the chosen sub-range
                 }
             }
             __syncthreads();
@@ -195,21 +198,56 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(
             hi = sh_hi;
             above = sh_above;
             const bool done = sh_done != 0;
+            const uint32_t nbin = sh_nbin;
             __syncthreads();
-            if (done) break;
+            if (nbin <= (uint32_t)kMaxCand) {
+                use_cand = true;
+                break;
+            }
+            if (done) break;      // one key left, held by more chunks than the pairwise step takes
         }
-        thr = lo;      // after the sh == 0 pass the range is one key
     }
 
-    // ---- ties on the threshold, in index order -----------------------------
+    // Chunks above the final range are kept, chunks below it are dropped; inside it
+    // the order (score descending, index ascending) decides.
     bool keep[kIpt];
-    uint64_t tie_mine = 0;
 #pragma unroll
-    for (int i = 0; i < kIpt; ++i) {
-        keep[i] = valid[i] && (take_all || key[i] > thr);
-        if (!take_all && valid[i] && key[i] == thr) tie_mine += pack_tot(1, size[i]);
-    }
-    if (!take_all) {
+    for (int i = 0; i < kIpt; ++i) keep[i] = valid[i] && (take_all || key[i] > hi);
+
+    if (!take_all && use_cand) {
+        // ---- few chunks left: each finds its running totals by comparing with all others
+        if (tid == 0) sh_ncand = 0;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kIpt; ++i) {
+            if (valid[i] && key[i] >= lo && key[i] <= hi) {
+                const uint32_t pos = atomicAdd(&sh_ncand, 1u);
+                if (pos < (uint32_t)kMaxCand) {
+                    cand_ki[pos] = ((uint64_t)key[i] << 32) | (uint32_t)(0x7fffffff - (c0 + i));
+                    cand_tot[pos] = pack_tot(1, size[i]);
+                }
+            }
+        }
+        __syncthreads();
+        const int n = (int)min(sh_ncand, (uint32_t)kMaxCand);
+#pragma unroll
+        for (int i = 0; i < kIpt; ++i) {
+            if (valid[i] && key[i] >= lo && key[i] <= hi) {
+                // "j comes no later than i" <=> (key_j, -idx_j) >= (key_i, -idx_i)
+                const uint64_t mine_ki = ((uint64_t)key[i] << 32) | (uint32_t)(0x7fffffff - (c0 + i));
+                uint64_t run = above;
+                for (int j = 0; j < n; ++j)
+                    if (cand_ki[j] >= mine_ki) run += cand_tot[j];
+                keep[i] = fits((uint32_t)(run >> 32), (uint32_t)run, max_cnt, max_tok);
+            }
+        }
+    } else if (!take_all) {
+        // ---- many ties on one key: running totals in index order by a workgroup scan
+        const uint32_t thr = lo;
+        uint64_t tie_mine = 0;
+#pragma unroll
+        for (int i = 0; i < kIpt; ++i)
+            if (valid[i] && key[i] == thr) tie_mine += pack_tot(1, size[i]);
         uint64_t tie_total;
         uint64_t run = above + block_excl_scan(tie_mine, wave_sums, &tie_total);
 #pragma unroll

@@ -150,14 +150,16 @@ def test_select_kmax_caps_the_count(L, oracle):
 # ---------------------------------------------------------------------------
 # a4 attention
 # ---------------------------------------------------------------------------
-def gpu_attention(L, case_dtype, q, K, V, packed, counts, sel, cnt, k_max, max_tokens=0, ws_bytes=None):
+def gpu_attention(L, case_dtype, q, K, V, packed, counts, sel, cnt, k_max, max_tokens=0, n_splits=None):
     B, Hkv, N, D = K.shape
     Hq = q.shape[1]
     c_max = packed.shape[1] - 1
     shape = L.make_shape(B, Hq, Hkv, D, N, c_max, k_max, TDT[case_dtype])
     out = torch.full((B, Hq, D), float("nan"), dtype=torch.float32, device="cuda")
     lse = torch.full((B, Hq), float("nan"), dtype=torch.float32, device="cuda")
-    nbytes = L.leoam_workspace_bytes(shape, max_tokens) if ws_bytes is None else ws_bytes
+    nbytes = L.leoam_workspace_bytes(shape, max_tokens)
+    if n_splits is not None:          # smallest workspace (one split) plus room for n_splits - 1 more partials
+        nbytes = L.leoam_workspace_bytes(shape, 1) + (n_splits - 1) * B * Hq * (D + 2) * 4
     ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
     L.sparse_chunk_attention_decode(shape, dev(q), dev(K), dev(V), dev(packed), dev(counts), dev(sel), dev(cnt),
                                     L.default_scale(D), out, lse, ws)
@@ -184,8 +186,8 @@ def test_attention_random_selection(L, oracle, dtype, G):
             cnt[b, h] = n
     cnt[1, 1] = 0                                     # one head keeps nothing
     want, want_lse = oracle.sparse_attention(q, K, V, packed, sel, cnt)
-    for ws_bytes in (None, B * Hkv * G * 130 * 4, 3 * B * Hkv * G * 130 * 4):      # default, 1 and 3 splits
-        got, got_lse = gpu_attention(L, dtype, q, K, V, packed, counts, sel, cnt, k_max, ws_bytes=ws_bytes)
+    for n_splits in (None, 1, 3, 3):      # default, one split, three splits (twice: the workspace is reusable)
+        got, got_lse = gpu_attention(L, dtype, q, K, V, packed, counts, sel, cnt, k_max, n_splits=n_splits)
         assert np.abs(got - want).max() <= TOL[dtype]
         fin = np.isfinite(want_lse)
         assert np.array_equal(np.isneginf(got_lse), np.isneginf(want_lse))
