@@ -60,7 +60,6 @@ __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
     // B-operand role of this lane: abstract row r of the set, channel quarter kq
     const int r = lane & 15, kq = lane >> 4;
     const int chunk_in_set = r & 7, is_min_row = r >> 3;
-    const int row_off = (2 * chunk_in_set + is_min_row) * ROWB + 16 * kq;   // + 64 * load
     // A-operand role: head a_head of the pass, block a_blk, channel quarter kq
     const int a_head = lane & 3, a_blk = (lane >> 2) & 3;
     const bool a_min = a_blk >= 2;                                          // blocks 2,3 hold kmin rows
@@ -68,21 +67,21 @@ __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
     const int n_sets = (C + kChunksPerSet - 1) / kChunksPerSet;
     const int stride = gridDim.x * kScoreWaves;
 
+    // Loads are unconditional (a guarded load would make the compiler wait for
+    // every outstanding load and defeat the prefetch): a row past the end of the
+    // buffer is read from the last chunk instead, and its result is dropped.
     auto fetch = [&](int set, uint4* v) {
-        const int c = set * kChunksPerSet + chunk_in_set;
-        const size_t base = (size_t)set * (kRowsPerSet * ROWB) + row_off;
+        const int c = min(set * kChunksPerSet + chunk_in_set, c_max - 1);
+        const size_t base = ((size_t)2 * c + is_min_row) * ROWB + 16 * kq;
 #pragma unroll
-        for (int i = 0; i < NLOAD; ++i) {
-            v[i] = make_uint4(0, 0, 0, 0);
-            if (c < c_max) v[i] = load16(Abh, base + 64 * i);      // rows past n_chunks exist in the buffer; their results are dropped
-        }
+        for (int i = 0; i < NLOAD; ++i) v[i] = load16(Abh, base + 64 * i);
     };
 
     // software pipeline: the next row set is in flight while this one is contracted;
     // the first fetch goes out before the queries are converted
     uint4 cur[NLOAD], nxt[NLOAD];
-    int set = blockIdx.x * kScoreWaves + wave;
-    fetch(set, cur);
+    const int g0 = blockIdx.x * kScoreWaves + wave;      // this wave's first group of four sets
+    fetch(4 * g0, cur);
 
     // A operands: clamped query values for every step, in double
     double qa[HS][NSTEP], qb[kLower ? HS : 1][kLower ? NSTEP : 1];
@@ -107,7 +106,11 @@ __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
         }
     }
 
-    auto consume = [&](int set, const uint4* v) {
+    // Scores of four consecutive row sets (32 chunks) are collected in one register
+    // per lane and written as a single 128-byte line: a store after every set would
+    // sit in the same in-order memory counter as the prefetched loads.
+    float pend_ub = 0.f, pend_lb = 0.f;
+    auto consume = [&](int it, int set, const uint4* v) {
         // two interleaved accumulator chains per head pass (even / odd steps)
         double ua[HS][2], la[kLower ? HS : 1][2];
 #pragma unroll
@@ -150,22 +153,35 @@ __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
             lb = fmin(lb, shfl_xor_d(lb, 16));
             lb = fmin(lb, shfl_xor_d(lb, 32));
         }
-        const int c = set * kChunksPerSet + lane;
-        if (lane < kChunksPerSet && c < C) {
-            score_ub[bh * c_max + c] = (float)ub + 0.0f;
-            if (kLower) score_lb[bh * c_max + c] = (float)lb + 0.0f;
+        // every lane holds the score of chunk (lane & 7) of this set
+        const int slot = it & 3;
+        if (((lane >> 3) & 3) == slot) {
+            pend_ub = (float)ub + 0.0f;
+            if (kLower) pend_lb = (float)lb + 0.0f;
+        }
+        if (slot == 3) {
+            const int c = (set - 3) * kChunksPerSet + lane;          // lanes 0..31 <-> the 32 chunks of the group
+            if (lane < 4 * kChunksPerSet && c < C) {
+                score_ub[bh * c_max + c] = pend_ub;
+                if (kLower) score_lb[bh * c_max + c] = pend_lb;
+            }
         }
     };
 
-    {
-        for (; set < n_sets; set += 2 * stride) {
-            fetch(set + stride, nxt);
-            consume(set, cur);
-            if (set + stride < n_sets) {
-                fetch(set + 2 * stride, cur);
-                consume(set + stride, nxt);
-            }
-        }
+    // A wave takes groups of four consecutive sets, groups round-robin over the
+    // waves of the (b,h).  No loads under a condition inside the loop; sets past
+    // the end are computed from clamped rows and store nothing.
+    const int n_groups = (n_sets + 3) >> 2;
+    const int my_groups = g0 < n_groups ? (n_groups - g0 + stride - 1) / stride : 0;
+    const int n_it = 4 * my_groups;
+    auto set_of = [&](int it) { return 4 * (g0 + (it >> 2) * stride) + (it & 3); };
+    for (int it = 0; it < n_it; it += 2) {
+        fetch(set_of(it + 1), nxt);
+        __builtin_amdgcn_sched_barrier(0);       // keep the loads ahead of the contraction
+        consume(it, set_of(it), cur);
+        fetch(set_of(it + 2), cur);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(it + 1, set_of(it + 1), nxt);
     }
     // tail of the row: chunks that do not exist
     for (int c = C + blockIdx.x * blockDim.x + threadIdx.x; c < c_max; c += gridDim.x * blockDim.x) {
@@ -182,7 +198,8 @@ static hipError_t launch_score(const leoam_shape* s, const void* q, const void* 
     const int sets = (s->c_max + kChunksPerSet - 1) / kChunksPerSet;
     const int units = s->batch * s->n_kv_heads;
     int gx = (1024 + units - 1) / units;
-    const int gx_max = (sets + kScoreWaves - 1) / kScoreWaves;
+    const int groups = (sets + 3) / 4;                      // a wave works on groups of four sets
+    const int gx_max = (groups + kScoreWaves - 1) / kScoreWaves;
     if (gx > gx_max) gx = gx_max;
     if (gx < 1) gx = 1;
     dim3 grid(gx, s->n_kv_heads, s->batch), block(kScoreWaves * LEOAM_WAVE);

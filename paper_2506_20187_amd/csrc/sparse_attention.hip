@@ -447,18 +447,17 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_mfma_kernel(
         for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
 
     auto fetch = [&](int t, KvTile& kv) {
-        // tile t of the current block: K row of token 16t + c16, V rows of tokens 16t + 4grp + i
-        const int krow = my_rows[16 * t + c16];
+        // tile t of the current block: K row of token 16t + c16, V rows of tokens 16t + 4grp + i.
+        // Loads are unconditional (a guarded load would make the compiler wait for every
+        // outstanding load and defeat the prefetch): a position past the end reads row 0,
+        // its logit is masked to -inf and its weight is exactly 0.
+        const int krow = max(my_rows[16 * t + c16], 0);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            kv.k[s] = make_uint4(0, 0, 0, 0);
-            if (krow >= 0) kv.k[s] = load16(Kbh, (size_t)krow * ROWB + 64 * s);
-        }
+        for (int s = 0; s < 4; ++s) kv.k[s] = load16(Kbh, (size_t)krow * ROWB + 64 * s);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int vrow = my_rows[16 * t + 4 * grp + i];
-            kv.v[i] = make_uint4(0, 0, 0, 0);
-            if (vrow >= 0) kv.v[i] = load16(Vbh, (size_t)vrow * ROWB);
+            const int vrow = max(my_rows[16 * t + 4 * grp + i], 0);
+            kv.v[i] = load16(Vbh, (size_t)vrow * ROWB);
         }
     };
 
@@ -544,12 +543,13 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_mfma_kernel(
         KvTile cur, nxt;
         fetch(0, cur);
         for (int t = 0; t < n_tiles; t += 2) {
-            if (t + 1 < n_tiles) fetch(t + 1, nxt);
+            // (no loads under a condition: a tile index past the end re-reads the last tile)
+            fetch(min(t + 1, n_tiles - 1), nxt);
+            __builtin_amdgcn_sched_barrier(0);       // keep the loads ahead of the tile's arithmetic
             consume(cur, nb - 16 * t);
-            if (t + 1 < n_tiles) {
-                if (t + 2 < n_tiles) fetch(t + 2, cur);
-                consume(nxt, nb - 16 * (t + 1));
-            }
+            fetch(min(t + 2, n_tiles - 1), cur);
+            __builtin_amdgcn_sched_barrier(0);
+            if (t + 1 < n_tiles) consume(nxt, nb - 16 * (t + 1));
         }
     }
 

@@ -80,6 +80,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(
     __shared__ uint32_t red_min[kSelWaves], red_max[kSelWaves];
     __shared__ uint32_t sh_lo, sh_hi, sh_done, sh_nbin, sh_ncand;
     __shared__ uint64_t cand_ki[kMaxCand], cand_tot[kMaxCand];
+    __shared__ uint32_t cand_keep[kMaxCand];
     __shared__ uint64_t sh_above;
 
     const int bh = blockIdx.x, b = bh / n_kv_heads;
@@ -215,14 +216,19 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(
     for (int i = 0; i < kIpt; ++i) keep[i] = valid[i] && (take_all || key[i] > hi);
 
     if (!take_all && use_cand) {
-        // ---- few chunks left: each finds its running totals by comparing with all others
+        // ---- few chunks left: the running totals of each come from comparing it with
+        // all the others; the n*n comparisons are spread over the whole workgroup
         if (tid == 0) sh_ncand = 0;
         __syncthreads();
+        uint32_t mypos[kIpt];
 #pragma unroll
         for (int i = 0; i < kIpt; ++i) {
+            mypos[i] = 0xffffffffu;
             if (valid[i] && key[i] >= lo && key[i] <= hi) {
                 const uint32_t pos = atomicAdd(&sh_ncand, 1u);
                 if (pos < (uint32_t)kMaxCand) {
+                    mypos[i] = pos;
+                    // "j comes no later than i" <=> (key_j, -idx_j) >= (key_i, -idx_i)
                     cand_ki[pos] = ((uint64_t)key[i] << 32) | (uint32_t)(0x7fffffff - (c0 + i));
                     cand_tot[pos] = pack_tot(1, size[i]);
                 }
@@ -230,17 +236,24 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(
         }
         __syncthreads();
         const int n = (int)min(sh_ncand, (uint32_t)kMaxCand);
-#pragma unroll
-        for (int i = 0; i < kIpt; ++i) {
-            if (valid[i] && key[i] >= lo && key[i] <= hi) {
-                // "j comes no later than i" <=> (key_j, -idx_j) >= (key_i, -idx_i)
-                const uint64_t mine_ki = ((uint64_t)key[i] << 32) | (uint32_t)(0x7fffffff - (c0 + i));
-                uint64_t run = above;
-                for (int j = 0; j < n; ++j)
-                    if (cand_ki[j] >= mine_ki) run += cand_tot[j];
-                keep[i] = fits((uint32_t)(run >> 32), (uint32_t)run, max_cnt, max_tok);
-            }
+        int tshift = 0;                                   // 2^tshift lanes share one chunk
+        while (tshift < 6 && (n << (tshift + 1)) <= kSelThreads) ++tshift;
+        const int cand = tid >> tshift, sub = tid & ((1 << tshift) - 1);
+        uint64_t run = 0;
+        if (cand < n) {
+            const uint64_t mine_ki = cand_ki[cand];
+            for (int j = sub; j < n; j += (1 << tshift))
+                if (cand_ki[j] >= mine_ki) run += cand_tot[j];
         }
+        for (int m = 1; m < (1 << tshift); m <<= 1) run += __shfl_xor(run, m, LEOAM_WAVE);
+        if (cand < n && sub == 0) {
+            run += above;
+            cand_keep[cand] = fits((uint32_t)(run >> 32), (uint32_t)run, max_cnt, max_tok) ? 1u : 0u;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kIpt; ++i)
+            if (mypos[i] != 0xffffffffu) keep[i] = cand_keep[mypos[i]] != 0u;
     } else if (!take_all) {
         // ---- many ties on one key: running totals in index order by a workgroup scan
         const uint32_t thr = lo;
