@@ -65,6 +65,19 @@ def algorithmic_bytes(layer, case, elem):
     return parts
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for a plain
+    copy of known size); None if there is no summary for this workload."""
+    path = os.path.join(ROOT, "profiles", f"pmc_{workload}_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch") and kernel in line:
+            return int(float(line.split("=")[1]))
+    return None
+
+
 def time_calls(fn, reps, torch):
     """Average wall time of fn() in ms over `reps` calls, HIP events on the current stream."""
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -205,7 +218,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(attn_gbs / HBM_PEAK_GBS, 4),
-            "traffic": None,
+            "traffic": measured_traffic(args.workload, "sparse_attention"),
             "bytes_per_launch": int(kv_bytes),
             "us_per_launch": round(attn_us, 2),
         },
