@@ -13,3 +13,4 @@ from .workloads import (  # noqa: F401
     uniform_boundaries,
     pack_boundaries,
 )
+from .quant import quantize_store, tag_four_bit, make_quant_case, QuantCase  # noqa: F401

@@ -259,7 +259,7 @@ def _gen_sequence(cfg_name: str, cfg: dict, layer: int, seq: int, n_ctx: int, de
     else:
         off = make_boundaries(n_ctx, _np_rng(seed, cfg_name, layer, seq, stream=1), sizes=cfg.get("sizes"),
                               size_range=cfg.get("size_range"), heavy=heavy, depth=depth)
-    return off, planted
+    return off, planted, heavy
 
 
 def make_case(config: str, layer: int = 0, *, device="cpu", seed: int = BASE_SEED, batch: Optional[int] = None,
@@ -281,10 +281,11 @@ def make_case(config: str, layer: int = 0, *, device="cpu", seed: int = BASE_SEE
     K = torch.empty(B, Hkv, N, D, dtype=tdt, device=device)
     V = torch.empty(B, Hkv, N, D, dtype=tdt, device=device)
     q = torch.empty(B, Hq, D, dtype=tdt, device=device)
-    offs, planted = [], None
+    offs, planted, heavy = [], None, []
     for b in range(B):
-        off, pl = _gen_sequence(config, cfg, layer, first_seq + b, N, device, seed, K[b], V[b], q[b])
+        off, pl, hv = _gen_sequence(config, cfg, layer, first_seq + b, N, device, seed, K[b], V[b], q[b])
         offs.append(off)
+        heavy.append(hv if hv is not None else np.zeros(N, dtype=bool))
         planted = pl if pl is not None else planted
     packed, counts, c_max = pack_boundaries(offs, N)
     smallest = min(int(np.diff(o).min()) for o in offs)
@@ -299,4 +300,4 @@ def make_case(config: str, layer: int = 0, *, device="cpu", seed: int = BASE_SEE
                 K=K, V=V, q=q,
                 chunk_off=torch.from_numpy(packed).to(device), n_chunks=torch.from_numpy(counts).to(device),
                 c_max=c_max, max_chunks=cfg["max_chunks"], token_budget=cfg["token_budget"], k_max=k_max,
-                planted=planted)
+                planted=planted, extra={"heavy": np.stack(heavy)})

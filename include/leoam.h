@@ -59,7 +59,26 @@ typedef enum {
     LEOAM_E_HIP = -6             /* a HIP call or launch failed */
 } leoam_status;
 
-typedef enum { LEOAM_F32 = 0, LEOAM_F16 = 1, LEOAM_BF16 = 2 } leoam_dtype;
+typedef enum { LEOAM_F32 = 0, LEOAM_F16 = 1, LEOAM_BF16 = 2, LEOAM_Q8Q4 = 3 } leoam_dtype;
+
+/*
+ * Compressed KV store (kv_dtype == LEOAM_Q8Q4; paper Sec. 4.4 "Dynamic KV
+ * compression", Sec. 6.1: compressed KV is INT4).  Every chunk of a (b,h) is
+ * stored either as 8-bit codes 0..255 (one byte per element, a token row is 128
+ * bytes) or as 4-bit codes 0..15 (two per byte, channel 2i in the low nibble of
+ * byte i, a row is 64 bytes), K and V in separate byte blobs that use the same
+ * per-chunk offsets.  A stored value is  scale * code + zero  with one
+ * (scale, zero) pair per (b, h, chunk, tensor), scale >= 0.  Which chunks are
+ * 4-bit is the caller's decision (the paper picks a share theta from a latency
+ * model; the tag is an input here).  q and the abstract are fp16.
+ * qmeta: [batch, n_kv_heads, c_max] records of 32 bytes.
+ */
+typedef struct {
+    int64_t byte_off; /* offset of the chunk's first row in the K blob and in the V blob; multiple of 16 */
+    int32_t bits;     /* 8 or 4 */
+    float scale_k, zero_k, scale_v, zero_v;
+    int32_t reserved;
+} leoam_qchunk;
 
 typedef struct {
     int32_t batch;          /* B  >= 1 */
@@ -69,8 +88,8 @@ typedef struct {
     int32_t n_ctx;          /* N, tokens per sequence (same for the whole batch) */
     int32_t c_max;          /* row stride of per-chunk arrays, 1..16384 */
     int32_t k_max;          /* row stride of sel_idx, 1..c_max; also caps the kept count */
-    int32_t kv_dtype;       /* leoam_dtype of K, V and q */
-    int32_t abstract_dtype; /* must equal kv_dtype */
+    int32_t kv_dtype;       /* leoam_dtype of K and V */
+    int32_t abstract_dtype; /* dtype of the abstract and of q: == kv_dtype, or LEOAM_F16 when kv_dtype == LEOAM_Q8Q4 */
 } leoam_shape;
 
 /*
@@ -80,8 +99,12 @@ typedef struct {
  * Exact (a maximum of stored values); the sign of a zero result is unspecified.
  * Rows of chunks >= n_chunks[b] are not written.  Token indices are clamped to
  * [0, n_ctx]; an empty chunk gives (-inf, +inf).
+ * LEOAM_Q8Q4: K is the K blob, qmeta the chunk records (NULL otherwise).  The
+ * maximum / minimum is taken over the stored values  scale_k*code + zero_k
+ * (evaluated in double) and rounded OUTWARD to fp16 (kmax up, kmin down), so the
+ * bounds of chunk_score still enclose every stored key.
  */
-int kv_chunk_abstract_build(const leoam_shape* shape, const void* K, const int32_t* chunk_off,
+int kv_chunk_abstract_build(const leoam_shape* shape, const void* K, const void* qmeta, const int32_t* chunk_off,
                             const int32_t* n_chunks, void* abstract, void* stream);
 
 /*
@@ -122,7 +145,11 @@ int chunk_topk_select(const leoam_shape* shape, const float* score_ub, const int
  * head j of kv head h:  z_t = softmax_scale * (q_j . K[b,h,t]),
  *   out[b,j,:] = sum_T softmax_T(z)_t * V[b,h,t,:],  lse[b,j] = log sum_T exp(z_t).
  * Nothing kept: out = 0, lse = -inf.  lse may be NULL.  Ids in sel_idx outside
- * [0, n_chunks) contribute no tokens.  k_max must be <= 8192 here.
+ * [0, n_chunks) contribute no tokens.  k_max must be <= 8192 here (<= 1024 for
+ * LEOAM_Q8Q4).  LEOAM_Q8Q4: K, V are the byte blobs, qmeta the chunk records
+ * (NULL otherwise); codes are expanded inside the kernel (Sec. 4.4: the cost of
+ * compression is decompression on the GPU), K[t] and V[t] above being the
+ * stored values scale*code + zero.
  * The kept tokens are split across workgroups; every split leaves a partial
  * (m, l, acc[D]) in the workspace and a second small kernel combines them in
  * split order, so results do not depend on scheduling.  Workspace: 16-byte
@@ -132,7 +159,7 @@ int chunk_topk_select(const leoam_shape* shape, const float* score_ub, const int
  * workspace must not overlap.
  */
 int sparse_chunk_attention_decode(const leoam_shape* shape, const void* q, const void* K, const void* V,
-                                  const int32_t* chunk_off, const int32_t* n_chunks, const int32_t* sel_idx,
+                                  const void* qmeta, const int32_t* chunk_off, const int32_t* n_chunks, const int32_t* sel_idx,
                                   const int32_t* sel_count, float softmax_scale, float* out, float* lse,
                                   void* workspace, size_t workspace_bytes, void* stream);
 

@@ -191,3 +191,92 @@ def decode_step(q, K, V, chunk_off, n_chunks, max_chunks, token_budget, k_max, a
     sel, cnt, tok = topk_select(ub, chunk_off, n_chunks, max_chunks, token_budget, k_max)
     out, lse = sparse_attention(q, K, V, chunk_off, sel, cnt)
     return dict(abstract=abstract, score=ub, sel_idx=sel, sel_count=cnt, sel_tokens=tok, out=out, lse=lse)
+
+
+# ---------------------------------------------------------------------------
+# compressed KV store (8-bit / 4-bit codes per chunk)
+# ---------------------------------------------------------------------------
+QCHUNK_DTYPE = np.dtype([("byte_off", "<i8"), ("bits", "<i4"), ("scale_k", "<f4"), ("zero_k", "<f4"),
+                         ("scale_v", "<f4"), ("zero_v", "<f4"), ("reserved", "<i4")])
+assert QCHUNK_DTYPE.itemsize == 32
+
+
+def _u8(x) -> np.ndarray:
+    try:
+        import torch
+        if isinstance(x, torch.Tensor):
+            x = x.detach().cpu().numpy()
+    except ImportError:  # pragma: no cover
+        pass
+    return np.ascontiguousarray(x).view(np.uint8).reshape(-1)
+
+
+def _qmeta(x) -> np.ndarray:
+    """[B,Hkv,c_max] records: accepts the structured array or its int32 [B,Hkv,c_max,8] image."""
+    try:
+        import torch
+        if isinstance(x, torch.Tensor):
+            x = x.detach().cpu().numpy()
+    except ImportError:  # pragma: no cover
+        pass
+    x = np.ascontiguousarray(x)
+    if x.dtype != QCHUNK_DTYPE:
+        x = x.view(QCHUNK_DTYPE).reshape(x.shape[:-1])
+    return x
+
+
+def half_ceil(x: float) -> float:
+    fn = _load().orc_half_ceil
+    fn.restype = ctypes.c_double
+    return float(fn(ctypes.c_double(x)))
+
+
+def half_floor(x: float) -> float:
+    fn = _load().orc_half_floor
+    fn.restype = ctypes.c_double
+    return float(fn(ctypes.c_double(x)))
+
+
+def dequant(blob, qmeta, chunk_off, n_chunks, n_ctx: int, head_dim: int, which: str = "k") -> np.ndarray:
+    """Stored values scale*code+zero of the whole store: float64 [B,Hkv,N,D]."""
+    qm = _qmeta(qmeta)
+    B, Hkv, c_max = qm.shape
+    off, nc = _i32(chunk_off), _i32(n_chunks)
+    out = np.zeros((B, Hkv, n_ctx, head_dim), dtype=np.float64)
+    bl = _u8(blob)
+    rc = _load().orc_dequant(B, Hkv, n_ctx, head_dim, _ptr(bl), _ptr(qm), 1 if which == "v" else 0, _ptr(off),
+                             _ptr(nc), c_max, _ptr(out))
+    assert rc == 0
+    return out
+
+
+def abstract_build_q(kblob, qmeta, chunk_off, n_chunks, head_dim: int = 128) -> np.ndarray:
+    """Sec. 4.3 abstract of the stored values, rounded outward to binary16: float64 [B,Hkv,c_max,2,D]."""
+    qm = _qmeta(qmeta)
+    B, Hkv, c_max = qm.shape
+    off, nc = _i32(chunk_off), _i32(n_chunks)
+    out = np.full((B, Hkv, c_max, 2, head_dim), np.nan, dtype=np.float64)
+    bl = _u8(kblob)
+    rc = _load().orc_abstract_build_q(B, Hkv, head_dim, _ptr(bl), _ptr(qm), _ptr(off), _ptr(nc), c_max, _ptr(out))
+    assert rc == 0
+    return out
+
+
+def sparse_attention_q(q, kblob, vblob, qmeta, chunk_off, sel_idx, sel_count, scale: Optional[float] = None):
+    """Eq. (1) over the kept chunks of the compressed store."""
+    qm = _qmeta(qmeta)
+    B, Hkv, c_max = qm.shape
+    qd = widen(q) if not (isinstance(q, np.ndarray) and q.dtype == np.float64) else np.ascontiguousarray(q)
+    Hq, D = qd.shape[1], qd.shape[2]
+    off = _i32(chunk_off)
+    sel, cnt = _i32(sel_idx), _i32(sel_count)
+    k_max = sel.shape[2]
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    out = np.empty((B, Hq, D), dtype=np.float64)
+    lse = np.empty((B, Hq), dtype=np.float64)
+    kb, vb = _u8(kblob), _u8(vblob)
+    rc = _load().orc_sparse_attention_q(B, Hq, Hkv, D, _ptr(qd), _ptr(kb), _ptr(vb), _ptr(qm), _ptr(off), c_max,
+                                        _ptr(sel), _ptr(cnt), k_max, ctypes.c_double(scale), _ptr(out), _ptr(lse))
+    assert rc == 0
+    return out, lse

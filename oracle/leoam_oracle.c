@@ -300,3 +300,156 @@ int orc_sparse_attention(int dtype, int B, int Hq, int Hkv, int N, int D, const 
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------------
+ * Compressed KV store (Sec. 4.4 dynamic KV compression; Sec. 6.1 INT4).
+ * A chunk of (b,h) is stored as 8-bit codes (one byte per element) or 4-bit
+ * codes (two per byte, even channel in the low nibble); a stored value is
+ * scale*code + zero with one (scale, zero) per (b,h,chunk,tensor).  The oracle
+ * works on the stored codes: value(t,d) = (double)scale * code + (double)zero.
+ * ------------------------------------------------------------------------ */
+typedef struct {
+    int64_t byte_off;
+    int32_t bits;
+    float scale_k, zero_k, scale_v, zero_v;
+    int32_t reserved;
+} orc_qchunk;
+
+static inline int q_code(const uint8_t *blob, const orc_qchunk *m, int t_in_chunk, int d, int D) {
+    if (m->bits == 8) return blob[m->byte_off + (int64_t)t_in_chunk * D + d];
+    uint8_t byte = blob[m->byte_off + (int64_t)t_in_chunk * (D / 2) + d / 2];
+    return (d & 1) ? (byte >> 4) : (byte & 15);
+}
+
+/* smallest binary16 value >= x (as a double); +inf if x is above the largest finite half */
+static double half_ceil(double x) {
+    /* walk the non-negative halves by bit pattern: they are ordered like their bits */
+    if (x != x) return x;
+    if (x > 65504.0) return INFINITY;
+    if (x <= -65504.0) return -65504.0;       /* the most negative finite half is >= x */
+    if (x >= 0.0) {
+        uint16_t lo = 0, hi = 0x7bff;             /* smallest pattern with value >= x */
+        while (lo < hi) {
+            uint16_t mid = (uint16_t)((lo + hi) / 2);
+            if (half_to_double(mid) >= x) hi = mid; else lo = (uint16_t)(mid + 1);
+        }
+        return half_to_double(lo);
+    }
+    /* x < 0: the largest magnitude m with -m >= x, i.e. largest pattern with value <= -x */
+    double ax = -x;
+    uint16_t lo = 0, hi = 0x7bff;
+    while (lo < hi) {
+        uint16_t mid = (uint16_t)((lo + hi + 1) / 2);
+        if (half_to_double(mid) <= ax) lo = mid; else hi = (uint16_t)(mid - 1);
+    }
+    return -half_to_double(lo);
+}
+
+double orc_half_ceil(double x) { return half_ceil(x); }
+double orc_half_floor(double x) { return -half_ceil(-x); }
+
+/* dequantise the whole (b,h,chunk) store to double: out [B,Hkv,N,D] */
+int orc_dequant(int B, int Hkv, int N, int D, const uint8_t *blob, const orc_qchunk *qmeta, int use_v,
+                const int32_t *chunk_off, const int32_t *n_chunks, int c_max, double *out) {
+    int bh;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (bh = 0; bh < B * Hkv; ++bh) {
+        int b = bh / Hkv;
+        const int32_t *off = chunk_off + (size_t)b * (c_max + 1);
+        for (int c = 0; c < n_chunks[b]; ++c) {
+            const orc_qchunk *m = qmeta + (size_t)bh * c_max + c;
+            double s = use_v ? (double)m->scale_v : (double)m->scale_k;
+            double z = use_v ? (double)m->zero_v : (double)m->zero_k;
+            for (int t = off[c]; t < off[c + 1]; ++t)
+                for (int d = 0; d < D; ++d)
+                    out[((size_t)bh * N + t) * D + d] = s * q_code(blob, m, t - off[c], d, D) + z;
+        }
+    }
+    return 0;
+}
+
+/* Sec. 4.3 abstract over the stored values, rounded outward to binary16:
+ * kmax = half_ceil(max_t value), kmin = half_floor(min_t value). */
+int orc_abstract_build_q(int B, int Hkv, int D, const uint8_t *kblob, const orc_qchunk *qmeta,
+                         const int32_t *chunk_off, const int32_t *n_chunks, int c_max, double *abs_out) {
+    int bh;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (bh = 0; bh < B * Hkv; ++bh) {
+        int b = bh / Hkv;
+        const int32_t *off = chunk_off + (size_t)b * (c_max + 1);
+        for (int c = 0; c < n_chunks[b]; ++c) {
+            const orc_qchunk *m = qmeta + (size_t)bh * c_max + c;
+            double *kmax = abs_out + (((size_t)bh * c_max + c) * 2 + 0) * D;
+            double *kmin = abs_out + (((size_t)bh * c_max + c) * 2 + 1) * D;
+            for (int d = 0; d < D; ++d) {
+                double hi = -INFINITY, lo = INFINITY;
+                for (int t = off[c]; t < off[c + 1]; ++t) {
+                    double x = (double)m->scale_k * q_code(kblob, m, t - off[c], d, D) + (double)m->zero_k;
+                    if (x > hi) hi = x;
+                    if (x < lo) lo = x;
+                }
+                kmax[d] = half_ceil(hi);
+                kmin[d] = -half_ceil(-lo);
+            }
+        }
+    }
+    return 0;
+}
+
+/* Eq. (1) over the kept chunks of the compressed store (same as orc_sparse_attention,
+ * K[t] and V[t] being the stored values). */
+int orc_sparse_attention_q(int B, int Hq, int Hkv, int D, const double *q, const uint8_t *kblob,
+                           const uint8_t *vblob, const orc_qchunk *qmeta, const int32_t *chunk_off, int c_max,
+                           const int32_t *sel_idx, const int32_t *sel_count, int k_max, double scale, double *out,
+                           double *lse) {
+    int G = Hq / Hkv;
+    int bj;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (bj = 0; bj < B * Hq; ++bj) {
+        int b = bj / Hq, j = bj % Hq, h = j / G;
+        size_t bh = (size_t)b * Hkv + h;
+        const int32_t *off = chunk_off + (size_t)b * (c_max + 1);
+        const int32_t *row = sel_idx + bh * k_max;
+        const double *qj = q + (size_t)bj * D;
+        double *o = out + (size_t)bj * D;
+        int cnt = sel_count[bh];
+        long T = 0;
+        for (int i = 0; i < cnt; ++i) T += off[row[i] + 1] - off[row[i]];
+        for (int d = 0; d < D; ++d) o[d] = 0.0;
+        if (T == 0) {
+            if (lse) lse[bj] = -INFINITY;
+            continue;
+        }
+        double *z = (double *)malloc(sizeof(double) * (size_t)T);
+        long n = 0;
+        double mx = -INFINITY;
+        for (int i = 0; i < cnt; ++i) {
+            const orc_qchunk *m = qmeta + bh * c_max + row[i];
+            for (int t = off[row[i]]; t < off[row[i] + 1]; ++t) {
+                double dot = 0.0;
+                for (int d = 0; d < D; ++d)
+                    dot += qj[d] * ((double)m->scale_k * q_code(kblob, m, t - off[row[i]], d, D) + (double)m->zero_k);
+                z[n] = scale * dot;
+                if (z[n] > mx) mx = z[n];
+                ++n;
+            }
+        }
+        double denom = 0.0;
+        for (long i = 0; i < T; ++i) {
+            z[i] = exp(z[i] - mx);
+            denom += z[i];
+        }
+        n = 0;
+        for (int i = 0; i < cnt; ++i) {
+            const orc_qchunk *m = qmeta + bh * c_max + row[i];
+            for (int t = off[row[i]]; t < off[row[i] + 1]; ++t) {
+                double p = z[n++] / denom;
+                for (int d = 0; d < D; ++d)
+                    o[d] += p * ((double)m->scale_v * q_code(vblob, m, t - off[row[i]], d, D) + (double)m->zero_v);
+            }
+        }
+        if (lse) lse[bj] = mx + log(denom);
+        free(z);
+    }
+    return 0;
+}

@@ -16,7 +16,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libleoam.so")
 
-F32, F16, BF16 = 0, 1, 2
+F32, F16, BF16, Q8Q4 = 0, 1, 2, 3
 _DTYPE_TAG = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 
 OK = 0
@@ -41,10 +41,10 @@ def _load() -> ctypes.CDLL:
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     sp = ctypes.POINTER(Shape)
-    lib.kv_chunk_abstract_build.argtypes = [sp, vp, vp, vp, vp, vp]
+    lib.kv_chunk_abstract_build.argtypes = [sp, vp, vp, vp, vp, vp, vp]
     lib.chunk_score.argtypes = [sp, vp, vp, vp, vp, vp, vp]
     lib.chunk_topk_select.argtypes = [sp, vp, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
-    lib.sparse_chunk_attention_decode.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, sz, vp]
+    lib.sparse_chunk_attention_decode.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, sz, vp]
     lib.leoam_workspace_bytes.argtypes = [sp, i32]
     lib.leoam_workspace_bytes.restype = sz
     lib.leoam_validate_boundaries.argtypes = [sp, vp, vp, vp]
@@ -74,8 +74,9 @@ def version() -> int:
 
 
 def make_shape(batch, n_q_heads, n_kv_heads, head_dim, n_ctx, c_max, k_max, dtype) -> Shape:
+    """dtype: a torch dtype, or Q8Q4 for the compressed store (q and abstract are then fp16)."""
     tag = _DTYPE_TAG[dtype] if isinstance(dtype, torch.dtype) else int(dtype)
-    return Shape(batch, n_q_heads, n_kv_heads, head_dim, n_ctx, c_max, k_max, tag, tag)
+    return Shape(batch, n_q_heads, n_kv_heads, head_dim, n_ctx, c_max, k_max, tag, F16 if tag == Q8Q4 else tag)
 
 
 def _p(t: Optional[torch.Tensor]):
@@ -97,8 +98,8 @@ def _check(status: int, where: str) -> None:
         raise LeoamError(status, where)
 
 
-def kv_chunk_abstract_build(shape: Shape, K, chunk_off, n_chunks, abstract, stream=None) -> None:
-    _check(_lib.kv_chunk_abstract_build(ctypes.byref(shape), _p(K), _p(chunk_off), _p(n_chunks), _p(abstract),
+def kv_chunk_abstract_build(shape: Shape, K, chunk_off, n_chunks, abstract, stream=None, qmeta=None) -> None:
+    _check(_lib.kv_chunk_abstract_build(ctypes.byref(shape), _p(K), _p(qmeta), _p(chunk_off), _p(n_chunks), _p(abstract),
                                         _stream(stream)), "kv_chunk_abstract_build")
 
 
@@ -116,9 +117,9 @@ def chunk_topk_select(shape: Shape, score_ub, chunk_off, n_chunks, max_chunks: i
 
 
 def sparse_chunk_attention_decode(shape: Shape, q, K, V, chunk_off, n_chunks, sel_idx, sel_count, softmax_scale,
-                                  out, lse, workspace, stream=None) -> None:
+                                  out, lse, workspace, stream=None, qmeta=None) -> None:
     nbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(_lib.sparse_chunk_attention_decode(ctypes.byref(shape), _p(q), _p(K), _p(V), _p(chunk_off), _p(n_chunks),
+    _check(_lib.sparse_chunk_attention_decode(ctypes.byref(shape), _p(q), _p(K), _p(V), _p(qmeta), _p(chunk_off), _p(n_chunks),
                                               _p(sel_idx), _p(sel_count), ctypes.c_float(softmax_scale), _p(out),
                                               _p(lse), _p(workspace), nbytes, _stream(stream)),
            "sparse_chunk_attention_decode")

@@ -1,0 +1,61 @@
+// Pieces shared by the attention kernels (dense and compressed store): launch
+// constants, the online-softmax helpers and the per-split partial layout.
+#pragma once
+#include "leoam_dev.h"
+
+namespace leoam {
+
+constexpr int kAttWaves = 4;
+constexpr int kAttThreads = kAttWaves * LEOAM_WAVE;
+constexpr int kAttRows = 8;            // rows per lane group per tile
+constexpr int kAttMaxSplits = 256;
+constexpr int kAttMaxSel = 8192;       // kept chunks per (b,h) the kernel can index
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ float exp2_or_zero(float x, float m) {
+    // 2^(x - m), with 2^(-inf - anything) = 0 also when m is -inf
+    return (x == -INFINITY) ? 0.f : exp2f(x - m);
+}
+
+// floats per partial: D accumulators + m + l
+constexpr int kPartStride = LEOAM_D + 2;
+
+
+// Cross-wave combine of the workgroup's online-softmax states into the partial
+// of this split.  xw[w][g] = (acc[D], m, l) of wave w, head g, log2 domain.
+// (Combining the splits in the same launch would need a device-scope release /
+// acquire per workgroup; on this part that is an L2 write-back and invalidate
+// per fence and costs far more than the small second kernel below.)
+template <int G>
+__device__ __forceinline__ void finish_split(float (*xw)[G][kPartStride], float* __restrict__ partial, int b, int h,
+                                             int split, int n_splits, int n_kv_heads) {
+    const int tid = threadIdx.x;
+    const size_t bh = (size_t)b * n_kv_heads + h;
+    __syncthreads();
+    float* part = partial + bh * G * (size_t)n_splits * kPartStride;
+    for (int i = tid; i < G * kPartStride; i += kAttThreads) {
+        const int g = i / kPartStride, d = i % kPartStride;
+        float m = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kAttWaves; ++w) m = fmaxf(m, xw[w][g][LEOAM_D]);
+        float v = 0.f;
+        if (d == LEOAM_D) {
+            v = m;
+        } else {
+#pragma unroll
+            for (int w = 0; w < kAttWaves; ++w) {
+                const float a = exp2_or_zero(xw[w][g][LEOAM_D], m);
+                v += a * (d < LEOAM_D ? xw[w][g][d] : xw[w][g][LEOAM_D + 1]);
+            }
+        }
+        part[((size_t)g * n_splits + split) * kPartStride + d] = v;
+    }
+}
+
+
+// host-side launch of the kernel that combines the partials (sparse_attention.hip)
+hipError_t launch_attention_merge(const leoam_shape* s, const float* partial, int n_splits, float* out, float* lse,
+                                  hipStream_t stream);
+
+}  // namespace leoam

@@ -225,7 +225,7 @@ static hipError_t score_by_group(const leoam_shape* s, const void* q, const void
 
 hipError_t chunk_score_dispatch(const leoam_shape* s, const void* q, const void* abstract, const int32_t* n_chunks,
                                 float* ub, float* lb, hipStream_t stream) {
-    switch (s->kv_dtype) {
+    switch (s->abstract_dtype) {      // dtype of the abstract and of q
     case LEOAM_F32: return score_by_group<F32>(s, q, abstract, n_chunks, ub, lb, stream);
     case LEOAM_F16: return score_by_group<F16>(s, q, abstract, n_chunks, ub, lb, stream);
     default: return score_by_group<BF16>(s, q, abstract, n_chunks, ub, lb, stream);

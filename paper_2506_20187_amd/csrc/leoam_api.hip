@@ -10,8 +10,12 @@ hipError_t abstract_build_dispatch(const leoam_shape*, const void*, const int32_
 hipError_t chunk_score_dispatch(const leoam_shape*, const void*, const void*, const int32_t*, float*, float*, hipStream_t);
 hipError_t topk_select_dispatch(const leoam_shape*, const float*, const int32_t*, const int32_t*, int, int, int32_t*,
                                 int32_t*, int32_t*, hipStream_t);
-hipError_t attention_dispatch(const leoam_shape*, const void*, const void*, const void*, const int32_t*, const int32_t*,
-                              const int32_t*, const int32_t*, float, float*, float*, void*, size_t, hipStream_t);
+hipError_t attention_dispatch(const leoam_shape*, const void*, const void*, const void*, const void*, const int32_t*,
+                              const int32_t*, const int32_t*, const int32_t*, float, float*, float*, void*, size_t,
+                              hipStream_t);
+hipError_t abstract_build_q_dispatch(const leoam_shape*, const void*, const void*, const int32_t*, const int32_t*, void*,
+                                     hipStream_t);
+int attention_q_max_sel();
 size_t attention_workspace_bytes(const leoam_shape*, int);
 size_t attention_min_workspace_bytes(const leoam_shape*);
 int attention_max_sel();
@@ -30,8 +34,12 @@ static int check_shape(const leoam_shape* s) {
     if (s->head_dim != LEOAM_D) return LEOAM_E_UNSUPPORTED;
     const int g = s->n_q_heads / s->n_kv_heads;
     if (g != 1 && g != 2 && g != 4 && g != 8) return LEOAM_E_UNSUPPORTED;
-    if (s->kv_dtype != LEOAM_F32 && s->kv_dtype != LEOAM_F16 && s->kv_dtype != LEOAM_BF16) return LEOAM_E_UNSUPPORTED;
-    if (s->abstract_dtype != s->kv_dtype) return LEOAM_E_UNSUPPORTED;
+    if (s->kv_dtype == LEOAM_Q8Q4) {
+        if (s->abstract_dtype != LEOAM_F16) return LEOAM_E_UNSUPPORTED;
+    } else {
+        if (s->kv_dtype != LEOAM_F32 && s->kv_dtype != LEOAM_F16 && s->kv_dtype != LEOAM_BF16) return LEOAM_E_UNSUPPORTED;
+        if (s->abstract_dtype != s->kv_dtype) return LEOAM_E_UNSUPPORTED;
+    }
     if (s->c_max > 16384) return LEOAM_E_UNSUPPORTED;
     if ((long long)s->batch * s->n_kv_heads > 65535 * 8) return LEOAM_E_UNSUPPORTED;
     if (s->n_kv_heads > 65535 || s->batch > 65535) return LEOAM_E_UNSUPPORTED;
@@ -45,11 +53,15 @@ using namespace leoam;
 
 extern "C" {
 
-int kv_chunk_abstract_build(const leoam_shape* shape, const void* K, const int32_t* chunk_off,
+int kv_chunk_abstract_build(const leoam_shape* shape, const void* K, const void* qmeta, const int32_t* chunk_off,
                             const int32_t* n_chunks, void* abstract, void* stream) {
     int rc = check_shape(shape);
     if (rc) return rc;
     if (!K || !chunk_off || !n_chunks || !abstract) return LEOAM_E_INVALID_ARG;
+    if (shape->kv_dtype == LEOAM_Q8Q4) {
+        if (!qmeta) return LEOAM_E_INVALID_ARG;
+        return from_hip(abstract_build_q_dispatch(shape, K, qmeta, chunk_off, n_chunks, abstract, (hipStream_t)stream));
+    }
     return from_hip(abstract_build_dispatch(shape, K, chunk_off, n_chunks, abstract, (hipStream_t)stream));
 }
 
@@ -75,16 +87,20 @@ int chunk_topk_select(const leoam_shape* shape, const float* score_ub, const int
 }
 
 int sparse_chunk_attention_decode(const leoam_shape* shape, const void* q, const void* K, const void* V,
-                                  const int32_t* chunk_off, const int32_t* n_chunks, const int32_t* sel_idx,
+                                  const void* qmeta, const int32_t* chunk_off, const int32_t* n_chunks, const int32_t* sel_idx,
                                   const int32_t* sel_count, float softmax_scale, float* out, float* lse,
                                   void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_shape(shape);
     if (rc) return rc;
     if (!q || !K || !V || !chunk_off || !n_chunks || !sel_idx || !sel_count || !out) return LEOAM_E_INVALID_ARG;
     if (shape->k_max > attention_max_sel()) return LEOAM_E_UNSUPPORTED;
+    if (shape->kv_dtype == LEOAM_Q8Q4) {
+        if (!qmeta) return LEOAM_E_INVALID_ARG;
+        if (shape->k_max > attention_q_max_sel()) return LEOAM_E_UNSUPPORTED;
+    }
     if (!workspace || workspace_bytes < attention_min_workspace_bytes(shape)) return LEOAM_E_WORKSPACE;
     if (((uintptr_t)workspace & 15u) != 0) return LEOAM_E_WORKSPACE;
-    return from_hip(attention_dispatch(shape, q, K, V, chunk_off, n_chunks, sel_idx, sel_count, softmax_scale, out, lse,
+    return from_hip(attention_dispatch(shape, q, K, V, qmeta, chunk_off, n_chunks, sel_idx, sel_count, softmax_scale, out, lse,
                                        workspace, workspace_bytes, (hipStream_t)stream));
 }
 

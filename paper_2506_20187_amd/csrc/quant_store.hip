@@ -1,0 +1,401 @@
+// Compressed KV store: abstract build and sparse decode attention over chunks
+// stored as 8-bit or 4-bit codes (paper Sec. 4.4 "Dynamic KV compression": the
+// price of compressed transfer is decompression on the GPU; Sec. 6.1: INT4).
+//
+// A stored value is scale*code + zero with one (scale, zero) per (b,h,chunk,
+// tensor).  Because they are per-chunk scalars nothing is dequantised element by
+// element in the attention kernel:
+//   q . k_t         = scale_k * (q . code_t) + zero_k * sum_d q_d
+//   sum_t p_t v_t   = sum_t (p_t * scale_v) code_t  +  (sum_t p_t * zero_v) * 1
+// so the codes go straight from integer to float (exact) into the same fp32
+// online-softmax pipeline as the dense kernels.
+//
+// Row layout: 8-bit chunks have 128-byte rows, 4-bit chunks 64-byte rows with
+// channel 2i in the low nibble of byte i.  In both kernels 16 lanes share a row
+// and a lane owns 8 consecutive channels (8 or 4 bytes).
+#include "attention_common.h"
+
+namespace leoam {
+
+struct QChunk {             // device image of leoam_qchunk
+    long long byte_off;
+    int bits;
+    float scale_k, zero_k, scale_v, zero_v;
+    int reserved;
+};
+static_assert(sizeof(QChunk) == sizeof(leoam_qchunk), "record layout");
+
+// the 8 codes of this lane's channels [8*c16, 8*c16+8) of the row at `row`
+__device__ __forceinline__ void load_codes(const unsigned char* row, int bits, int c16, float* x) {
+    if (bits == 8) {
+        const uint2 w = *reinterpret_cast<const uint2*>(row + 8 * c16);
+        x[0] = (float)(w.x & 0xffu); x[1] = (float)((w.x >> 8) & 0xffu);
+        x[2] = (float)((w.x >> 16) & 0xffu); x[3] = (float)(w.x >> 24);
+        x[4] = (float)(w.y & 0xffu); x[5] = (float)((w.y >> 8) & 0xffu);
+        x[6] = (float)((w.y >> 16) & 0xffu); x[7] = (float)(w.y >> 24);
+    } else {
+        const uint32_t w = *reinterpret_cast<const uint32_t*>(row + 4 * c16);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = (float)((w >> (4 * e)) & 0xfu);
+    }
+}
+__device__ __forceinline__ void load_codes_int(const unsigned char* row, int bits, int c16, int* x) {
+    if (bits == 8) {
+        const uint2 w = *reinterpret_cast<const uint2*>(row + 8 * c16);
+        x[0] = w.x & 0xffu; x[1] = (w.x >> 8) & 0xffu; x[2] = (w.x >> 16) & 0xffu; x[3] = w.x >> 24;
+        x[4] = w.y & 0xffu; x[5] = (w.y >> 8) & 0xffu; x[6] = (w.y >> 16) & 0xffu; x[7] = w.y >> 24;
+    } else {
+        const uint32_t w = *reinterpret_cast<const uint32_t*>(row + 4 * c16);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = (w >> (4 * e)) & 0xfu;
+    }
+}
+
+// ---- outward rounding double -> binary16 ------------------------------------
+__device__ __forceinline__ float float_next_up(float f) {
+    uint32_t u = float_to_bits(f);
+    if ((u & 0x7fffffffu) == 0) return bits_to_float(1u);           // +-0 -> smallest positive
+    return bits_to_float((u & 0x80000000u) ? u - 1 : u + 1);
+}
+__device__ __forceinline__ uint16_t half_next_up(uint16_t h) {
+    if ((h & 0x7fffu) == 0) return 1;
+    return (h & 0x8000u) ? (uint16_t)(h - 1) : (uint16_t)(h + 1);
+}
+// smallest binary16 >= x (x finite), as bits
+__device__ __forceinline__ uint16_t half_ceil_bits(double x) {
+    float f = (float)x;                                              // nearest float
+    if ((double)f < x) f = float_next_up(f);                         // smallest float >= x
+    _Float16 h = (_Float16)f;                                        // nearest half
+    uint16_t hb = __builtin_bit_cast(uint16_t, h);
+    if ((float)h < f) hb = half_next_up(hb);                         // smallest half >= f
+    return hb;
+}
+__device__ __forceinline__ uint16_t half_floor_bits(double x) { return (uint16_t)(half_ceil_bits(-x) ^ 0x8000u); }
+
+// ---------------------------------------------------------------------------
+// abstract of the stored values (paper Sec. 4.3), rounded outward to binary16.
+// scale >= 0, so max over tokens of scale*code+zero = scale*max(code)+zero: the
+// reduction runs on integer codes (exact), one evaluation per channel at the end.
+// ---------------------------------------------------------------------------
+constexpr int kQAbsWaves = 4;
+
+__global__ __launch_bounds__(kQAbsWaves* LEOAM_WAVE) void abstract_build_q_kernel(
+    const unsigned char* __restrict__ kblob, const QChunk* __restrict__ qmeta, const int32_t* __restrict__ chunk_off,
+    const int32_t* __restrict__ n_chunks, uint16_t* __restrict__ abstract, int n_ctx, int c_max, int n_kv_heads) {
+    const int b = blockIdx.z, h = blockIdx.y;
+    const int wave = threadIdx.x / LEOAM_WAVE, lane = lane_id();
+    const int grp = lane >> 4, c16 = lane & 15;
+    const int C = min(max(n_chunks[b], 0), c_max);
+    const int32_t* off = chunk_off + (size_t)b * (c_max + 1);
+    const size_t bh = (size_t)b * n_kv_heads + h;
+    uint16_t* Abh = abstract + bh * (size_t)c_max * 2 * LEOAM_D;
+
+    for (int c = blockIdx.x * kQAbsWaves + wave; c < C; c += gridDim.x * kQAbsWaves) {
+        const QChunk m = qmeta[bh * c_max + c];
+        const int t0 = min(max(off[c], 0), n_ctx);
+        const int t1 = min(max(off[c + 1], t0), n_ctx);
+        const int rowb = (m.bits == 8) ? LEOAM_D : LEOAM_D / 2;
+        const unsigned char* base = kblob + m.byte_off;
+        int mx[8], mn[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            mx[e] = -1;
+            mn[e] = 256;
+        }
+        // lane group grp walks rows grp, grp+4, ...; two rows in flight per lane
+        int t = grp;
+        const int n = t1 - t0;
+        for (; t + 4 < n; t += 8) {
+            int x0[8], x1[8];
+            load_codes_int(base + (size_t)t * rowb, m.bits, c16, x0);
+            load_codes_int(base + (size_t)(t + 4) * rowb, m.bits, c16, x1);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                mx[e] = max(mx[e], max(x0[e], x1[e]));
+                mn[e] = min(mn[e], min(x0[e], x1[e]));
+            }
+        }
+        for (; t < n; t += 4) {
+            int x0[8];
+            load_codes_int(base + (size_t)t * rowb, m.bits, c16, x0);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                mx[e] = max(mx[e], x0[e]);
+                mn[e] = min(mn[e], x0[e]);
+            }
+        }
+        // fold the four lane groups: pack (max, 255 - min) into one register per channel pair
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            int v = (mx[e] & 0x1ff) | ((mn[e] & 0x1ff) << 16);
+#pragma unroll
+            for (int msk = 16; msk < LEOAM_WAVE; msk <<= 1) {
+                const int o = __shfl_xor(v, msk, LEOAM_WAVE);
+                const int omx = (o << 23) >> 23, omn = o >> 16;             // 9-bit fields, max may be -1
+                const int vmx = (v << 23) >> 23, vmn = v >> 16;
+                v = (max(vmx, omx) & 0x1ff) | (min(vmn, omn) << 16);
+            }
+            mx[e] = (v << 23) >> 23;
+            mn[e] = v >> 16;
+        }
+        if (grp < 2) {
+            // group 0 writes kmax, group 1 writes kmin: 8 halves = 16 bytes per lane
+            uint32_t w[4];
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+                uint16_t h0, h1;
+                if (n <= 0) {
+                    h0 = h1 = (grp == 0) ? 0xfc00u : 0x7c00u;               // empty chunk: (-inf, +inf)
+                } else if (grp == 0) {
+                    h0 = half_ceil_bits((double)m.scale_k * mx[e] + (double)m.zero_k);
+                    h1 = half_ceil_bits((double)m.scale_k * mx[e + 1] + (double)m.zero_k);
+                } else {
+                    h0 = half_floor_bits((double)m.scale_k * mn[e] + (double)m.zero_k);
+                    h1 = half_floor_bits((double)m.scale_k * mn[e + 1] + (double)m.zero_k);
+                }
+                w[e / 2] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+            }
+            store16(Abh, (((size_t)c * 2 + grp) * LEOAM_D + 8 * c16) * 2, make_uint4(w[0], w[1], w[2], w[3]));
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// sparse decode attention over the compressed store (Eq. 1 over the kept chunks)
+// ---------------------------------------------------------------------------
+constexpr int kQGroups = kAttWaves * 4;            // 16-lane groups per workgroup
+constexpr int kQTile = kQGroups * kAttRows;        // tokens per tile (128)
+constexpr int kQMaxSel = 1024;                     // kept chunks per (b,h) held in LDS
+
+template <int G>
+__global__ __launch_bounds__(kAttThreads) void sparse_attention_q_kernel(
+    const char* __restrict__ q, const unsigned char* __restrict__ kblob, const unsigned char* __restrict__ vblob,
+    const QChunk* __restrict__ qmeta, const int32_t* __restrict__ chunk_off, const int32_t* __restrict__ n_chunks,
+    const int32_t* __restrict__ sel_idx, const int32_t* __restrict__ sel_count, float scale_log2,
+    float* __restrict__ partial, int n_splits, int c_max, int k_max, int n_kv_heads, int n_ctx) {
+    constexpr int EPL = 8;
+    __shared__ long long ch_off[kQMaxSel];
+    __shared__ float4 ch_par[kQMaxSel];            // scale_k, zero_k, scale_v, zero_v
+    __shared__ int32_t ch_bits[kQMaxSel];
+    __shared__ int32_t prefix[kQMaxSel + 1];
+    __shared__ int32_t tok_k[kQTile], tok_o[kQTile];   // kept-list position -> (chunk slot, token inside chunk)
+    __shared__ float xw[kAttWaves][G][kPartStride];
+    __shared__ int32_t sh_total;
+
+    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid / LEOAM_WAVE;
+    const int grp = lane >> 4, c16 = lane & 15;
+    const size_t bh = (size_t)b * n_kv_heads + h;
+    const int C = min(max(n_chunks[b], 0), c_max);
+    const int cnt = min(min(max(sel_count[bh], 0), k_max), kQMaxSel);
+    const int32_t* off = chunk_off + (size_t)b * (c_max + 1);
+    const int32_t* sel = sel_idx + bh * (size_t)k_max;
+
+    for (int i = tid; i < cnt; i += kAttThreads) {
+        const int id = sel[i];
+        int sz = 0;
+        QChunk m = {0, 8, 0.f, 0.f, 0.f, 0.f, 0};
+        if (id >= 0 && id < C) {
+            const int t0 = min(max(off[id], 0), n_ctx);
+            sz = min(max(off[id + 1], t0), n_ctx) - t0;
+            m = qmeta[bh * c_max + id];
+        }
+        ch_off[i] = m.byte_off;
+        ch_bits[i] = m.bits;
+        ch_par[i] = make_float4(m.scale_k, m.zero_k, m.scale_v, m.zero_v);
+        prefix[i + 1] = sz;
+    }
+    if (tid == 0) prefix[0] = 0;
+    __syncthreads();
+    if (wave == 0) {
+        const int per = (cnt + LEOAM_WAVE - 1) / LEOAM_WAVE;
+        const int i0 = 1 + lane * per, i1 = min(cnt + 1, i0 + per);
+        int s = 0;
+        for (int i = i0; i < i1; ++i) s += prefix[i];
+        int incl = s;
+#pragma unroll
+        for (int d = 1; d < LEOAM_WAVE; d <<= 1) {
+            const int o = __shfl_up(incl, d, LEOAM_WAVE);
+            if (lane >= d) incl += o;
+        }
+        int run = incl - s;
+        for (int i = i0; i < i1; ++i) {
+            run += prefix[i];
+            prefix[i] = run;
+        }
+        if (lane == LEOAM_WAVE - 1) sh_total = incl;
+    }
+    __syncthreads();
+    const int total = sh_total;
+    int per_split = (total + n_splits - 1) / n_splits;
+    per_split = ((per_split + kQTile - 1) / kQTile) * kQTile;
+    const int r0 = min(total, split * per_split), r1 = min(total, r0 + per_split);
+
+    // queries (fp16): this lane's 8 channels, pre-multiplied by scale*log2(e); and sum_d of them per head
+    float qs[G][EPL], qsum[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const size_t qrow = ((size_t)b * n_kv_heads * G + (size_t)h * G + g) * (LEOAM_D * 2);
+        float x[EPL];
+        unpack<F16>(load16(q, qrow + 16 * c16), x);
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+            qs[g][e] = x[e] * scale_log2;
+            s += qs[g][e];
+        }
+        qsum[g] = row16_sum(s);
+    }
+
+    float m_run[G], l_run[G], accz[G], acc[G][EPL];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        m_run[g] = -INFINITY;
+        l_run[g] = 0.f;
+        accz[g] = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+    }
+
+    for (int tb = r0; tb < r1; tb += kQTile) {
+        __syncthreads();
+        for (int i = tid; i < kQTile; i += kAttThreads) {
+            const int x = tb + i;
+            int k = -1, o = 0;
+            if (x < r1) {
+                int lo = 0, hi = cnt;          // largest k with prefix[k] <= x
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (prefix[mid] <= x) lo = mid; else hi = mid;
+                }
+                k = lo;
+                o = x - prefix[lo];
+            }
+            tok_k[i] = k;
+            tok_o[i] = o;
+        }
+        __syncthreads();
+
+        float z[kAttRows][G], vx[kAttRows][EPL], sv[kAttRows], zv[kAttRows];
+        float mt[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) mt[g] = m_run[g];
+#pragma unroll
+        for (int j = 0; j < kAttRows; ++j) {
+            const int slot = j * kQGroups + wave * 4 + grp;
+            const int k = tok_k[slot];
+            const int kk = max(k, 0);
+            const int bits = ch_bits[kk];
+            const float4 par = ch_par[kk];
+            const size_t rowoff = (size_t)ch_off[kk] + (size_t)tok_o[slot] * (bits == 8 ? LEOAM_D : LEOAM_D / 2);
+            float kx[EPL];
+            load_codes(kblob + rowoff, bits, c16, kx);
+            load_codes(vblob + rowoff, bits, c16, vx[j]);
+            sv[j] = par.z;
+            zv[j] = par.w;
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                float d = 0.f;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) d = fmaf(qs[g][e], kx[e], d);
+                d = row16_sum(d);
+                z[j][g] = (k >= 0) ? fmaf(par.x, d, par.y * qsum[g]) : -INFINITY;
+                mt[g] = fmaxf(mt[g], z[j][g]);
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float corr = exp2_or_zero(m_run[g], mt[g]);
+            m_run[g] = mt[g];
+            l_run[g] *= corr;
+            accz[g] *= corr;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[g][e] *= corr;
+        }
+#pragma unroll
+        for (int j = 0; j < kAttRows; ++j) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float p = exp2_or_zero(z[j][g], m_run[g]);
+                l_run[g] += p;
+                accz[g] = fmaf(p, zv[j], accz[g]);
+                const float ps = p * sv[j];
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(ps, vx[j][e], acc[g][e]);
+            }
+        }
+    }
+    // the zero-point share is the same for every channel: fold it in, then merge as usual
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] += accz[g];
+
+#pragma unroll
+    for (int msk = 16; msk < LEOAM_WAVE; msk <<= 1) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float m_o = shfl_xor_f(m_run[g], msk);
+            const float l_o = shfl_xor_f(l_run[g], msk);
+            const float m_n = fmaxf(m_run[g], m_o);
+            const bool low = (lane & msk) == 0;
+            const float a_self = exp2_or_zero(m_run[g], m_n), a_oth = exp2_or_zero(m_o, m_n);
+            l_run[g] = low ? (l_run[g] * a_self + l_o * a_oth) : (l_o * a_oth + l_run[g] * a_self);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+                const float o = shfl_xor_f(acc[g][e], msk);
+                acc[g][e] = low ? (acc[g][e] * a_self + o * a_oth) : (o * a_oth + acc[g][e] * a_self);
+            }
+            m_run[g] = m_n;
+        }
+    }
+    if (grp == 0) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) xw[wave][g][c16 * EPL + e] = acc[g][e];
+            if (lane == 0) {
+                xw[wave][g][LEOAM_D] = m_run[g];
+                xw[wave][g][LEOAM_D + 1] = l_run[g];
+            }
+        }
+    }
+    finish_split<G>(xw, partial, b, h, split, n_splits, n_kv_heads);
+}
+
+int attention_q_max_sel() { return kQMaxSel; }
+
+hipError_t abstract_build_q_dispatch(const leoam_shape* s, const void* kblob, const void* qmeta,
+                                     const int32_t* chunk_off, const int32_t* n_chunks, void* abstract,
+                                     hipStream_t stream) {
+    int gx = (s->c_max + kQAbsWaves - 1) / kQAbsWaves;
+    if (gx > 8192) gx = 8192;
+    dim3 grid(gx, s->n_kv_heads, s->batch);
+    hipLaunchKernelGGL(abstract_build_q_kernel, grid, dim3(kQAbsWaves * LEOAM_WAVE), 0, stream,
+                       (const unsigned char*)kblob, (const QChunk*)qmeta, chunk_off, n_chunks, (uint16_t*)abstract,
+                       s->n_ctx, s->c_max, s->n_kv_heads);
+    return hipGetLastError();
+}
+
+hipError_t attention_q_dispatch(const leoam_shape* s, const void* q, const void* K, const void* V, const void* qmeta,
+                                const int32_t* chunk_off, const int32_t* n_chunks, const int32_t* sel_idx,
+                                const int32_t* sel_count, float scale, float* out, float* lse, float* ws, int n_splits,
+                                hipStream_t stream) {
+    dim3 grid(n_splits, s->n_kv_heads, s->batch);
+#define LEOAM_ATTQ(GG)                                                                                                  \
+    hipLaunchKernelGGL((sparse_attention_q_kernel<GG>), grid, dim3(kAttThreads), 0, stream, (const char*)q,            \
+                       (const unsigned char*)K, (const unsigned char*)V, (const QChunk*)qmeta, chunk_off, n_chunks,     \
+                       sel_idx, sel_count, scale * kLog2e, ws, n_splits, s->c_max, s->k_max, s->n_kv_heads, s->n_ctx)
+    switch (s->n_q_heads / s->n_kv_heads) {
+    case 1: LEOAM_ATTQ(1); break;
+    case 2: LEOAM_ATTQ(2); break;
+    case 4: LEOAM_ATTQ(4); break;
+    default: LEOAM_ATTQ(8); break;
+    }
+#undef LEOAM_ATTQ
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_attention_merge(s, ws, n_splits, out, lse, stream);
+}
+
+}  // namespace leoam

@@ -12,94 +12,71 @@
 // order, so results do not depend on scheduling.
 #include <type_traits>
 
-#include "leoam_dev.h"
+#include "attention_common.h"
 
 namespace leoam {
 
-constexpr int kAttWaves = 4;
-constexpr int kAttThreads = kAttWaves * LEOAM_WAVE;
-constexpr int kAttRows = 8;            // rows per lane group per tile
-constexpr int kAttMaxSplits = 256;
-constexpr int kAttMaxSel = 8192;       // kept chunks per (b,h) the kernel can index
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
-
-__device__ __forceinline__ float exp2_or_zero(float x, float m) {
-    // 2^(x - m), with 2^(-inf - anything) = 0 also when m is -inf
-    return (x == -INFINITY) ? 0.f : exp2f(x - m);
-}
-
-// floats per partial: D accumulators + m + l
-constexpr int kPartStride = LEOAM_D + 2;
-
-
-// Cross-wave combine of the workgroup's online-softmax states into the partial
-// of this split.  xw[w][g] = (acc[D], m, l) of wave w, head g, log2 domain.
-// (Combining the splits in the same launch would need a device-scope release /
-// acquire per workgroup; on this part that is an L2 write-back and invalidate
-// per fence and costs far more than the small second kernel below.)
-template <int G>
-__device__ __forceinline__ void finish_split(float (*xw)[G][kPartStride], float* __restrict__ partial, int b, int h,
-                                             int split, int n_splits, int n_kv_heads) {
-    const int tid = threadIdx.x;
-    const size_t bh = (size_t)b * n_kv_heads + h;
-    __syncthreads();
-    float* part = partial + bh * G * (size_t)n_splits * kPartStride;
-    for (int i = tid; i < G * kPartStride; i += kAttThreads) {
-        const int g = i / kPartStride, d = i % kPartStride;
-        float m = -INFINITY;
-#pragma unroll
-        for (int w = 0; w < kAttWaves; ++w) m = fmaxf(m, xw[w][g][LEOAM_D]);
-        float v = 0.f;
-        if (d == LEOAM_D) {
-            v = m;
-        } else {
-#pragma unroll
-            for (int w = 0; w < kAttWaves; ++w) {
-                const float a = exp2_or_zero(xw[w][g][LEOAM_D], m);
-                v += a * (d < LEOAM_D ? xw[w][g][d] : xw[w][g][LEOAM_D + 1]);
-            }
-        }
-        part[((size_t)g * n_splits + split) * kPartStride + d] = v;
-    }
-}
-
-// out[b,j,:] = sum_s 2^(m_s - m) o_s / sum_s 2^(m_s - m) l_s, splits in index
-// order.  One workgroup per (b, query head); every load is issued before any is
-// used, so the kernel costs one memory round trip.
-constexpr int kMergeMaxSplits = 16;      // splits handled per register batch
-__global__ __launch_bounds__(LEOAM_D) void attention_merge_kernel(const float* __restrict__ partial, int n_splits,
-                                                                 float* __restrict__ out, float* __restrict__ lse) {
+// out[b,j,:] = sum_s 2^(m_s - m) o_s / sum_s 2^(m_s - m) l_s.  One workgroup per
+// (b, query head): kMergeParts thread rows take the splits round-robin, each
+// issues all of its loads before using any (one memory round trip for up to
+// kMergeParts*kMergeBatch splits), and the rows are then folded in a fixed order.
+constexpr int kMergeParts = 4;
+constexpr int kMergeBatch = 16;
+__global__ __launch_bounds__(LEOAM_D* kMergeParts) void attention_merge_kernel(const float* __restrict__ partial,
+                                                                               int n_splits, float* __restrict__ out,
+                                                                               float* __restrict__ lse) {
+    __shared__ float sm[kMergeParts], sl[kMergeParts][LEOAM_D], so[kMergeParts][LEOAM_D];
     const size_t bj = blockIdx.x;
-    const int d = threadIdx.x;
-    const float* part = partial + bj * (size_t)n_splits * kPartStride;
+    const int d = threadIdx.x % LEOAM_D, part = threadIdx.x / LEOAM_D;
+    const float* base = partial + bj * (size_t)n_splits * kPartStride;
     float m = -INFINITY, o = 0.f, l = 0.f;
-    for (int s0 = 0; s0 < n_splits; s0 += kMergeMaxSplits) {
-        float ms[kMergeMaxSplits], ls[kMergeMaxSplits], os[kMergeMaxSplits];
+    for (int s0 = part; s0 < n_splits; s0 += kMergeParts * kMergeBatch) {
+        float ms[kMergeBatch], ls[kMergeBatch], os[kMergeBatch];
 #pragma unroll
-        for (int i = 0; i < kMergeMaxSplits; ++i) {
-            const int s = s0 + i;
+        for (int i = 0; i < kMergeBatch; ++i) {
+            const int s = s0 + i * kMergeParts;
             const bool ok = s < n_splits;
-            ms[i] = ok ? part[(size_t)s * kPartStride + LEOAM_D] : -INFINITY;
-            ls[i] = ok ? part[(size_t)s * kPartStride + LEOAM_D + 1] : 0.f;
-            os[i] = ok ? part[(size_t)s * kPartStride + d] : 0.f;
+            const float* p = base + (size_t)(ok ? s : 0) * kPartStride;      // unconditional loads, masked below
+            ms[i] = p[LEOAM_D];
+            ls[i] = p[LEOAM_D + 1];
+            os[i] = p[d];
+            if (!ok) {
+                ms[i] = -INFINITY;
+                ls[i] = 0.f;
+                os[i] = 0.f;
+            }
         }
         float mb = m;
 #pragma unroll
-        for (int i = 0; i < kMergeMaxSplits; ++i) mb = fmaxf(mb, ms[i]);
+        for (int i = 0; i < kMergeBatch; ++i) mb = fmaxf(mb, ms[i]);
         const float c = exp2_or_zero(m, mb);
         o *= c;
         l *= c;
         m = mb;
 #pragma unroll
-        for (int i = 0; i < kMergeMaxSplits; ++i) {
+        for (int i = 0; i < kMergeBatch; ++i) {
             const float a = exp2_or_zero(ms[i], m);
             o += a * os[i];
             l += a * ls[i];
         }
     }
-    out[bj * LEOAM_D + d] = (l > 0.f) ? o / l : 0.f;
-    if (lse && d == 0) lse[bj] = (l > 0.f) ? (m + log2f(l)) * kLn2 : -INFINITY;
+    if (d == 0) sm[part] = m;
+    sl[part][d] = l;
+    so[part][d] = o;
+    __syncthreads();
+    if (part != 0) return;
+    float mm = -INFINITY;
+#pragma unroll
+    for (int p = 0; p < kMergeParts; ++p) mm = fmaxf(mm, sm[p]);
+    float oo = 0.f, ll = 0.f;
+#pragma unroll
+    for (int p = 0; p < kMergeParts; ++p) {
+        const float a = exp2_or_zero(sm[p], mm);
+        oo += a * so[p][d];
+        ll += a * sl[p][d];
+    }
+    out[bj * LEOAM_D + d] = (ll > 0.f) ? oo / ll : 0.f;
+    if (lse && d == 0) lse[bj] = (ll > 0.f) ? (mm + log2f(ll)) * kLn2 : -INFINITY;
 }
 
 template <typename T, int G>
@@ -576,6 +553,13 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_mfma_kernel(
     finish_split<G>(xw, partial, b, h, split, n_splits, n_kv_heads);
 }
 
+hipError_t launch_attention_merge(const leoam_shape* s, const float* partial, int n_splits, float* out, float* lse,
+                                  hipStream_t stream) {
+    hipLaunchKernelGGL(attention_merge_kernel, dim3(s->batch * s->n_q_heads), dim3(LEOAM_D * kMergeParts), 0, stream,
+                       partial, n_splits, out, lse);
+    return hipGetLastError();
+}
+
 static inline size_t part_bytes_per_split(const leoam_shape* s) {
     return (size_t)s->batch * s->n_q_heads * kPartStride * sizeof(float);
 }
@@ -583,7 +567,8 @@ static inline size_t part_bytes_per_split(const leoam_shape* s) {
 int attention_recommended_splits(const leoam_shape* s, int max_tokens) {
     if (max_tokens <= 0 || max_tokens > s->n_ctx) max_tokens = s->n_ctx;
     // smallest range a workgroup takes: one tile per lane group (fp32) / one 16-token tile per wave
-    const int granule = (s->kv_dtype == LEOAM_F32) ? kAttWaves * 2 * kAttRows : kMfmaGranule;
+    const int granule = (s->kv_dtype == LEOAM_F32) ? kAttWaves * 2 * kAttRows
+                        : (s->kv_dtype == LEOAM_Q8Q4) ? kAttWaves * 4 * kAttRows : kMfmaGranule;
     const int by_tokens = (max_tokens + granule - 1) / granule;
     const int units = s->batch * s->n_kv_heads;
     int want = (768 + units - 1) / units;        // about three resident workgroups per compute unit
@@ -617,9 +602,7 @@ static hipError_t launch_attention(const leoam_shape* s, const void* q, const vo
                            n_splits, s->c_max, s->k_max, s->n_kv_heads, s->n_ctx);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(attention_merge_kernel, dim3(s->batch * s->n_q_heads), dim3(LEOAM_D), 0, stream, ws, n_splits, out,
-                       lse);
-    return hipGetLastError();
+    return launch_attention_merge(s, ws, n_splits, out, lse, stream);
 }
 
 template <typename T>
@@ -640,7 +623,12 @@ static hipError_t attention_by_group(const leoam_shape* s, const void* q, const 
 
 int attention_max_sel() { return kAttMaxSel; }
 
-hipError_t attention_dispatch(const leoam_shape* s, const void* q, const void* K, const void* V,
+hipError_t attention_q_dispatch(const leoam_shape* s, const void* q, const void* K, const void* V, const void* qmeta,
+                                const int32_t* chunk_off, const int32_t* n_chunks, const int32_t* sel_idx,
+                                const int32_t* sel_count, float scale, float* out, float* lse, float* ws, int n_splits,
+                                hipStream_t stream);      // quant_store.hip
+
+hipError_t attention_dispatch(const leoam_shape* s, const void* q, const void* K, const void* V, const void* qmeta,
                               const int32_t* chunk_off, const int32_t* n_chunks, const int32_t* sel_idx,
                               const int32_t* sel_count, float scale, float* out, float* lse, void* workspace,
                               size_t workspace_bytes, hipStream_t stream) {
@@ -650,6 +638,9 @@ hipError_t attention_dispatch(const leoam_shape* s, const void* q, const void* K
     const int n_splits = (int)n;
     void* ws = workspace;
     switch (s->kv_dtype) {
+    case LEOAM_Q8Q4:
+        return attention_q_dispatch(s, q, K, V, qmeta, chunk_off, n_chunks, sel_idx, sel_count, scale, out, lse, (float*)ws,
+                                    n_splits, stream);
     case LEOAM_F32:
         return attention_by_group<F32>(s, q, K, V, chunk_off, n_chunks, sel_idx, sel_count, scale, out, lse, ws, n_splits, stream);
     case LEOAM_F16:
