@@ -31,6 +31,7 @@ RESIDENT = {
     "c1": list(range(32)),
     "c2": list(range(32)),
     "c3": [0, 1, 2, 7, 15, 23, 30, 31],
+    "c4": [0, 1, 2, 7, 15, 23, 30, 31],      # compressed store (8-bit / 4-bit chunks), 512K context
 }
 ELEM = {"f32": 4, "f16": 2, "bf16": 2}
 
@@ -47,16 +48,28 @@ def parse():
     return ap.parse_args()
 
 
-def algorithmic_bytes(layer, case, elem):
-    """Bytes one layer-step has to move, by part (see module docstring)."""
-    import torch
+def algorithmic_bytes(layer, case, elem, four_bit=None):
+    """Bytes one layer-step has to move, by part (see module docstring).  With a
+    compressed store (four_bit[b,c] given) a kept token costs 2*128 or 2*64 bytes
+    and a kept chunk its 32-byte record; abstracts and q are fp16."""
+    import numpy as np
     hkv, d, g = case.hkv, case.d, case.g
     chunks = int(case.n_chunks.sum().item()) * hkv                  # (b,h,c) triples
     kept_tokens = int(layer.sel_tokens.sum().item())                # over (b,h)
+    kv = kept_tokens * 2 * d * elem
+    if four_bit is not None:
+        elem = 2
+        sel = layer.sel_idx.cpu().numpy()
+        sizes = np.diff(case.chunk_off.cpu().numpy().astype(np.int64), axis=1)
+        kv = 0
+        for b in range(sel.shape[0]):
+            for h in range(sel.shape[1]):
+                ids = sel[b, h][sel[b, h] >= 0]
+                kv += int((sizes[b, ids] * np.where(four_bit[b, ids], d, 2 * d)).sum()) + 32 * len(ids)
     parts = {
         "abstract": chunks * 2 * d * elem,
         "score_wr_rd": chunks * 4 * 2,
-        "kv": kept_tokens * 2 * d * elem,
+        "kv": kv,
         "q_out": case.batch * case.hq * d * (elem + 4),
     }
     parts["total"] = sum(parts.values())
@@ -113,11 +126,22 @@ def main():
     elem = ELEM[cfg["dtype"]]
 
     t0 = time.time()
-    layers, cases = [], []
+    layers, cases, tags = [], [], []
+    quant = args.workload == "c4"
     for lid in layer_ids:
-        case = gen.make_case(args.workload, layer=lid, device="cuda")
-        lay = L.DecodeLayer(case.K, case.V, case.chunk_off, case.n_chunks, case.hq, case.k_max, case.max_chunks,
-                            case.token_budget)
+        if quant:
+            qc = gen.make_quant_case("c4", layer=lid, device="cuda")
+            case = qc.case
+            lay = L.DecodeLayer(qc.kblob, qc.vblob, case.chunk_off, case.n_chunks, case.hq, case.k_max,
+                                case.max_chunks, case.token_budget, qmeta=qc.qmeta, n_kv_heads=case.hkv,
+                                n_ctx=case.n_ctx)
+            case.K = case.V = None          # only the compressed store stays resident
+            tags.append(qc.four_bit)
+        else:
+            case = gen.make_case(args.workload, layer=lid, device="cuda")
+            lay = L.DecodeLayer(case.K, case.V, case.chunk_off, case.n_chunks, case.hq, case.k_max, case.max_chunks,
+                                case.token_budget)
+            tags.append(None)
         layers.append(lay)
         cases.append(case)
     torch.cuda.synchronize()
@@ -129,8 +153,8 @@ def main():
         for lay in layers:
             lay.build_abstract()
     ab_ms = time_calls(build_all, 2, torch)
-    k_bytes = sum(c.K.numel() * elem for c in cases)
-    ab_out_bytes = sum(int(c.n_chunks.sum().item()) * c.hkv * 2 * c.d * elem for c in cases)
+    k_bytes = sum(lay.K.numel() * lay.K.element_size() for lay in layers)
+    ab_out_bytes = sum(lay.abstract.numel() * lay.abstract.element_size() for lay in layers)
 
     # ---- the timed step ----------------------------------------------------------
     def step():
@@ -148,7 +172,7 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     us_per_layer = ms_per_step * 1e3 / len(layers)
 
-    parts = [algorithmic_bytes(lay, case, elem) for lay, case in zip(layers, cases)]
+    parts = [algorithmic_bytes(lay, case, elem, fb) for lay, case, fb in zip(layers, cases, tags)]
     step_bytes = sum(p["total"] for p in parts)
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
@@ -165,7 +189,7 @@ def main():
     def only_attention():
         for lay, case in zip(layers, cases):
             B.sparse_chunk_attention_decode(lay.shape, case.q, lay.K, lay.V, lay.chunk_off, lay.n_chunks, lay.sel_idx,
-                                            lay.sel_count, lay.scale, lay.out, lay.lse, lay.workspace)
+                                            lay.sel_count, lay.scale, lay.out, lay.lse, lay.workspace, None, lay.qmeta)
 
     nl = len(layers)
     score_us = time_calls(only_score, args.kernel_reps, torch) * 1e3 / nl
@@ -198,11 +222,11 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": cfg["dtype"],
+        "dtype": "u8/u4 codes, f32 accumulate" if quant else cfg["dtype"],
         "data": "synthetic",
         "config": {
             "workload": f"{args.workload}: batch {cfg['batch']}, {cfg['hq']} q / {cfg['hkv']} kv heads, head_dim 128, "
-                        f"ctx {cfg['n_ctx']}, {cfg['dtype']} K/V, token budget {cfg['token_budget']}",
+                        f"ctx {cfg['n_ctx']}, {'8-bit/4-bit compressed' if quant else cfg['dtype']} K/V, token budget {cfg['token_budget']}",
             "resident_layers": layer_ids,
             "layer_steps_per_step": nl,
             "bytes_per_layer_step": int(step_bytes / nl),
@@ -235,19 +259,26 @@ def main():
         import oracle
         lay, case = layers[0], cases[0]
         nseq = min(case.batch, 4)
-        Kc, Vc, qc = case.K[:nseq].cpu(), case.V[:nseq].cpu(), case.q[:nseq].cpu()
+        qc = case.q[:nseq].cpu()
         off, nc = case.chunk_off[:nseq].cpu(), case.n_chunks[:nseq].cpu()
-        ab = np.nan_to_num(oracle.abstract_build(Kc, off, nc))          # prefill-time, not timed
+        if quant:
+            kb, vb, qm = lay.K.cpu(), lay.V.cpu(), lay.qmeta.cpu()
+            ab = np.nan_to_num(oracle.abstract_build_q(kb, qm, off, nc))   # prefill-time, not timed
+        else:
+            Kc, Vc = case.K[:nseq].cpu(), case.V[:nseq].cpu()
+            ab = np.nan_to_num(oracle.abstract_build(Kc, off, nc))      # prefill-time, not timed
         reps, cpu_s = 0, 0.0
         while reps < 3 or (cpu_s < 10.0 and reps < 200):
             t = time.perf_counter()
             ub = oracle.chunk_score(qc, ab, nc)
             sel, cnt, tok = oracle.topk_select(ub, off, nc, case.max_chunks, case.token_budget, case.k_max)
-            oracle.sparse_attention(qc, Kc, Vc, off, sel, cnt)
+            if quant:
+                oracle.sparse_attention_q(qc, kb, vb, qm, off, sel, cnt)
+            else:
+                oracle.sparse_attention(qc, Kc, Vc, off, sel, cnt)
             cpu_s += time.perf_counter() - t
             reps += 1
-        sample_bytes = (int(nc.sum()) * case.hkv * (2 * case.d * elem + 8) + int(tok.sum()) * 2 * case.d * elem
-                        + nseq * case.hq * case.d * (elem + 4))
+        sample_bytes = parts[0]["total"] * nseq // case.batch
         out["cpu_baseline"] = {
             "value": round(sample_bytes / (cpu_s / reps) / 1e9, 3),
             "unit": "GB/s",
