@@ -7,11 +7,14 @@
 // the order, it is described by one threshold key T: every chunk with key > T is
 // kept, chunks with key == T are kept in index order while they fit, everything
 // below is dropped.  T is found by a radix descent over the 32-bit order-
-// preserving image of the float score: each pass histograms (count, tokens) of
-// the chunks still in range into 256 equal sub-ranges, a single wave walks the
-// histogram from the top and picks the sub-range in which the running totals
-// stop fitting, and the range shrinks by 2^8.  At most four passes.  All integer
-// work, exact, no ordering ambiguity.
+// preserving image of the float score: a pass histograms (count, tokens) of the
+// chunks still in range into 256 equal sub-ranges of the live key range (LDS,
+// one packed 64-bit atomic per chunk), one wave walks the histogram from the top
+// and picks the sub-range in which the running totals stop fitting.  As soon as
+// that sub-range holds at most 1024 chunks (normally after the first pass) they
+// are ranked pairwise, the n*n comparisons spread over the workgroup; a single
+// key shared by more chunks than that falls back to a scan in index order.  All
+// integer work, exact, no ordering ambiguity.
 //
 // One workgroup of 1024 lanes per (sequence, kv head); every lane keeps kIpt
 // consecutive chunks in registers, so "ascending chunk index" is "lane order".
@@ -99,7 +102,15 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(
     const int c0 = tid * kIpt;
     uint32_t kmin = 0xffffffffu, kmaxv = 0;
     uint64_t mine = 0;
-    int prev = (c0 < C) ? min(max(off[c0], 0), n_ctx) : 0;
+    // (loads are unconditional and clamped to the buffers, not to n_chunks: a load under a
+    // condition would be waited for on its own, one memory round trip per chunk)
+    int offv[kIpt + 1];
+    float sc[kIpt];
+#pragma unroll
+    for (int i = 0; i <= kIpt; ++i) offv[i] = off[min(c0 + i, c_max)];
+#pragma unroll
+    for (int i = 0; i < kIpt; ++i) sc[i] = srow[min(c0 + i, c_max - 1)];
+    int prev = min(max(offv[0], 0), n_ctx);
 #pragma unroll
     for (int i = 0; i < kIpt; ++i) {
         const int c = c0 + i;
@@ -107,10 +118,10 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(
         key[i] = 0;
         size[i] = 0;
         if (valid[i]) {
-            const int nxt = min(max(off[c + 1], prev), n_ctx);
+            const int nxt = min(max(offv[i + 1], prev), n_ctx);
             size[i] = (uint32_t)(nxt - prev);
             prev = nxt;
-            key[i] = order_key(srow[c]);
+            key[i] = order_key(sc[i]);
             kmin = min(kmin, key[i]);
             kmaxv = max(kmaxv, key[i]);
             mine += pack_tot(1, size[i]);
