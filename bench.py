@@ -189,12 +189,19 @@ def main():
     def only_attention():
         for lay, case in zip(layers, cases):
             B.sparse_chunk_attention_decode(lay.shape, case.q, lay.K, lay.V, lay.chunk_off, lay.n_chunks, lay.sel_idx,
-                                            lay.sel_count, lay.scale, lay.out, lay.lse, lay.workspace, None, lay.qmeta)
+                                            lay.sel_count, lay.scale, lay.out, lay.lse, lay.att_workspace, None, lay.qmeta)
+
+    def only_select_attention():
+        for lay, case in zip(layers, cases):
+            B.chunk_select_attention_decode(lay.shape, lay.score, case.q, lay.K, lay.V, lay.chunk_off, lay.n_chunks,
+                                            lay.max_chunks, lay.token_budget, lay.scale, lay.sel_idx, lay.sel_count,
+                                            lay.sel_tokens, lay.out, lay.lse, lay.workspace, None, lay.qmeta)
 
     nl = len(layers)
     score_us = time_calls(only_score, args.kernel_reps, torch) * 1e3 / nl
     select_us = time_calls(only_select, args.kernel_reps, torch) * 1e3 / nl
     attn_us = time_calls(only_attention, args.kernel_reps, torch) * 1e3 / nl
+    fused_us = time_calls(only_select_attention, args.kernel_reps, torch) * 1e3 / nl
     kv_bytes = sum(p["kv"] + p["q_out"] for p in parts) / nl
     abs_bytes = sum(p["abstract"] + p["score_wr_rd"] // 2 for p in parts) / nl
     attn_gbs = kv_bytes / (attn_us * 1e-6) / 1e9
@@ -234,7 +241,8 @@ def main():
             "chunks_per_layer_step": int(sum(p["chunks"] for p in parts) / nl),
         },
         "kernels_us_per_layer_step": {"chunk_score": round(score_us, 2), "chunk_topk_select": round(select_us, 2),
-                                      "sparse_chunk_attention_decode": round(attn_us, 2)},
+                                      "sparse_chunk_attention_decode": round(attn_us, 2),
+                                      "chunk_select_attention_decode": round(fused_us, 2)},
         "roofline": {
             "kernel": "sparse_attention_kernel (+ merge)",
             "bound": "hbm",

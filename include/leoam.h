@@ -11,6 +11,7 @@
  *   chunk_topk_select              Sec. 4.2 / 6.1: order chunks by upper bound,
  *                                  keep the front of the list under a budget.
  *   sparse_chunk_attention_decode  Sec. 2.1 Eq. (1) over the kept chunks only.
+ *   chunk_select_attention_decode  the last two steps in one launch.
  *
  * Conventions (all entry points)
  *   - Every pointer except `const leoam_shape*` is a DEVICE pointer owned by the
@@ -162,6 +163,38 @@ int sparse_chunk_attention_decode(const leoam_shape* shape, const void* q, const
                                   const void* qmeta, const int32_t* chunk_off, const int32_t* n_chunks, const int32_t* sel_idx,
                                   const int32_t* sel_count, float softmax_scale, float* out, float* lse,
                                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * chunk_topk_select followed by sparse_chunk_attention_decode (Sec. 4.2 / 6.1,
+ * then Sec. 2.1 Eq. (1) over the kept chunks; Sec. 4.1: the evaluation result
+ * selects the KV the decoding computation uses), with the same arguments,
+ * outputs and preconditions as those two calls.  For fp16 / bf16 K and V with
+ * group size <= 4, k_max <= 2048 and c_max <= 8192 both steps run in a single
+ * kernel: every workgroup selects for its (b,h), keeps the kept chunks' token
+ * ranges on chip and streams its share of the kept tokens; workgroups that share
+ * a (b,h) combine their partials in the same launch, in split order, so results
+ * do not depend on scheduling.  Other shapes run the two kernels of the separate
+ * calls back to back.  sel_idx / sel_count / sel_tokens are written as by
+ * chunk_topk_select.
+ * Workspace: leoam_fused_workspace_bytes() bytes, 16-byte aligned.  Its first
+ * 4 * batch * n_kv_heads bytes (rounded up to 256) are arrival counters: they
+ * must be ZERO when the call is issued and are zero again when it completes, so
+ * a workspace is cleared once (leoam_workspace_init) and then reused; the rest
+ * needs no initialisation.  A smaller workspace gives fewer splits.  Calls that
+ * share a workspace must not overlap.
+ */
+int chunk_select_attention_decode(const leoam_shape* shape, const float* score_ub, const void* q, const void* K,
+                                  const void* V, const void* qmeta, const int32_t* chunk_off, const int32_t* n_chunks,
+                                  int32_t max_chunks, int32_t token_budget, float softmax_scale, int32_t* sel_idx,
+                                  int32_t* sel_count, int32_t* sel_tokens, float* out, float* lse, void* workspace,
+                                  size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace chunk_select_attention_decode wants when at most
+ * `max_tokens` tokens are kept per (b,h) (<= 0: n_ctx).  0 on a bad shape. */
+size_t leoam_fused_workspace_bytes(const leoam_shape* shape, int32_t max_tokens);
+
+/* Zero-fills a workspace (size a multiple of 16, 16-byte aligned) on `stream`. */
+int leoam_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 
 /* Bytes of workspace sparse_chunk_attention_decode wants when at most
  * `max_tokens` tokens are kept per (b,h) (<= 0: n_ctx).  0 on a bad shape. */

@@ -45,15 +45,21 @@ def _load() -> ctypes.CDLL:
     lib.chunk_score.argtypes = [sp, vp, vp, vp, vp, vp, vp]
     lib.chunk_topk_select.argtypes = [sp, vp, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.sparse_chunk_attention_decode.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, sz, vp]
+    lib.chunk_select_attention_decode.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_float, vp, vp, vp,
+                                                  vp, vp, vp, sz, vp]
     lib.leoam_workspace_bytes.argtypes = [sp, i32]
     lib.leoam_workspace_bytes.restype = sz
+    lib.leoam_fused_workspace_bytes.argtypes = [sp, i32]
+    lib.leoam_fused_workspace_bytes.restype = sz
+    lib.leoam_workspace_init.argtypes = [vp, sz, vp]
     lib.leoam_validate_boundaries.argtypes = [sp, vp, vp, vp]
     lib.leoam_copy_probe.argtypes = [vp, vp, sz, vp]
     lib.leoam_status_string.argtypes = [ctypes.c_int]
     lib.leoam_status_string.restype = ctypes.c_char_p
     lib.leoam_version.restype = ctypes.c_int
     for name in ("kv_chunk_abstract_build", "chunk_score", "chunk_topk_select", "sparse_chunk_attention_decode",
-                 "leoam_validate_boundaries", "leoam_copy_probe"):
+                 "chunk_select_attention_decode", "leoam_workspace_init", "leoam_validate_boundaries",
+                 "leoam_copy_probe"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -61,6 +67,7 @@ def _load() -> ctypes.CDLL:
 _lib = _load()
 
 EXPORTS = ("kv_chunk_abstract_build", "chunk_score", "chunk_topk_select", "sparse_chunk_attention_decode",
+           "chunk_select_attention_decode", "leoam_fused_workspace_bytes", "leoam_workspace_init",
            "leoam_workspace_bytes", "leoam_validate_boundaries", "leoam_copy_probe", "leoam_status_string",
            "leoam_version")
 
@@ -123,6 +130,26 @@ def sparse_chunk_attention_decode(shape: Shape, q, K, V, chunk_off, n_chunks, se
                                               _p(sel_idx), _p(sel_count), ctypes.c_float(softmax_scale), _p(out),
                                               _p(lse), _p(workspace), nbytes, _stream(stream)),
            "sparse_chunk_attention_decode")
+
+
+def chunk_select_attention_decode(shape: Shape, score_ub, q, K, V, chunk_off, n_chunks, max_chunks: int,
+                                  token_budget: int, softmax_scale, sel_idx, sel_count, sel_tokens, out, lse, workspace,
+                                  stream=None, qmeta=None) -> None:
+    nbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(_lib.chunk_select_attention_decode(ctypes.byref(shape), _p(score_ub), _p(q), _p(K), _p(V), _p(qmeta),
+                                              _p(chunk_off), _p(n_chunks), int(max_chunks), int(token_budget),
+                                              ctypes.c_float(softmax_scale), _p(sel_idx), _p(sel_count), _p(sel_tokens),
+                                              _p(out), _p(lse), _p(workspace), nbytes, _stream(stream)),
+           "chunk_select_attention_decode")
+
+
+def leoam_fused_workspace_bytes(shape: Shape, max_tokens: int) -> int:
+    return int(_lib.leoam_fused_workspace_bytes(ctypes.byref(shape), int(max_tokens)))
+
+
+def leoam_workspace_init(workspace, stream=None) -> None:
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(_lib.leoam_workspace_init(_p(workspace), nbytes, _stream(stream)), "leoam_workspace_init")
 
 
 def leoam_workspace_bytes(shape: Shape, max_tokens: int) -> int:

@@ -1,6 +1,8 @@
 // Pieces shared by the attention kernels (dense and compressed store): launch
 // constants, the online-softmax helpers and the per-split partial layout.
 #pragma once
+#include <type_traits>
+
 #include "leoam_dev.h"
 
 namespace leoam {
@@ -53,6 +55,34 @@ __device__ __forceinline__ void finish_split(float (*xw)[G][kPartStride], float*
     }
 }
 
+
+// ---- matrix-core pieces of the 16-bit kernels ----------------------------------
+// v_mfma_f32_16x16x32 (bf16 / f16): D[i][j] += sum_k A[i][k] B[k][j], A lane =
+// (i = lane%16, k = 8*(lane/16)..+8), B lane = (j = lane%16, same k), D lane =
+// (j = lane%16, i = 4*(lane/16)..+4).
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+template <typename T> __device__ __forceinline__ f32x4_t mfma_16x16x32(const uint4& a, const uint4& b, f32x4_t c);
+template <> __device__ __forceinline__ f32x4_t mfma_16x16x32<BF16>(const uint4& a, const uint4& b, f32x4_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+template <> __device__ __forceinline__ f32x4_t mfma_16x16x32<F16>(const uint4& a, const uint4& b, f32x4_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+}
+
+// value held by lane kSrc of this lane's 16-lane row
+template <int kSrc> __device__ __forceinline__ float row_bcast(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x150 + kSrc, 0xf, 0xf, true));
+}
+
+template <int kBegin, int kEnd, typename F> __device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (kBegin < kEnd) {
+        f(std::integral_constant<int, kBegin>{});
+        static_for<kBegin + 1, kEnd>(f);
+    }
+}
 
 // host-side launch of the kernel that combines the partials (sparse_attention.hip)
 hipError_t launch_attention_merge(const leoam_shape* s, const float* partial, int n_splits, float* out, float* lse,

@@ -19,6 +19,12 @@ int attention_q_max_sel();
 size_t attention_workspace_bytes(const leoam_shape*, int);
 size_t attention_min_workspace_bytes(const leoam_shape*);
 int attention_max_sel();
+hipError_t select_attention_dispatch(const leoam_shape*, const float*, const void*, const void*, const void*, const void*,
+                                     const int32_t*, const int32_t*, int, int, float, int32_t*, int32_t*, int32_t*,
+                                     float*, float*, void*, size_t, hipStream_t);
+size_t select_attention_workspace_bytes(const leoam_shape*, int);
+size_t select_attention_min_workspace_bytes(const leoam_shape*);
+hipError_t workspace_zero_dispatch(void*, size_t, hipStream_t);
 
 __global__ void copy_probe_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
@@ -102,6 +108,37 @@ int sparse_chunk_attention_decode(const leoam_shape* shape, const void* q, const
     if (((uintptr_t)workspace & 15u) != 0) return LEOAM_E_WORKSPACE;
     return from_hip(attention_dispatch(shape, q, K, V, qmeta, chunk_off, n_chunks, sel_idx, sel_count, softmax_scale, out, lse,
                                        workspace, workspace_bytes, (hipStream_t)stream));
+}
+
+int chunk_select_attention_decode(const leoam_shape* shape, const float* score_ub, const void* q, const void* K,
+                                  const void* V, const void* qmeta, const int32_t* chunk_off, const int32_t* n_chunks,
+                                  int32_t max_chunks, int32_t token_budget, float softmax_scale, int32_t* sel_idx,
+                                  int32_t* sel_count, int32_t* sel_tokens, float* out, float* lse, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!score_ub || !q || !K || !V || !chunk_off || !n_chunks || !sel_idx || !sel_count || !out)
+        return LEOAM_E_INVALID_ARG;
+    if (shape->k_max > attention_max_sel()) return LEOAM_E_UNSUPPORTED;
+    if (shape->kv_dtype == LEOAM_Q8Q4) {
+        if (!qmeta) return LEOAM_E_INVALID_ARG;
+        if (shape->k_max > attention_q_max_sel()) return LEOAM_E_UNSUPPORTED;
+    }
+    if (!workspace || workspace_bytes < select_attention_min_workspace_bytes(shape)) return LEOAM_E_WORKSPACE;
+    if (((uintptr_t)workspace & 15u) != 0) return LEOAM_E_WORKSPACE;
+    return from_hip(select_attention_dispatch(shape, score_ub, q, K, V, qmeta, chunk_off, n_chunks, max_chunks,
+                                              token_budget, softmax_scale, sel_idx, sel_count, sel_tokens, out, lse,
+                                              workspace, workspace_bytes, (hipStream_t)stream));
+}
+
+size_t leoam_fused_workspace_bytes(const leoam_shape* shape, int32_t max_tokens) {
+    if (check_shape(shape)) return 0;
+    return select_attention_workspace_bytes(shape, max_tokens);
+}
+
+int leoam_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+    if (!workspace || (workspace_bytes & 15u) || ((uintptr_t)workspace & 15u)) return LEOAM_E_INVALID_ARG;
+    return from_hip(workspace_zero_dispatch(workspace, workspace_bytes, (hipStream_t)stream));
 }
 
 size_t leoam_workspace_bytes(const leoam_shape* shape, int32_t max_tokens) {

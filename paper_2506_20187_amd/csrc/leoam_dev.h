@@ -102,4 +102,89 @@ __device__ __forceinline__ float row16_sum(float v) {
     return v;
 }
 
+// ---- wave-wide scans and reductions on the DPP data path --------------------------
+// row_shr:n (0x110+n) shifts inside a 16-lane row, row_bcast:15 (0x142) / row_bcast:31
+// (0x143) carry a row's last lane into the following rows; lanes without a source
+// take `kIdentity`.  Six steps give an inclusive scan over the 64 lanes without
+// touching LDS.
+template <int kCtrl, int kRowMask, uint32_t kIdentity> __device__ __forceinline__ uint32_t dpp_or_identity(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)kIdentity, (int)v, kCtrl, kRowMask, 0xf, false);
+}
+
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
+    v += dpp_or_identity<0x111, 0xf, 0u>(v);
+    v += dpp_or_identity<0x112, 0xf, 0u>(v);
+    v += dpp_or_identity<0x114, 0xf, 0u>(v);
+    v += dpp_or_identity<0x118, 0xf, 0u>(v);
+    v += dpp_or_identity<0x142, 0xa, 0u>(v);
+    v += dpp_or_identity<0x143, 0xc, 0u>(v);
+    return v;
+}
+
+// inclusive scan inside every 16-lane row
+__device__ __forceinline__ uint32_t row16_incl_scan_u32(uint32_t v) {
+    v += dpp_or_identity<0x111, 0xf, 0u>(v);
+    v += dpp_or_identity<0x112, 0xf, 0u>(v);
+    v += dpp_or_identity<0x114, 0xf, 0u>(v);
+    v += dpp_or_identity<0x118, 0xf, 0u>(v);
+    return v;
+}
+
+// minimum / maximum over the wave; every lane gets the result
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+    v = min(v, dpp_or_identity<0x111, 0xf, 0xffffffffu>(v));
+    v = min(v, dpp_or_identity<0x112, 0xf, 0xffffffffu>(v));
+    v = min(v, dpp_or_identity<0x114, 0xf, 0xffffffffu>(v));
+    v = min(v, dpp_or_identity<0x118, 0xf, 0xffffffffu>(v));
+    v = min(v, dpp_or_identity<0x142, 0xa, 0xffffffffu>(v));
+    v = min(v, dpp_or_identity<0x143, 0xc, 0xffffffffu>(v));
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, LEOAM_WAVE - 1);
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+    v = max(v, dpp_or_identity<0x111, 0xf, 0u>(v));
+    v = max(v, dpp_or_identity<0x112, 0xf, 0u>(v));
+    v = max(v, dpp_or_identity<0x114, 0xf, 0u>(v));
+    v = max(v, dpp_or_identity<0x118, 0xf, 0u>(v));
+    v = max(v, dpp_or_identity<0x142, 0xa, 0u>(v));
+    v = max(v, dpp_or_identity<0x143, 0xc, 0u>(v));
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, LEOAM_WAVE - 1);
+}
+// minimum / maximum over the first 16 lanes; every lane gets the result
+__device__ __forceinline__ uint32_t row0_min_u32(uint32_t v) {
+    v = min(v, dpp_or_identity<0x111, 0xf, 0xffffffffu>(v));
+    v = min(v, dpp_or_identity<0x112, 0xf, 0xffffffffu>(v));
+    v = min(v, dpp_or_identity<0x114, 0xf, 0xffffffffu>(v));
+    v = min(v, dpp_or_identity<0x118, 0xf, 0xffffffffu>(v));
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 15);
+}
+__device__ __forceinline__ uint32_t row0_max_u32(uint32_t v) {
+    v = max(v, dpp_or_identity<0x111, 0xf, 0u>(v));
+    v = max(v, dpp_or_identity<0x112, 0xf, 0u>(v));
+    v = max(v, dpp_or_identity<0x114, 0xf, 0u>(v));
+    v = max(v, dpp_or_identity<0x118, 0xf, 0u>(v));
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 15);
+}
+
+// ---- sums across the four 16-lane rows -----------------------------------------
+// v_permlane32_swap a, b exchanges a[32..63] with b[0..31]; v_permlane16_swap
+// exchanges rows 1 and 3 of a with rows 0 and 2 of b.  (Written as assembly: the
+// compiler builtins of this toolchain lose the second result.  The s_nop pairs
+// cover the wait states these instructions need after / before other vector ops.)
+__device__ __forceinline__ void permlane32_swap(float& a, float& b) {
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ void permlane16_swap(float& a, float& b) {
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+// For each lane position j = lane % 16, the sums of a, b, c, d over lanes j, j+16,
+// j+32, j+48: row 0 returns a's sum, row 1 c's, row 2 b's, row 3 d's.
+__device__ __forceinline__ float rows_sum4(float a, float b, float c, float d) {
+    permlane32_swap(a, b);
+    float u = a + b;      // rows 0,1: a summed over lanes 32 apart; rows 2,3: b
+    permlane32_swap(c, d);
+    float w = c + d;
+    permlane16_swap(u, w);
+    return u + w;
+}
+
 }  // namespace leoam

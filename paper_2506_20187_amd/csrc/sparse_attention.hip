@@ -297,30 +297,6 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_kernel(
 // 4*grp+0..3, so the weight it needs is a broadcast inside its own 16-lane row
 // (DPP row_newbcast), not a shuffle.
 // ---------------------------------------------------------------------------
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
-typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
-typedef __attribute__((ext_vector_type(4))) float f32x4_t;
-
-template <typename T> __device__ __forceinline__ f32x4_t mfma_16x16x32(const uint4& a, const uint4& b, f32x4_t c);
-template <> __device__ __forceinline__ f32x4_t mfma_16x16x32<BF16>(const uint4& a, const uint4& b, f32x4_t c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
-}
-template <> __device__ __forceinline__ f32x4_t mfma_16x16x32<F16>(const uint4& a, const uint4& b, f32x4_t c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
-}
-
-// value held by lane kSrc of this lane's 16-lane row
-template <int kSrc> __device__ __forceinline__ float row_bcast(float v) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x150 + kSrc, 0xf, 0xf, true));
-}
-
-template <int kBegin, int kEnd, typename F> __device__ __forceinline__ void static_for(F&& f) {
-    if constexpr (kBegin < kEnd) {
-        f(std::integral_constant<int, kBegin>{});
-        static_for<kBegin + 1, kEnd>(f);
-    }
-}
-
 constexpr int kMfmaWaveBlock = 256;                   // tokens a wave maps to rows at a time
 constexpr int kMfmaGranule = kAttWaves * 16;           // a split is a multiple of this many tokens
 

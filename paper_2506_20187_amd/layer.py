@@ -8,7 +8,7 @@ from . import binding as B
 
 class DecodeLayer:
     """Owns abstract / score / selection / output / workspace buffers of one
-    layer and calls the four entry points in the paper's order.  All arithmetic
+    layer and calls the entry points in the paper's order.  All arithmetic
     happens inside libleoam.so."""
 
     def __init__(self, K: torch.Tensor, V: torch.Tensor, chunk_off: torch.Tensor, n_chunks: torch.Tensor,
@@ -35,18 +35,34 @@ class DecodeLayer:
         self.sel_tokens = torch.empty(batch, hkv, dtype=torch.int32, device=dev)
         self.out = torch.empty(batch, n_q_heads, d, dtype=torch.float32, device=dev)
         self.lse = torch.empty(batch, n_q_heads, dtype=torch.float32, device=dev)
-        nbytes = B.leoam_workspace_bytes(self.shape, token_budget)
-        self.workspace = torch.empty(max(16, nbytes), dtype=torch.uint8, device=dev)
+        pad16 = lambda n: (max(16, n) + 15) // 16 * 16
+        # workspace of the one-launch select + attention: starts with arrival counters, zeroed once
+        self.workspace = torch.empty(pad16(B.leoam_fused_workspace_bytes(self.shape, token_budget)), dtype=torch.uint8,
+                                     device=dev)
+        B.leoam_workspace_init(self.workspace)
+        # workspace of the separate attention call (contents irrelevant)
+        self.att_workspace = torch.empty(pad16(B.leoam_workspace_bytes(self.shape, token_budget)), dtype=torch.uint8,
+                                         device=dev)
         self.scale = B.default_scale(d)
 
     def build_abstract(self, stream=None) -> None:
         B.kv_chunk_abstract_build(self.shape, self.K, self.chunk_off, self.n_chunks, self.abstract, stream, self.qmeta)
 
     def step(self, q: torch.Tensor, stream=None) -> torch.Tensor:
+        """score, then selection + attention in one call."""
+        s = self.shape
+        B.chunk_score(s, q, self.abstract, self.n_chunks, self.score, None, stream)
+        B.chunk_select_attention_decode(s, self.score, q, self.K, self.V, self.chunk_off, self.n_chunks, self.max_chunks,
+                                        self.token_budget, self.scale, self.sel_idx, self.sel_count, self.sel_tokens,
+                                        self.out, self.lse, self.workspace, stream, self.qmeta)
+        return self.out
+
+    def step_separate(self, q: torch.Tensor, stream=None) -> torch.Tensor:
+        """The same step through the three separate entry points."""
         s = self.shape
         B.chunk_score(s, q, self.abstract, self.n_chunks, self.score, None, stream)
         B.chunk_topk_select(s, self.score, self.chunk_off, self.n_chunks, self.max_chunks, self.token_budget,
                             self.sel_idx, self.sel_count, self.sel_tokens, None, stream)
         B.sparse_chunk_attention_decode(s, q, self.K, self.V, self.chunk_off, self.n_chunks, self.sel_idx,
-                                        self.sel_count, self.scale, self.out, self.lse, self.workspace, stream, self.qmeta)
+                                        self.sel_count, self.scale, self.out, self.lse, self.att_workspace, stream, self.qmeta)
         return self.out

@@ -230,19 +230,24 @@ def test_attention_ignores_bad_ids(L, oracle):
 # ---------------------------------------------------------------------------
 # whole path on the paper-shaped configs
 # ---------------------------------------------------------------------------
-def run_path(L, case):
-    """abstract -> score -> select -> attention through the C ABI."""
+def run_path(L, case, separate=False):
+    """abstract -> score -> select -> attention through the C ABI; the last two
+    steps either in one call (what bench.py times) or as two calls."""
     layer = L.DecodeLayer(dev(case.K), dev(case.V), dev(case.chunk_off), dev(case.n_chunks), case.hq, case.k_max,
                           case.max_chunks, case.token_budget)
     assert L.leoam_validate_boundaries(layer.shape, layer.chunk_off, layer.n_chunks) == 0
     layer.build_abstract()
-    layer.step(dev(case.q))
+    for buf in (layer.sel_idx, layer.sel_count, layer.sel_tokens):
+        buf.fill_(-7)
+    layer.out.fill_(float("nan"))
+    layer.lse.fill_(float("nan"))
+    (layer.step_separate if separate else layer.step)(dev(case.q))
     torch.cuda.synchronize()
     return layer
 
 
-def check_path(L, oracle, case, seqs=None):
-    layer = run_path(L, case)
+def check_path(L, oracle, case, seqs=None, separate=False):
+    layer = run_path(L, case, separate)
     sl = slice(None) if seqs is None else seqs
     K, V, q = case.K[sl].cpu(), case.V[sl].cpu(), case.q[sl].cpu()
     off, nc = case.chunk_off[sl].cpu(), case.n_chunks[sl].cpu()
@@ -263,42 +268,50 @@ def check_path(L, oracle, case, seqs=None):
     return dict(err=err, tokens=tok, margin=margin)
 
 
-def test_path_c0(L, oracle):
+SEPARATE = pytest.mark.parametrize("separate", [False, True], ids=["one_call", "two_calls"])
+
+
+@SEPARATE
+def test_path_c0(L, oracle, separate):
     case = gen.make_case("c0")
-    res = check_path(L, oracle, case)
+    res = check_path(L, oracle, case, separate=separate)
     assert np.all(res["tokens"] == 512)
 
 
+@SEPARATE
 @pytest.mark.parametrize("layer", [0, 31])
-def test_path_c1_reduced(L, oracle, layer):
+def test_path_c1_reduced(L, oracle, layer, separate):
     case = gen.make_case("c1", layer=layer, n_ctx=8192 + 37, hq=8, hkv=8, token_budget=1024)
-    check_path(L, oracle, case)
+    check_path(L, oracle, case, separate=separate)
 
 
+@SEPARATE
 @pytest.mark.parametrize("layer", [0, 17, 31])
-def test_path_c2_reduced(L, oracle, layer):
+def test_path_c2_reduced(L, oracle, layer, separate):
     case = gen.make_case("c2", layer=layer, n_ctx=16384 + 5, hq=8, hkv=2, token_budget=2048)
-    check_path(L, oracle, case)
+    check_path(L, oracle, case, separate=separate)
 
 
-def test_path_c3_reduced_batch(L, oracle):
+@SEPARATE
+def test_path_c3_reduced_batch(L, oracle, separate):
     case = gen.make_case("c3", layer=9, batch=3, n_ctx=8192 + 100, hq=8, hkv=2, token_budget=1024)
-    check_path(L, oracle, case)
+    check_path(L, oracle, case, separate=separate)
 
 
-def test_path_empty_selection(L, oracle):
+@SEPARATE
+def test_path_empty_selection(L, oracle, separate):
     case = gen.make_case("c2", layer=3, n_ctx=4096, hq=4, hkv=1, token_budget=8)     # every chunk has >= 16 tokens
-    layer = run_path(L, case)
+    layer = run_path(L, case, separate)
     assert int(layer.sel_count.abs().sum()) == 0
     assert torch.all(layer.sel_idx == -1)
     assert torch.all(layer.out == 0) and torch.all(torch.isneginf(layer.lse))
 
 
-@pytest.mark.parametrize("cfg,layer", [("c1", 5), ("c2", 0), ("c2", 31)])
-def test_path_full_size_layer(L, oracle, cfg, layer):
+@pytest.mark.parametrize("cfg,layer,separate", [("c1", 5, False), ("c2", 0, False), ("c2", 31, False), ("c2", 31, True)])
+def test_path_full_size_layer(L, oracle, cfg, layer, separate):
     """One layer at the full shape of the benchmarked configuration, generated in HBM."""
     case = gen.make_case(cfg, layer=layer, device="cuda")
-    check_path(L, oracle, case)
+    check_path(L, oracle, case, separate=separate)
 
 
 def test_path_c3_full_shape_sampled(L, oracle):
@@ -306,6 +319,83 @@ def test_path_c3_full_shape_sampled(L, oracle):
     checks two of the sixteen sequences end to end."""
     case = gen.make_case("c3", layer=30, device="cuda")
     check_path(L, oracle, case, seqs=slice(5, 7))
+
+
+# ---------------------------------------------------------------------------
+# selection + attention in one call
+# ---------------------------------------------------------------------------
+def gpu_select_attend(L, dtype, score, q, K, V, packed, counts, max_chunks, budget, k_max, ws=None, n_splits=None):
+    B, Hkv, N, D = K.shape
+    Hq = q.shape[1]
+    c_max = packed.shape[1] - 1
+    shape = L.make_shape(B, Hq, Hkv, D, N, c_max, k_max, TDT[dtype])
+    sel = torch.full((B, Hkv, k_max), -7, dtype=torch.int32, device="cuda")
+    cnt = torch.full((B, Hkv), -7, dtype=torch.int32, device="cuda")
+    tok = torch.full((B, Hkv), -7, dtype=torch.int32, device="cuda")
+    out = torch.full((B, Hq, D), float("nan"), dtype=torch.float32, device="cuda")
+    lse = torch.full((B, Hq), float("nan"), dtype=torch.float32, device="cuda")
+    if ws is None:
+        nbytes = L.leoam_fused_workspace_bytes(shape, budget)
+        if n_splits is not None:      # counters + room for exactly n_splits partials
+            nbytes = (B * Hkv * 4 + 255) // 256 * 256 + n_splits * B * Hq * (D + 2) * 4
+        ws = torch.empty((nbytes + 15) // 16 * 16, dtype=torch.uint8, device="cuda")
+        L.leoam_workspace_init(ws)
+        head = (B * Hkv * 4 + 255) // 256 * 256
+        ws[head:] = 0xFF               # the partials area needs no initialisation: poison it (NaN patterns)
+    L.chunk_select_attention_decode(shape, dev(score), dev(q), dev(K), dev(V), dev(packed), dev(counts), max_chunks,
+                                    budget, L.default_scale(D), sel, cnt, tok, out, lse, ws)
+    torch.cuda.synchronize()
+    return (sel.cpu().numpy(), cnt.cpu().numpy(), tok.cpu().numpy(), out.cpu().numpy().astype(np.float64),
+            lse.cpu().numpy().astype(np.float64), ws)
+
+
+@pytest.mark.parametrize("dtype,G,C", [("bf16", 4, 700), ("bf16", 4, 3000), ("f16", 1, 1500), ("f16", 2, 6000),
+                                       ("bf16", 2, 300), ("bf16", 1, 40), ("f16", 4, 2047),
+                                       ("f32", 2, 900), ("bf16", 8, 900)])      # last two: shapes that take two launches
+def test_select_attention_one_call(L, oracle, dtype, G, C):
+    rng = np.random.default_rng(1000 + C + G)
+    B, Hkv, D = 2, 2, 128
+    offs = []
+    for b in range(B):
+        n = C if b == 0 else max(1, C - int(rng.integers(0, C // 3 + 1)))
+        sizes = rng.integers(1, 9, size=n)
+        offs.append(np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32))
+    N = int(max(o[-1] for o in offs))
+    offs = [np.concatenate([o[:-1], [N]]).astype(np.int32) for o in offs]
+    packed, counts, c_max = gen.pack_boundaries(offs, N)
+    K = torch.from_numpy(rng.standard_normal((B, Hkv, N, D)).astype(np.float32)).to(TDT[dtype])
+    V = torch.from_numpy(rng.standard_normal((B, Hkv, N, D)).astype(np.float32)).to(TDT[dtype])
+    q = torch.from_numpy(rng.standard_normal((B, Hkv * G, D)).astype(np.float32) * 1.5).to(TDT[dtype])
+    score = (rng.standard_normal((B, Hkv, c_max)) * 20).astype(np.float32)
+    score[:, :, ::5] = np.round(score[:, :, ::5])              # some exact ties
+    k_max = min(c_max, 2048)
+    ws = None
+    for max_chunks, budget, n_splits in ((0, N // 8, None), (0, N // 8, 1), (0, N // 3, 3), (0, N // 3, 3),
+                                         (max(1, C // 9), 0, 5), (0, 1, None), (0, 0, 2), (1, 0, 2)):
+        # the library caps the count at k_max; the oracle takes that cap as max_chunks
+        cap = min(max_chunks, k_max) if max_chunks > 0 else k_max
+        want_sel, want_cnt, want_tok = oracle.topk_select(score, packed, counts, cap, budget, k_max)
+        want_out, want_lse = oracle.sparse_attention(q, K, V, packed, want_sel, want_cnt)
+        sel, cnt, tok, out, lse, ws_used = gpu_select_attend(L, dtype, score, q, K, V, packed, counts, max_chunks, budget,
+                                                             k_max, n_splits=n_splits)
+        tag = f"max_chunks={max_chunks} budget={budget} splits={n_splits}"
+        assert np.array_equal(cnt, want_cnt), tag
+        assert np.array_equal(sel, want_sel), tag
+        assert np.array_equal(tok, want_tok), tag
+        assert np.abs(out - want_out).max() <= TOL[dtype], tag
+        fin = np.isfinite(want_lse)
+        assert np.array_equal(np.isneginf(lse), np.isneginf(want_lse)), tag
+        assert np.abs(lse[fin] - want_lse[fin]).max() <= 1e-4 if fin.any() else True
+        if ws is None:
+            ws = ws_used
+    # the same workspace serves call after call without being cleared again
+    want_sel, want_cnt, want_tok = oracle.topk_select(score, packed, counts, 0, N // 8, k_max)
+    want_out, _ = oracle.sparse_attention(q, K, V, packed, want_sel, want_cnt)
+    for _ in range(3):
+        sel, cnt, tok, out, lse, _ = gpu_select_attend(L, dtype, score, q, K, V, packed, counts, 0, N // 8, k_max, ws=ws)
+        assert np.array_equal(sel, want_sel) and np.abs(out - want_out).max() <= TOL[dtype]
+    head = (B * Hkv * 4 + 255) // 256 * 256
+    assert int(ws[:head].to(torch.int32).sum()) == 0           # counters are back at zero
 
 
 # ---------------------------------------------------------------------------
