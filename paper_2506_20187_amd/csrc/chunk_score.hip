@@ -83,34 +83,37 @@ __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
     const int g0 = blockIdx.x * kScoreWaves + wave;      // this wave's first group of four sets
     fetch(4 * g0, cur);
 
-    // A operands: clamped query values for every step, in double
-    double qa[HS][NSTEP], qb[kLower ? HS : 1][kLower ? NSTEP : 1];
+    // A operands: clamped query values for every step, in double.  They are the same
+    // for the four waves and would take 64 registers per lane, so they live in LDS
+    // (each wave converts a quarter) and are read back step by step: the registers
+    // this frees double the number of waves a compute unit keeps in flight.
+    __shared__ double qa_lds[HS][NSTEP][LEOAM_WAVE];
+    __shared__ double qb_lds[kLower ? HS : 1][kLower ? NSTEP : 1][LEOAM_WAVE];
 #pragma unroll
     for (int s = 0; s < HS; ++s) {
-        const int head = 4 * s + a_head;
-#pragma unroll
-        for (int i = 0; i < NLOAD; ++i) {
+        const int head = min(4 * s + a_head, G - 1);
+        const size_t qrow = ((size_t)b * n_kv_heads * G + (size_t)h * G + head) * ROWB;
+        for (int i = wave; i < NLOAD; i += kScoreWaves) {
             float x[EPL];
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) x[e] = 0.f;
-            if (head < G) {
-                const size_t qrow = ((size_t)b * n_kv_heads * G + (size_t)h * G + head) * ROWB;
-                unpack<T>(load16(q, qrow + 64 * i + 16 * kq), x);
-            }
+            unpack<T>(load16(q, qrow + 64 * i + 16 * kq), x);
 #pragma unroll
             for (int e = 0; e < EPL; ++e) {
-                const float pos = fmaxf(x[e], 0.f), neg = fminf(x[e], 0.f);
-                qa[s][i * EPL + e] = (double)(a_min ? neg : pos);
-                if (kLower) qb[s][i * EPL + e] = (double)(a_min ? pos : neg);
+                const float xe = (4 * s + a_head < G) ? x[e] : 0.f;
+                const float pos = fmaxf(xe, 0.f), neg = fminf(xe, 0.f);
+                qa_lds[s][i * EPL + e][lane] = (double)(a_min ? neg : pos);
+                if (kLower) qb_lds[s][i * EPL + e][lane] = (double)(a_min ? pos : neg);
             }
         }
     }
+    __syncthreads();
+    int q_lane = lane;
 
     // Scores of four consecutive row sets (32 chunks) are collected in one register
     // per lane and written as a single 128-byte line: a store after every set would
     // sit in the same in-order memory counter as the prefetched loads.
     float pend_ub = 0.f, pend_lb = 0.f;
     auto consume = [&](int it, int set, const uint4* v) {
+        asm volatile("" : "+v"(q_lane));      // keeps the LDS reads of the A operands inside this call
         // two interleaved accumulator chains per head pass (even / odd steps)
         double ua[HS][2], la[kLower ? HS : 1][2];
 #pragma unroll
@@ -127,9 +130,9 @@ __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
                 const double xd = (double)x[e];
 #pragma unroll
                 for (int s = 0; s < HS; ++s) {
-                    ua[s][e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[s][i * EPL + e], xd, ua[s][e & 1], 0, 0, 0);
+                    ua[s][e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(qa_lds[s][i * EPL + e][q_lane], xd, ua[s][e & 1], 0, 0, 0);
                     if (kLower)
-                        la[s][e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(qb[s][i * EPL + e], xd, la[s][e & 1], 0, 0, 0);
+                        la[s][e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(qb_lds[s][i * EPL + e][q_lane], xd, la[s][e & 1], 0, 0, 0);
                 }
             }
         }
@@ -193,15 +196,17 @@ __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
 template <typename T, int G>
 static hipError_t launch_score(const leoam_shape* s, const void* q, const void* abstract, const int32_t* n_chunks,
                                float* ub, float* lb, hipStream_t stream) {
-    // about sixteen workgroups per compute unit in total (measured best on MI355X);
-    // every wave still walks several groups of row sets with the next set prefetched
+    // About eighteen workgroups per compute unit in total, so that most waves take a
+    // single group of row sets.  The count per (b,h) is kept odd: with 8, 16 or 32
+    // workgroups per (b,h) the kernel measured 13 % slower on MI355X (the workgroups
+    // that run together then walk the abstract at a power-of-two stride).
     const int sets = (s->c_max + kChunksPerSet - 1) / kChunksPerSet;
     const int units = s->batch * s->n_kv_heads;
-    int gx = (4096 + units - 1) / units;
+    int gx = (4480 + units - 1) / units;
     const int groups = (sets + 3) / 4;                      // a wave works on groups of four sets
     const int gx_max = (groups + kScoreWaves - 1) / kScoreWaves;
     if (gx > gx_max) gx = gx_max;
-    if (gx < 1) gx = 1;
+    gx |= 1;
     dim3 grid(gx, s->n_kv_heads, s->batch), block(kScoreWaves * LEOAM_WAVE);
     if (lb)
         hipLaunchKernelGGL((chunk_score_kernel<T, G, true>), grid, block, 0, stream, (const char*)q,
