@@ -210,6 +210,17 @@ def main():
     attn_gbs = kv_bytes / (fused_us * 1e-6) / 1e9
     score_gbs = abs_bytes / (score_us * 1e-6) / 1e9
 
+    # ---- abstract maintenance for one appended token per sequence (dense stores) ----
+    append_us = None
+    if not quant:
+        lay = layers[0]
+        off2, nc2, ab2 = lay.chunk_off.clone(), (lay.n_chunks - 1).clamp(min=0), lay.abstract.clone()
+        st = torch.empty(lay.shape.batch, dtype=torch.int32, device="cuda")      # last chunk dropped: >= 16 free slots
+        append_us = time_calls(lambda: B.kv_chunk_abstract_append(lay.shape, lay.K, off2, nc2, 1 << 20, ab2, st), 14,
+                               torch) * 1e3
+        assert int(st.abs().sum()) == 0
+        del off2, nc2, ab2
+
     # ---- plain copy of known size: the "what does this box stream" reference ------
     nbytes = 1 << 30
     src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
@@ -263,6 +274,7 @@ def main():
                                  "us_per_launch": round(score_us, 2)},
         "abstract_build": {"GBps_of_K_streamed": round((k_bytes + ab_out_bytes) / (ab_ms * 1e-3) / 1e9, 1),
                            "ms_per_layer": round(ab_ms / nl, 3)},
+        "abstract_append_us": None if append_us is None else round(append_us, 2),
         "copy_probe_GBps": round(copy_gbs, 1),
     }
 

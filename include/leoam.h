@@ -6,6 +6,7 @@
  *
  *   kv_chunk_abstract_build        Sec. 4.3: per chunk, the element-wise maximum
  *                                  and minimum key vectors (the "KV abstract").
+ *   kv_chunk_abstract_append       the same, updated for one new token per step.
  *   chunk_score                    Sec. 4.1 / 4.3: chunk importance = upper bound
  *                                  of q.k over the chunk, from abstract + query.
  *   chunk_topk_select              Sec. 4.2 / 6.1: order chunks by upper bound,
@@ -107,6 +108,36 @@ typedef struct {
  */
 int kv_chunk_abstract_build(const leoam_shape* shape, const void* K, const void* qmeta, const int32_t* chunk_off,
                             const int32_t* n_chunks, void* abstract, void* stream);
+
+/*
+ * The abstract of Sec. 4.3 kept up to date while decoding adds one token per
+ * sequence and step (Sec. 2.1: output tokens are generated one by one and join
+ * the context).  For every sequence b the new token is t = chunk_off[b][n_chunks[b]]
+ * (the current length; rows need not reach n_ctx, which is the capacity of the
+ * K rows), and the caller has already stored its key in K[b,:,t,:].  If the last
+ * chunk holds fewer than chunk_size tokens it grows by one and its abstract rows
+ * become max(kmax, k_t) / min(kmin, k_t); otherwise a new one-token chunk with
+ * kmax = kmin = k_t is opened (chunk_size is the layer's initial chunk size;
+ * Sec. 6.1 uses 64, and 8 in the first two layers).  The result equals
+ * kv_chunk_abstract_build on the new boundaries.  chunk_off, n_chunks and
+ * abstract are updated in place; status[b] (nullable) = 0 done, 1 cache full
+ * (t == n_ctx), 2 no room for another chunk (n_chunks == c_max); sequences with a
+ * non-zero status are left untouched.  fp32 / fp16 / bf16 stores only.
+ */
+int kv_chunk_abstract_append(const leoam_shape* shape, const void* K, int32_t* chunk_off, int32_t* n_chunks,
+                             int32_t chunk_size, void* abstract, int32_t* status, void* stream);
+
+/*
+ * Sec. 4.2 "Dynamic chunk resizing": the expected number of importance
+ * evaluations when n_tokens start as n_chunks equal chunks, a split costs two
+ * evaluations and happens with probability rho at every tree level (rho = share
+ * of important tokens of the layer), and a chunk of size n/m is split at most
+ * log2(n/m) - 1 times:
+ *   f(m) = m * sum_{i=0}^{log2(n/m)-1} (2 rho)^i.
+ * Host arithmetic only.  -1 unless n_chunks divides n_tokens into a power-of-two
+ * chunk size and 0 <= rho <= 1.
+ */
+double leoam_tree_evaluations(int64_t n_tokens, int64_t n_chunks, double rho);
 
 /*
  * Sec. 4.1 (chunk importance is the upper bound of the token importance in the

@@ -94,26 +94,59 @@ def widen(x) -> np.ndarray:
     return out
 
 
-def abstract_build(K, chunk_off, n_chunks) -> np.ndarray:
+def abstract_build(K, chunk_off, n_chunks, full: bool = True) -> np.ndarray:
     """Sec. 4.3 abstract: float64 [B,Hkv,c_max,2,D]; [..,0,:]=kmax, [..,1,:]=kmin.
-    Rows of unused chunks are NaN."""
+    Rows of unused chunks are NaN.  full=False: the chunks may stop before N (a
+    cache that is still being filled)."""
     a, tag = _as_numpy(K)
     B, Hkv, N, D = a.shape
     off = _i32(chunk_off)
     nc = _i32(n_chunks)
     c_max = off.shape[1] - 1
-    _check_boundaries(off, nc, N)
+    _check_boundaries(off, nc, N, full)
     out = np.full((B, Hkv, c_max, 2, D), np.nan, dtype=np.float64)
     rc = _load().orc_abstract_build(tag, B, Hkv, N, D, _ptr(a), _ptr(off), _ptr(nc), c_max, _ptr(out))
     assert rc == 0
     return out
 
 
-def _check_boundaries(off: np.ndarray, nc: np.ndarray, N: int) -> None:
+def _check_boundaries(off: np.ndarray, nc: np.ndarray, N: int, full: bool = True) -> None:
     for b in range(off.shape[0]):
         row = off[b, : nc[b] + 1]
-        if row[0] != 0 or row[-1] != N or np.any(np.diff(row) <= 0):
+        if row[0] != 0 or (row[-1] != N if full else row[-1] > N) or np.any(np.diff(row) <= 0):
             raise ValueError(f"chunk boundaries of sequence {b} do not tile [0,{N})")
+
+
+def abstract_append(K, chunk_off, n_chunks, chunk_size: int, abstract):
+    """One decode step of abstract maintenance (Sec. 4.3 abstract, Sec. 2.1 token-by-token
+    decoding): the key at index chunk_off[b][n_chunks[b]] joins the last chunk, or opens a
+    new one once the last chunk holds chunk_size tokens.  Returns new copies
+    (chunk_off, n_chunks, abstract float64, status int32 [B])."""
+    a, tag = _as_numpy(K)
+    B, Hkv, N, D = a.shape
+    off = _i32(chunk_off).copy()
+    nc = _i32(n_chunks).copy()
+    c_max = off.shape[1] - 1
+    _check_boundaries(off, nc, N, full=False)
+    ab = np.array(abstract, dtype=np.float64, copy=True, order="C")
+    assert ab.shape == (B, Hkv, c_max, 2, D)
+    status = np.zeros(B, dtype=np.int32)
+    rc = _load().orc_abstract_append(tag, B, Hkv, N, D, _ptr(a), _ptr(off), _ptr(nc), c_max, int(chunk_size), _ptr(ab),
+                                     _ptr(status))
+    assert rc == 0
+    return off, nc, ab, status
+
+
+def tree_evaluations(n_tokens: int, n_chunks: int, rho: float) -> float:
+    """Sec. 4.2 "Dynamic chunk resizing": f(m) = m * sum_{i=0}^{log2(n/m)-1} (2 rho)^i, summed
+    term by term in the order printed."""
+    size = n_tokens // n_chunks
+    levels = int(round(np.log2(size)))
+    assert n_chunks * size == n_tokens and (1 << levels) == size
+    total = 0.0
+    for i in range(levels):
+        total += (2.0 * rho) ** i
+    return n_chunks * total
 
 
 def chunk_score(q, abstract, n_chunks, want_lower: bool = False, want_f64: bool = False):

@@ -9,6 +9,7 @@
  * Each function follows one passage of the paper (arXiv 2506.20187):
  *   orc_abstract_build   Sec. 4.3 "KV abstract extraction": the element-wise
  *                        maximum and minimum key vectors of a chunk.
+ *   orc_abstract_append  the same abstract, kept up to date for one appended key.
  *   orc_chunk_score      Sec. 4.1 (chunk importance = upper bound of token
  *                        importance inside the chunk) and Sec. 4.3 (upper and
  *                        lower bounds from the abstract and the query).
@@ -114,6 +115,57 @@ int orc_abstract_build(int dtype, int B, int Hkv, int N, int D, const void *K, c
                     if (x < kmin[d]) kmin[d] = x;
                 }
             }
+        }
+    }
+    return 0;
+}
+
+/*
+ * Sec. 4.3 abstract while decoding appends one key per sequence (Sec. 2.1: tokens
+ * are generated one by one).  The new token of sequence b sits at index
+ * t = chunk_off[b][n_chunks[b]] of K.  While the last chunk has fewer than
+ * chunk_size tokens it takes the token (its kmax / kmin rows are compared with the
+ * new key, element by element); otherwise a new chunk holding just that token is
+ * opened.  status[b]: 0 done, 1 cache full, 2 no room for another chunk (then
+ * nothing of that sequence changes).  abstract: double [B,Hkv,c_max,2,D].
+ */
+int orc_abstract_append(int dtype, int B, int Hkv, int N, int D, const void *K, int32_t *chunk_off, int32_t *n_chunks,
+                        int c_max, int chunk_size, double *abstract, int32_t *status) {
+    for (int b = 0; b < B; ++b) {
+        int32_t *off = chunk_off + (size_t)b * (c_max + 1);
+        int C = n_chunks[b];
+        int t = off[C];
+        int room = C > 0 && (t - off[C - 1]) < chunk_size;
+        status[b] = 0;
+        if (t >= N) {
+            status[b] = 1;
+            continue;
+        }
+        if (!room && C >= c_max) {
+            status[b] = 2;
+            continue;
+        }
+        int c = room ? C - 1 : C;
+        for (int h = 0; h < Hkv; ++h) {
+            size_t bh = (size_t)b * Hkv + h;
+            double *kmax = abstract + ((bh * c_max + c) * 2 + 0) * D;
+            double *kmin = abstract + ((bh * c_max + c) * 2 + 1) * D;
+            for (int d = 0; d < D; ++d) {
+                double x = widen(K, dtype, (bh * N + t) * D + d);
+                if (!room) {
+                    kmax[d] = x;
+                    kmin[d] = x;
+                } else {
+                    if (x > kmax[d]) kmax[d] = x;
+                    if (x < kmin[d]) kmin[d] = x;
+                }
+            }
+        }
+        if (room) {
+            off[C] = t + 1;
+        } else {
+            off[C + 1] = t + 1;
+            n_chunks[b] = C + 1;
         }
     }
     return 0;

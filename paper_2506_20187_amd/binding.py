@@ -43,6 +43,9 @@ def _load() -> ctypes.CDLL:
     sp = ctypes.POINTER(Shape)
     lib.kv_chunk_abstract_build.argtypes = [sp, vp, vp, vp, vp, vp, vp]
     lib.chunk_score.argtypes = [sp, vp, vp, vp, vp, vp, vp]
+    lib.kv_chunk_abstract_append.argtypes = [sp, vp, vp, vp, i32, vp, vp, vp]
+    lib.leoam_tree_evaluations.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_double]
+    lib.leoam_tree_evaluations.restype = ctypes.c_double
     lib.chunk_topk_select.argtypes = [sp, vp, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.sparse_chunk_attention_decode.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, sz, vp]
     lib.chunk_select_attention_decode.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_float, vp, vp, vp,
@@ -58,7 +61,7 @@ def _load() -> ctypes.CDLL:
     lib.leoam_status_string.restype = ctypes.c_char_p
     lib.leoam_version.restype = ctypes.c_int
     for name in ("kv_chunk_abstract_build", "chunk_score", "chunk_topk_select", "sparse_chunk_attention_decode",
-                 "chunk_select_attention_decode", "leoam_workspace_init", "leoam_validate_boundaries",
+                 "chunk_select_attention_decode", "kv_chunk_abstract_append", "leoam_workspace_init", "leoam_validate_boundaries",
                  "leoam_copy_probe"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
@@ -68,6 +71,7 @@ _lib = _load()
 
 EXPORTS = ("kv_chunk_abstract_build", "chunk_score", "chunk_topk_select", "sparse_chunk_attention_decode",
            "chunk_select_attention_decode", "leoam_fused_workspace_bytes", "leoam_workspace_init",
+           "kv_chunk_abstract_append", "leoam_tree_evaluations",
            "leoam_workspace_bytes", "leoam_validate_boundaries", "leoam_copy_probe", "leoam_status_string",
            "leoam_version")
 
@@ -108,6 +112,16 @@ def _check(status: int, where: str) -> None:
 def kv_chunk_abstract_build(shape: Shape, K, chunk_off, n_chunks, abstract, stream=None, qmeta=None) -> None:
     _check(_lib.kv_chunk_abstract_build(ctypes.byref(shape), _p(K), _p(qmeta), _p(chunk_off), _p(n_chunks), _p(abstract),
                                         _stream(stream)), "kv_chunk_abstract_build")
+
+
+def kv_chunk_abstract_append(shape: Shape, K, chunk_off, n_chunks, chunk_size: int, abstract, status=None,
+                             stream=None) -> None:
+    _check(_lib.kv_chunk_abstract_append(ctypes.byref(shape), _p(K), _p(chunk_off), _p(n_chunks), int(chunk_size),
+                                         _p(abstract), _p(status), _stream(stream)), "kv_chunk_abstract_append")
+
+
+def leoam_tree_evaluations(n_tokens: int, n_chunks: int, rho: float) -> float:
+    return float(_lib.leoam_tree_evaluations(int(n_tokens), int(n_chunks), float(rho)))
 
 
 def chunk_score(shape: Shape, q, abstract, n_chunks, score_ub, score_lb=None, stream=None) -> None:

@@ -25,6 +25,7 @@ hipError_t select_attention_dispatch(const leoam_shape*, const float*, const voi
 size_t select_attention_workspace_bytes(const leoam_shape*, int);
 size_t select_attention_min_workspace_bytes(const leoam_shape*);
 hipError_t workspace_zero_dispatch(void*, size_t, hipStream_t);
+hipError_t abstract_append_dispatch(const leoam_shape*, const void*, int32_t*, int32_t*, int, void*, int32_t*, hipStream_t);
 
 __global__ void copy_probe_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
@@ -69,6 +70,30 @@ int kv_chunk_abstract_build(const leoam_shape* shape, const void* K, const void*
         return from_hip(abstract_build_q_dispatch(shape, K, qmeta, chunk_off, n_chunks, abstract, (hipStream_t)stream));
     }
     return from_hip(abstract_build_dispatch(shape, K, chunk_off, n_chunks, abstract, (hipStream_t)stream));
+}
+
+int kv_chunk_abstract_append(const leoam_shape* shape, const void* K, int32_t* chunk_off, int32_t* n_chunks,
+                             int32_t chunk_size, void* abstract, int32_t* status, void* stream) {
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!K || !chunk_off || !n_chunks || !abstract || chunk_size < 1) return LEOAM_E_INVALID_ARG;
+    if (shape->kv_dtype == LEOAM_Q8Q4) return LEOAM_E_UNSUPPORTED;
+    return from_hip(abstract_append_dispatch(shape, K, chunk_off, n_chunks, chunk_size, abstract, status,
+                                             (hipStream_t)stream));
+}
+
+double leoam_tree_evaluations(int64_t n_tokens, int64_t n_chunks, double rho) {
+    if (n_chunks < 1 || n_tokens < n_chunks || n_tokens % n_chunks || !(rho >= 0.0) || !(rho <= 1.0)) return -1.0;
+    int64_t size = n_tokens / n_chunks;
+    if (size & (size - 1)) return -1.0;
+    int levels = 0;
+    while (((int64_t)1 << levels) < size) ++levels;
+    double sum = 0.0, term = 1.0;
+    for (int i = 0; i < levels; ++i) {
+        sum += term;
+        term *= 2.0 * rho;
+    }
+    return (double)n_chunks * sum;
 }
 
 int chunk_score(const leoam_shape* shape, const void* q, const void* abstract, const int32_t* n_chunks,

@@ -68,6 +68,72 @@ def test_abstract_exact(L, oracle, dtype):
         assert np.isnan(got[b, :, n:]).all()        # rows of absent chunks are not written
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_abstract_append_exact(L, oracle, dtype):
+    """One new token per sequence and step: boundaries, counts, status and abstract rows follow the oracle bit for bit."""
+    rng = np.random.default_rng(77)
+    B, Hkv, N, D, cs, c_max = 4, 5, 150, 128, 8, 14
+    K = torch.from_numpy(rng.standard_normal((B, Hkv, N, D)).astype(np.float32)).to(TDT[dtype])
+    off = np.zeros((B, c_max + 1), dtype=np.int32)
+    nc = np.asarray([0, 3, 2, 1], dtype=np.int32)
+    off[1, :4] = [0, 5, 12, 35]              # last chunk longer than the chunk size: a new chunk opens at once
+    off[2, :3] = [0, 70, 146]                # reaches the end of the cache after four steps
+    off[3, :2] = [0, 3]                      # runs out of chunk slots
+    ab0 = oracle.abstract_build(K, off, nc, full=False)
+    shape = L.make_shape(B, Hkv, Hkv, D, N, c_max, 1, TDT[dtype])
+    d_off, d_nc = dev(off), dev(nc)
+    d_ab = torch.from_numpy(np.nan_to_num(ab0, nan=512.0)).to(TDT[dtype]).cuda()      # unused rows hold a marker
+    d_K, d_st = dev(K), torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    ab = ab0
+    seen = set()
+    for step in range(120):
+        off, nc, ab, st = oracle.abstract_append(K, off, nc, cs, ab)
+        L.kv_chunk_abstract_append(shape, d_K, d_off, d_nc, cs, d_ab, d_st)
+        torch.cuda.synchronize()
+        assert np.array_equal(d_st.cpu().numpy(), st), f"status, step {step}"
+        assert np.array_equal(d_nc.cpu().numpy(), nc), f"n_chunks, step {step}"
+        got_off, got_ab = d_off.cpu().numpy(), host_f64(d_ab)
+        for b in range(B):
+            assert np.array_equal(got_off[b, : nc[b] + 1], off[b, : nc[b] + 1]), f"boundaries, step {step}"
+            assert np.array_equal(got_ab[b, :, : nc[b]], ab[b, :, : nc[b]]), f"abstract, step {step}"
+            assert np.all(got_ab[b, :, nc[b]:] == 512.0)                              # rows of absent chunks untouched
+        seen |= set(st.tolist())
+    assert seen == {0, 1, 2}
+
+
+def test_decode_loop_with_appends(L, oracle):
+    """A short decode loop: append the step's key, then score -> select -> attention on the grown cache."""
+    case = gen.make_case("c2", layer=11, n_ctx=4096, hq=8, hkv=2, token_budget=512)
+    K, V = case.K, case.V
+    B, Hkv, N, D = K.shape
+    c_max = case.chunk_off.shape[1] - 1 + 8
+    # the cache starts 40 tokens short of its capacity: keep the chunks that end before that point
+    row = case.chunk_off[0].numpy()
+    keep = int(np.searchsorted(row[: int(case.n_chunks[0]) + 1], N - 40, side="right")) - 1
+    off = np.zeros((B, c_max + 1), dtype=np.int32)
+    off[0, : keep + 1] = row[: keep + 1]
+    nc = np.asarray([keep], dtype=np.int32)
+    layer = L.DecodeLayer(dev(K), dev(V), dev(off), dev(nc), case.hq, case.k_max, 0, case.token_budget)
+    layer.build_abstract()
+    ab = oracle.abstract_build(K, off, nc, full=False)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    for step in range(12):
+        q = (case.q.float() + 0.3 * torch.from_numpy(rng.standard_normal(tuple(case.q.shape)).astype(np.float32))).to(K.dtype)
+        off, nc, ab, st = oracle.abstract_append(K, off, nc, 16, ab)
+        L.kv_chunk_abstract_append(layer.shape, layer.K, layer.chunk_off, layer.n_chunks, 16, layer.abstract, None)
+        layer.step(dev(q))
+        torch.cuda.synchronize()
+        ub = oracle.chunk_score(q, np.nan_to_num(ab), nc)
+        sel, cnt, tok = oracle.topk_select(ub, off, nc, 0, case.token_budget, case.k_max)
+        out, _ = oracle.sparse_attention(q, K, V, off, sel, cnt)
+        n = int(nc[0])
+        assert np.array_equal(layer.n_chunks.cpu().numpy(), nc)
+        assert np.array_equal(layer.score[:, :, :n].cpu().numpy(), ub[:, :, :n]), f"score, step {step}"
+        assert np.array_equal(layer.sel_idx.cpu().numpy(), sel) and np.array_equal(layer.sel_count.cpu().numpy(), cnt)
+        assert np.abs(host_f64(layer.out) - out).max() <= TOL[case.dtype], f"attention, step {step}"
+
+
 # ---------------------------------------------------------------------------
 # a2 score
 # ---------------------------------------------------------------------------
