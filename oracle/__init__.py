@@ -313,3 +313,23 @@ def sparse_attention_q(q, kblob, vblob, qmeta, chunk_off, sel_idx, sel_count, sc
                                         _ptr(sel), _ptr(cnt), k_max, ctypes.c_double(scale), _ptr(out), _ptr(lse))
     assert rc == 0
     return out, lse
+
+
+def tree_refine(q, K, chunk_size: int, k_tokens: int, max_rounds: int, node_cap: int):
+    """Sec. 4.2 tree-structured chunk refinement (see leoam_oracle.c).  Returns
+    (ref_off int32 [B,Hkv,node_cap+1], ref_score float32 [B,Hkv,node_cap], ref_count [B,Hkv],
+    evaluations [B,Hkv], status [B,Hkv])."""
+    ka, tag = _as_numpy(K)
+    B, Hkv, N, D = ka.shape
+    qd = widen(q) if not (isinstance(q, np.ndarray) and q.dtype == np.float64) else np.ascontiguousarray(q)
+    Hq = qd.shape[1]
+    off = np.zeros((B, Hkv, node_cap + 1), dtype=np.int32)
+    score = np.full((B, Hkv, node_cap), -np.inf, dtype=np.float32)
+    cnt = np.zeros((B, Hkv), dtype=np.int32)
+    evals = np.zeros((B, Hkv), dtype=np.int32)
+    status = np.zeros((B, Hkv), dtype=np.int32)
+    rc = _load().orc_tree_refine(tag, B, Hq, Hkv, N, D, _ptr(ka), _ptr(qd), int(chunk_size), int(k_tokens), int(max_rounds),
+                                 int(node_cap), _ptr(off), _ptr(score), _ptr(cnt), _ptr(evals), _ptr(status))
+    if rc != 0:
+        raise ValueError("tree_refine: node_cap below the initial chunk count, or k_tokens outside [1, N]")
+    return off, score, cnt, evals, status

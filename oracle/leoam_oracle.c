@@ -505,3 +505,180 @@ int orc_sparse_attention_q(int B, int Hq, int Hkv, int D, const double *q, const
     }
     return 0;
 }
+
+/* ===========================================================================
+ * Tree-structured chunk refinement (Sec. 4.2, "Tree-structured KV chunk
+ * management"; Fig. 9).  Per (sequence, kv head):
+ *
+ *   - the context starts as equal chunks of chunk_size tokens, each evaluated
+ *     once: upper bound U and lower bound L of the token importance in it
+ *     (importance of token t = max over the group's heads of q_j.k_t; U as in
+ *     orc_chunk_score; L = the LARGEST of the heads' lower bounds, which every
+ *     token's importance still reaches; both from the chunk's element-wise
+ *     max / min keys, so that U = L = the importance for a single token);
+ *   - chunks are kept in a queue ordered by U; the front of the queue is read
+ *     until it covers k tokens.  A chunk whose lower bound beats the upper
+ *     bound of all but at most k tokens holds important tokens only and is
+ *     confirmed; the other front chunks are mixed: they are split in two and
+ *     their halves evaluated (two evaluations per split);
+ *   - this repeats until the front consists of confirmed chunks and single
+ *     tokens, or max_rounds is reached;
+ *   - runs of unimportant chunks (upper bound below the k-th largest lower
+ *     bound: they cannot hold one of the k most important tokens) are merged,
+ *     and so are runs of confirmed chunks.
+ *
+ * Order statistics are over tokens: a chunk counts size times.
+ *   v      = k-th largest U      (chunks with U >= v are the front of the queue)
+ *   mu     = (k+1)-th largest U  (-inf when k == N)
+ *   lambda = k-th largest L
+ *   confirmed: L > mu;  unimportant: U < lambda;  split: U >= v, not confirmed, size > 1.
+ * A split puts ceil(size/2) tokens in the left half.  If a round's splits
+ * would exceed node_cap nodes the refinement stops there (status 1).
+ *
+ * Output per (b,h): boundaries of the final partition, a score per chunk
+ * (FLT_MAX for confirmed chunks, otherwise its U; merged unimportant runs carry
+ * the largest U of the run), the number of chunks, and the number of
+ * evaluations (initial chunks + 2 per split).  Selecting from these scores
+ * with a token budget of k (orc_topk_select) gives the important tokens.
+ * =========================================================================== */
+typedef struct {
+    int start, size;
+    float U, L;
+} tnode;
+
+static void node_bounds(int dtype, const void *K, const double *q, int G, int D, size_t base_row, tnode *nd,
+                        double *kmax, double *kmin) {
+    for (int d = 0; d < D; ++d) {
+        kmax[d] = -INFINITY;
+        kmin[d] = INFINITY;
+    }
+    for (int t = nd->start; t < nd->start + nd->size; ++t)
+        for (int d = 0; d < D; ++d) {
+            double x = widen(K, dtype, (base_row + t) * D + d);
+            if (x > kmax[d]) kmax[d] = x;
+            if (x < kmin[d]) kmin[d] = x;
+        }
+    float U = -INFINITY, L = -INFINITY;
+    for (int j = 0; j < G; ++j) {
+        double u = 0.0, l = 0.0;
+        for (int d = 0; d < D; ++d) {
+            double a = q[(size_t)j * D + d] * kmax[d], b = q[(size_t)j * D + d] * kmin[d];
+            u += a > b ? a : b;
+            l += a > b ? b : a;
+        }
+        float uf = (float)u + 0.0f, lf = (float)l + 0.0f;
+        if (uf > U) U = uf;
+        if (lf > L) L = lf;
+    }
+    nd->U = U;
+    nd->L = L;
+}
+
+typedef struct {
+    float key;
+    int weight;
+} wkey;
+
+static int wkey_desc(const void *a, const void *b) {
+    float x = ((const wkey *)a)->key, y = ((const wkey *)b)->key;
+    return (x < y) - (x > y);
+}
+
+/* the rank-th largest key when every key counts `weight` times (rank >= 1); -inf if there are fewer */
+static float weighted_kth_largest(wkey *w, int n, long rank) {
+    qsort(w, n, sizeof(wkey), wkey_desc);
+    long acc = 0;
+    for (int i = 0; i < n; ++i) {
+        acc += w[i].weight;
+        if (acc >= rank) return w[i].key;
+    }
+    return -INFINITY;
+}
+
+int orc_tree_refine(int dtype, int B, int Hq, int Hkv, int N, int D, const void *K, const double *q, int chunk_size,
+                    int k_tokens, int max_rounds, int node_cap, int32_t *ref_off, float *ref_score,
+                    int32_t *ref_count, int32_t *ref_evals, int32_t *ref_status) {
+    int G = Hq / Hkv;
+    int m0 = (N + chunk_size - 1) / chunk_size;
+    if (m0 > node_cap || k_tokens < 1 || k_tokens > N) return -1;
+    int bh;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (bh = 0; bh < B * Hkv; ++bh) {
+        int b = bh / Hkv, h = bh % Hkv;
+        const double *qg = q + ((size_t)b * Hq + (size_t)h * G) * D;
+        size_t base_row = (size_t)bh * N;
+        tnode *cur = (tnode *)malloc(sizeof(tnode) * (size_t)node_cap), *nxt = (tnode *)malloc(sizeof(tnode) * (size_t)node_cap);
+        wkey *w = (wkey *)malloc(sizeof(wkey) * (size_t)node_cap);
+        double *kmax = (double *)malloc(sizeof(double) * D), *kmin = (double *)malloc(sizeof(double) * D);
+        int n = m0, evals = m0, status = 0;
+        for (int c = 0; c < m0; ++c) {
+            cur[c].start = c * chunk_size;
+            cur[c].size = (c + 1) * chunk_size <= N ? chunk_size : N - c * chunk_size;
+            node_bounds(dtype, K, qg, G, D, base_row, &cur[c], kmax, kmin);
+        }
+        float lambda = 0.f, mu = 0.f;
+        for (int round = 0;; ++round) {
+            for (int i = 0; i < n; ++i) { w[i].key = cur[i].U; w[i].weight = cur[i].size; }
+            float v = weighted_kth_largest(w, n, k_tokens);
+            for (int i = 0; i < n; ++i) { w[i].key = cur[i].U; w[i].weight = cur[i].size; }
+            mu = weighted_kth_largest(w, n, (long)k_tokens + 1);
+            for (int i = 0; i < n; ++i) { w[i].key = cur[i].L; w[i].weight = cur[i].size; }
+            lambda = weighted_kth_largest(w, n, k_tokens);
+            if (round >= max_rounds) break;
+            int n_split = 0;
+            for (int i = 0; i < n; ++i)
+                if (cur[i].U >= v && !(cur[i].L > mu) && cur[i].size > 1) ++n_split;
+            if (n_split == 0) break;
+            if (n + n_split > node_cap) {
+                status = 1;
+                break;
+            }
+            int m = 0;
+            for (int i = 0; i < n; ++i) {
+                if (cur[i].U >= v && !(cur[i].L > mu) && cur[i].size > 1) {
+                    int left = (cur[i].size + 1) / 2;
+                    nxt[m].start = cur[i].start;
+                    nxt[m].size = left;
+                    node_bounds(dtype, K, qg, G, D, base_row, &nxt[m], kmax, kmin);
+                    ++m;
+                    nxt[m].start = cur[i].start + left;
+                    nxt[m].size = cur[i].size - left;
+                    node_bounds(dtype, K, qg, G, D, base_row, &nxt[m], kmax, kmin);
+                    ++m;
+                    evals += 2;
+                } else {
+                    nxt[m++] = cur[i];
+                }
+            }
+            tnode *tmp = cur;
+            cur = nxt;
+            nxt = tmp;
+            n = m;
+        }
+        /* final partition: merge runs of confirmed chunks and runs of unimportant chunks */
+        int32_t *off = ref_off + (size_t)bh * (node_cap + 1);
+        float *sc = ref_score + (size_t)bh * node_cap;
+        int m = 0, prev_kind = -1;      /* 0 mixed, 1 confirmed, 2 unimportant */
+        for (int i = 0; i < n; ++i) {
+            int kind = (cur[i].L > mu) ? 1 : (cur[i].U < lambda ? 2 : 0);
+            if (m > 0 && kind != 0 && kind == prev_kind) {
+                if (kind == 2 && cur[i].U > sc[m - 1]) sc[m - 1] = cur[i].U;
+            } else {
+                off[m] = cur[i].start;
+                sc[m] = kind == 1 ? 3.402823466e+38f : cur[i].U;
+                ++m;
+            }
+            prev_kind = kind;
+        }
+        off[m] = N;
+        ref_count[bh] = m;
+        ref_evals[bh] = evals;
+        ref_status[bh] = status;
+        free(cur);
+        free(nxt);
+        free(w);
+        free(kmax);
+        free(kmin);
+    }
+    return 0;
+}
