@@ -13,6 +13,8 @@
  *                                  keep the front of the list under a budget.
  *   sparse_chunk_attention_decode  Sec. 2.1 Eq. (1) over the kept chunks only.
  *   chunk_select_attention_decode  the last two steps in one launch.
+ *   chunk_tree_refine              Sec. 4.2: tree-structured split / merge of chunks
+ *                                  around the k most important tokens.
  *
  * Conventions (all entry points)
  *   - Every pointer except `const leoam_shape*` is a DEVICE pointer owned by the
@@ -126,6 +128,43 @@ int kv_chunk_abstract_build(const leoam_shape* shape, const void* K, const void*
  */
 int kv_chunk_abstract_append(const leoam_shape* shape, const void* K, int32_t* chunk_off, int32_t* n_chunks,
                              int32_t chunk_size, void* abstract, int32_t* status, void* stream);
+
+/*
+ * Sec. 4.2 "Tree-structured KV chunk management" (Fig. 9).  Per (b, kv head) the
+ * context starts as chunks of chunk_size tokens (the last one may be shorter)
+ * whose abstract rows `abstract[b,h,c]`, c < ceil(n_ctx / chunk_size) <= c_max,
+ * were built by kv_chunk_abstract_build.  Every chunk gets an upper bound U and a
+ * lower bound L of the importance of its tokens (importance of token t = max over
+ * the group's query heads of q_j.k_t; U = max_j U_j, L = max_j L_j with U_j, L_j
+ * as in chunk_score, each the double sum rounded once to float).  With order
+ * statistics taken over tokens (a chunk counts `size` times),
+ *   v = k-th largest U,  mu = (k+1)-th largest U (-inf if k == n_ctx),  lambda = k-th largest L,
+ * a chunk with L > mu holds only tokens of the k most important ones (confirmed),
+ * a chunk with U < lambda holds none (unimportant), and every chunk with U >= v
+ * (the front of the queue ordered by U, read until it covers k tokens) that is
+ * neither confirmed nor a single token is split in two (ceil(size/2) tokens to
+ * the left) and its halves are evaluated from their keys.  This is repeated until
+ * nothing is split, max_rounds rounds were made, or a round would need more than
+ * node_cap nodes (then ref_status = 1 and that round is not made).  Finally runs
+ * of confirmed chunks and runs of unimportant chunks are merged.
+ *   ref_off   [batch, n_kv_heads, node_cap + 1]  boundaries of the final partition
+ *   ref_score [batch, n_kv_heads, node_cap]      FLT_MAX for a confirmed chunk, else its U
+ *                                               (a merged unimportant run: the largest U in it)
+ *   ref_count, ref_evals, ref_status [batch, n_kv_heads]   chunks; evaluations made
+ *                                               (initial chunks + 2 per split); 0 or 1
+ * Reading ref_off / ref_score / ref_count as the boundaries, scores and counts of
+ * batch * n_kv_heads sequences with one kv head each, chunk_topk_select with
+ * token_budget = k keeps the k most important tokens (exactly, once nothing is
+ * left to split), and sparse_chunk_attention_decode attends to them.
+ * fp32 / fp16 / bf16 stores.  Workspace: leoam_tree_workspace_bytes(), 16-byte
+ * aligned, contents irrelevant.
+ */
+int chunk_tree_refine(const leoam_shape* shape, const void* q, const void* K, const void* abstract, int32_t chunk_size,
+                      int32_t k_tokens, int32_t max_rounds, int32_t node_cap, int32_t* ref_off, float* ref_score,
+                      int32_t* ref_count, int32_t* ref_evals, int32_t* ref_status, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
+size_t leoam_tree_workspace_bytes(const leoam_shape* shape, int32_t node_cap);
 
 /*
  * Sec. 4.2 "Dynamic chunk resizing": the expected number of importance

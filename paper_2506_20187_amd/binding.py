@@ -44,6 +44,9 @@ def _load() -> ctypes.CDLL:
     lib.kv_chunk_abstract_build.argtypes = [sp, vp, vp, vp, vp, vp, vp]
     lib.chunk_score.argtypes = [sp, vp, vp, vp, vp, vp, vp]
     lib.kv_chunk_abstract_append.argtypes = [sp, vp, vp, vp, i32, vp, vp, vp]
+    lib.chunk_tree_refine.argtypes = [sp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.leoam_tree_workspace_bytes.argtypes = [sp, i32]
+    lib.leoam_tree_workspace_bytes.restype = sz
     lib.leoam_tree_evaluations.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_double]
     lib.leoam_tree_evaluations.restype = ctypes.c_double
     lib.chunk_topk_select.argtypes = [sp, vp, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
@@ -61,7 +64,7 @@ def _load() -> ctypes.CDLL:
     lib.leoam_status_string.restype = ctypes.c_char_p
     lib.leoam_version.restype = ctypes.c_int
     for name in ("kv_chunk_abstract_build", "chunk_score", "chunk_topk_select", "sparse_chunk_attention_decode",
-                 "chunk_select_attention_decode", "kv_chunk_abstract_append", "leoam_workspace_init", "leoam_validate_boundaries",
+                 "chunk_select_attention_decode", "kv_chunk_abstract_append", "chunk_tree_refine", "leoam_workspace_init", "leoam_validate_boundaries",
                  "leoam_copy_probe"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
@@ -71,7 +74,7 @@ _lib = _load()
 
 EXPORTS = ("kv_chunk_abstract_build", "chunk_score", "chunk_topk_select", "sparse_chunk_attention_decode",
            "chunk_select_attention_decode", "leoam_fused_workspace_bytes", "leoam_workspace_init",
-           "kv_chunk_abstract_append", "leoam_tree_evaluations",
+           "kv_chunk_abstract_append", "leoam_tree_evaluations", "chunk_tree_refine", "leoam_tree_workspace_bytes",
            "leoam_workspace_bytes", "leoam_validate_boundaries", "leoam_copy_probe", "leoam_status_string",
            "leoam_version")
 
@@ -118,6 +121,19 @@ def kv_chunk_abstract_append(shape: Shape, K, chunk_off, n_chunks, chunk_size: i
                              stream=None) -> None:
     _check(_lib.kv_chunk_abstract_append(ctypes.byref(shape), _p(K), _p(chunk_off), _p(n_chunks), int(chunk_size),
                                          _p(abstract), _p(status), _stream(stream)), "kv_chunk_abstract_append")
+
+
+def chunk_tree_refine(shape: Shape, q, K, abstract, chunk_size: int, k_tokens: int, max_rounds: int, node_cap: int,
+                      ref_off, ref_score, ref_count, ref_evals, ref_status, workspace, stream=None) -> None:
+    nbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(_lib.chunk_tree_refine(ctypes.byref(shape), _p(q), _p(K), _p(abstract), int(chunk_size), int(k_tokens),
+                                  int(max_rounds), int(node_cap), _p(ref_off), _p(ref_score), _p(ref_count),
+                                  _p(ref_evals), _p(ref_status), _p(workspace), nbytes, _stream(stream)),
+           "chunk_tree_refine")
+
+
+def leoam_tree_workspace_bytes(shape: Shape, node_cap: int) -> int:
+    return int(_lib.leoam_tree_workspace_bytes(ctypes.byref(shape), int(node_cap)))
 
 
 def leoam_tree_evaluations(n_tokens: int, n_chunks: int, rho: float) -> float:

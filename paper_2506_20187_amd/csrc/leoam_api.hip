@@ -25,6 +25,9 @@ hipError_t select_attention_dispatch(const leoam_shape*, const float*, const voi
 size_t select_attention_workspace_bytes(const leoam_shape*, int);
 size_t select_attention_min_workspace_bytes(const leoam_shape*);
 hipError_t workspace_zero_dispatch(void*, size_t, hipStream_t);
+size_t tree_workspace_bytes(const leoam_shape*, int);
+hipError_t tree_refine_dispatch(const leoam_shape*, const void*, const void*, const void*, int, int, int, int, int32_t*,
+                                float*, int32_t*, int32_t*, int32_t*, void*, hipStream_t);
 hipError_t abstract_append_dispatch(const leoam_shape*, const void*, int32_t*, int32_t*, int, void*, int32_t*, hipStream_t);
 
 __global__ void copy_probe_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
@@ -80,6 +83,37 @@ int kv_chunk_abstract_append(const leoam_shape* shape, const void* K, int32_t* c
     if (shape->kv_dtype == LEOAM_Q8Q4) return LEOAM_E_UNSUPPORTED;
     return from_hip(abstract_append_dispatch(shape, K, chunk_off, n_chunks, chunk_size, abstract, status,
                                              (hipStream_t)stream));
+}
+
+static int check_tree(const leoam_shape* shape, int32_t chunk_size, int32_t k_tokens, int32_t max_rounds,
+                      int32_t node_cap) {
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (shape->kv_dtype == LEOAM_Q8Q4) return LEOAM_E_UNSUPPORTED;
+    if (chunk_size < 1 || node_cap < 1 || max_rounds < 0) return LEOAM_E_INVALID_ARG;
+    if (k_tokens < 1 || k_tokens > shape->n_ctx) return LEOAM_E_INVALID_ARG;
+    const long long m0 = ((long long)shape->n_ctx + chunk_size - 1) / chunk_size;
+    if (m0 > node_cap || m0 > shape->c_max) return LEOAM_E_INVALID_ARG;
+    return LEOAM_OK;
+}
+
+size_t leoam_tree_workspace_bytes(const leoam_shape* shape, int32_t node_cap) {
+    if (check_shape(shape) || node_cap < 1) return 0;
+    return tree_workspace_bytes(shape, node_cap);
+}
+
+int chunk_tree_refine(const leoam_shape* shape, const void* q, const void* K, const void* abstract, int32_t chunk_size,
+                      int32_t k_tokens, int32_t max_rounds, int32_t node_cap, int32_t* ref_off, float* ref_score,
+                      int32_t* ref_count, int32_t* ref_evals, int32_t* ref_status, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+    int rc = check_tree(shape, chunk_size, k_tokens, max_rounds, node_cap);
+    if (rc) return rc;
+    if (!q || !K || !abstract || !ref_off || !ref_score || !ref_count || !ref_evals || !ref_status)
+        return LEOAM_E_INVALID_ARG;
+    if (!workspace || workspace_bytes < tree_workspace_bytes(shape, node_cap) || ((uintptr_t)workspace & 15u))
+        return LEOAM_E_WORKSPACE;
+    return from_hip(tree_refine_dispatch(shape, q, K, abstract, chunk_size, k_tokens, max_rounds, node_cap, ref_off,
+                                         ref_score, ref_count, ref_evals, ref_status, workspace, (hipStream_t)stream));
 }
 
 double leoam_tree_evaluations(int64_t n_tokens, int64_t n_chunks, double rho) {

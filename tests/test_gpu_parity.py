@@ -465,6 +465,111 @@ def test_select_attention_one_call(L, oracle, dtype, G, C):
 
 
 # ---------------------------------------------------------------------------
+# tree-structured chunk refinement (Sec. 4.2)
+# ---------------------------------------------------------------------------
+def gpu_tree_refine(L, dtype, q, K, cs, k, max_rounds, cap):
+    B, Hkv, N, D = K.shape
+    Hq = q.shape[1]
+    m0 = -(-N // cs)
+    off0 = np.minimum(np.arange(m0 + 1, dtype=np.int64) * cs, N).astype(np.int32)
+    packed = np.tile(off0, (B, 1))
+    counts = np.full(B, m0, dtype=np.int32)
+    shape = L.make_shape(B, Hq, Hkv, D, N, m0, 1, TDT[dtype])
+    ab = torch.empty(B, Hkv, m0, 2, D, dtype=TDT[dtype], device="cuda")
+    L.kv_chunk_abstract_build(shape, dev(K), dev(packed), dev(counts), ab)
+    r_off = torch.full((B, Hkv, cap + 1), -7, dtype=torch.int32, device="cuda")
+    r_score = torch.full((B, Hkv, cap), float("nan"), dtype=torch.float32, device="cuda")
+    r_cnt = torch.full((B, Hkv), -7, dtype=torch.int32, device="cuda")
+    r_ev, r_st = torch.full_like(r_cnt, -7), torch.full_like(r_cnt, -7)
+    ws = torch.empty(L.leoam_tree_workspace_bytes(shape, cap), dtype=torch.uint8, device="cuda")
+    L.chunk_tree_refine(shape, dev(q), dev(K), ab, cs, k, max_rounds, cap, r_off, r_score, r_cnt, r_ev, r_st, ws)
+    torch.cuda.synchronize()
+    return r_off, r_score, r_cnt, r_ev.cpu().numpy(), r_st.cpu().numpy()
+
+
+def check_tree(L, oracle, dtype, q, K, cs, k, max_rounds, cap):
+    want_off, want_score, want_cnt, want_ev, want_st = oracle.tree_refine(q, K, cs, k, max_rounds, cap)
+    r_off, r_score, r_cnt, ev, st = gpu_tree_refine(L, dtype, q, K, cs, k, max_rounds, cap)
+    tag = f"cs={cs} k={k} rounds={max_rounds} cap={cap}"
+    assert np.array_equal(st, want_st), tag
+    assert np.array_equal(r_cnt.cpu().numpy(), want_cnt), tag
+    assert np.array_equal(ev, want_ev), tag
+    got_off, got_score = r_off.cpu().numpy(), r_score.cpu().numpy()
+    B, Hkv = want_cnt.shape
+    for b in range(B):
+        for h in range(Hkv):
+            n = want_cnt[b, h]
+            assert np.array_equal(got_off[b, h, : n + 1], want_off[b, h, : n + 1]), tag
+            assert np.array_equal(got_score[b, h, :n], want_score[b, h, :n]), tag
+    return r_off, r_score, r_cnt, want_ev
+
+
+@pytest.mark.parametrize("dtype,G,N,cs", [("f32", 1, 256, 16), ("bf16", 4, 1024, 64), ("f16", 2, 300, 32), ("bf16", 1, 2500, 64),
+                                          ("f16", 8, 512, 8)])
+def test_tree_refine_exact(L, oracle, dtype, G, N, cs):
+    rng = np.random.default_rng(N + G)
+    B, Hkv, D = 2, 3, 128
+    K = torch.from_numpy(rng.standard_normal((B, Hkv, N, D)).astype(np.float32)).to(TDT[dtype])
+    q = torch.from_numpy(rng.standard_normal((B, Hkv * G, D)).astype(np.float32)).to(TDT[dtype])
+    for k, rounds, cap in ((N // 10, 10 ** 6, N), (1, 10 ** 6, N), (N // 3, 2, N), (N // 10, 0, N), (N, 5, N),
+                           (N // 4, 10 ** 6, -(-N // cs) + 5)):
+        check_tree(L, oracle, dtype, q, K, cs, max(1, k), rounds, cap)
+
+
+def test_tree_refine_ties_and_deserts(L, oracle):
+    # all tokens equal: the complete tree, ties resolved by index
+    K = torch.ones(1, 2, 64, 128)
+    q = torch.ones(1, 2, 128)
+    check_tree(L, oracle, "f32", q, K, 8, 5, 100, 64)
+    check_tree(L, oracle, "f32", q, K, 8, 5, 100, 20)          # node_cap too small: reported, partition still valid
+    # clusters of important tokens in a desert
+    g = torch.Generator().manual_seed(9)
+    N, cs, D = 4096, 64, 128
+    K = (torch.randn(1, 1, N, D, generator=g) * 0.1)
+    q = torch.randn(1, 1, D, generator=g)
+    hot = np.concatenate([np.arange(s, s + 24) for s in (100, 1500, 1540, 3000, 4000)])
+    K[0, 0, hot] += 6.0 * (q[0, 0] / q[0, 0].norm())
+    K, q = K.to(torch.bfloat16), q.to(torch.bfloat16)
+    _, _, _, ev = check_tree(L, oracle, "bf16", q, K, cs, len(hot), 10 ** 6, 512)
+    assert ev[0, 0] < N // 8
+
+
+def test_tree_refine_feeds_selection_and_attention(L, oracle):
+    """refine -> chunk_topk_select with a budget of k tokens -> attention, read as batch * n_kv_heads
+    sequences of one kv head: the attention runs over exactly the k most important tokens."""
+    rng = np.random.default_rng(31)
+    B, Hkv, G, N, D, cs, k = 2, 2, 4, 2048, 128, 64, 200
+    K = torch.from_numpy(rng.standard_normal((B, Hkv, N, D)).astype(np.float32)).to(torch.bfloat16)
+    V = torch.from_numpy(rng.standard_normal((B, Hkv, N, D)).astype(np.float32)).to(torch.bfloat16)
+    q = torch.from_numpy(rng.standard_normal((B, Hkv * G, D)).astype(np.float32)).to(torch.bfloat16)
+    cap = N                   # random keys have no deserts: the tree grows close to single tokens
+    r_off, r_score, r_cnt, _ = check_tree(L, oracle, "bf16", q, K, cs, k, 10 ** 6, cap)
+    shape = L.make_shape(B * Hkv, G, 1, D, N, cap, cap, torch.bfloat16)
+    sel = torch.empty(B * Hkv, 1, cap, dtype=torch.int32, device="cuda")
+    cnt = torch.empty(B * Hkv, 1, dtype=torch.int32, device="cuda")
+    tok = torch.empty_like(cnt)
+    out = torch.empty(B * Hkv, G, D, dtype=torch.float32, device="cuda")
+    ws = torch.empty(L.leoam_fused_workspace_bytes(shape, k), dtype=torch.uint8, device="cuda")
+    L.leoam_workspace_init(ws)
+    L.chunk_select_attention_decode(shape, r_score.view(B * Hkv, 1, cap), dev(q), dev(K), dev(V), r_off.view(B * Hkv, cap + 1),
+                                    r_cnt.view(B * Hkv), 0, k, L.default_scale(D), sel, cnt, tok, out, None, ws)
+    torch.cuda.synchronize()
+    assert torch.all(tok == k)
+    # token-level reference: softmax attention over the k most important tokens of every (b, kv head)
+    Kd, Vd, qd = K.double(), V.double(), q.double().view(B, Hkv, G, D)
+    logits = torch.einsum("bhgd,bhtd->bhgt", qd, Kd)
+    imp = logits.max(dim=2).values.float()
+    want = torch.empty(B, Hkv, G, D, dtype=torch.float64)
+    for b in range(B):
+        for h in range(Hkv):
+            order = np.lexsort((np.arange(N), -imp[b, h].double().numpy()))[:k]
+            idx = torch.from_numpy(np.sort(order))
+            p = torch.softmax(logits[b, h][:, idx] / D ** 0.5, dim=-1)
+            want[b, h] = p @ Vd[b, h, idx]
+    assert np.abs(host_f64(out).reshape(B, Hkv, G, D) - want.numpy()).max() <= TOL["bf16"]
+
+
+# ---------------------------------------------------------------------------
 # error paths (host-visible faults are refused before any launch)
 # ---------------------------------------------------------------------------
 def test_error_codes(L):
