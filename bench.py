@@ -221,6 +221,40 @@ def main():
         assert int(st.abs().sum()) == 0
         del off2, nc2, ab2
 
+    # ---- tree-structured refinement (Sec. 4.2) from uniform chunks of 64 tokens --------------
+    # (a) keys with planted runs of important tokens in a desert (the structure Sec. 3.5 reports for deep
+    #     layers; 128 runs of 32 tokens per head, k = 4096), (b) layer 0 of the workload itself, whose
+    #     Gaussian keys give loose bounds: the tree then grows towards single tokens until the round limit.
+    tree = None
+    if not quant:
+        lay, case = layers[0], cases[0]
+        cs, cap, rounds = 64, 32768, 64
+        nb, hk, nctx = lay.shape.batch, lay.shape.n_kv_heads, lay.shape.n_ctx
+        m0 = -(-nctx // cs)
+        tshape = B.make_shape(nb, case.hq, hk, case.d, nctx, m0, 1, lay.K.dtype)
+        u_off = torch.clamp(torch.arange(m0 + 1, dtype=torch.int32, device="cuda") * cs, max=nctx).repeat(nb, 1).contiguous()
+        u_nc = torch.full((nb,), m0, dtype=torch.int32, device="cuda")
+        u_ab = torch.empty(nb, hk, m0, 2, case.d, dtype=lay.K.dtype, device="cuda")
+        r_off = torch.empty(nb, hk, cap + 1, dtype=torch.int32, device="cuda")
+        r_score = torch.empty(nb, hk, cap, dtype=torch.float32, device="cuda")
+        r_cnt = torch.empty(nb, hk, dtype=torch.int32, device="cuda")
+        r_ev, r_st = torch.empty_like(r_cnt), torch.empty_like(r_cnt)
+        tws = torch.empty(B.leoam_tree_workspace_bytes(tshape, cap), dtype=torch.uint8, device="cuda")
+        Kd, qd, hot = gen.make_desert_keys(nb, hk, case.g, nctx, clusters=128, cluster_len=(32, 32), dtype=cfg["dtype"],
+                                           device="cuda")
+        tree = {"initial_chunk": cs, "initial_chunks_per_head": m0, "token_level_evaluations_per_head": nctx,
+                "max_rounds": rounds}
+        for name, Kt, qt, k_tok in (("planted_runs", Kd, qd, int(hot[0, 0].sum())), ("workload_layer", lay.K, case.q,
+                                                                                  int(case.token_budget))):
+            B.kv_chunk_abstract_build(tshape, Kt, u_off, u_nc, u_ab)
+            tree_ms = time_calls(lambda: B.chunk_tree_refine(tshape, qt, Kt, u_ab, cs, k_tok, rounds, cap, r_off, r_score,
+                                                             r_cnt, r_ev, r_st, tws), 5, torch)
+            tree[name] = {"us_per_layer_step": round(tree_ms * 1e3, 1), "k_tokens": k_tok,
+                          "evaluations_per_head_avg": round(float(r_ev.float().mean()), 1),
+                          "final_chunks_per_head_avg": round(float(r_cnt.float().mean()), 1),
+                          "node_cap_overflows": int(r_st.sum())}
+        del u_ab, r_off, r_score, tws, Kd, qd
+
     # ---- plain copy of known size: the "what does this box stream" reference ------
     nbytes = 1 << 30
     src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
@@ -275,6 +309,7 @@ def main():
         "abstract_build": {"GBps_of_K_streamed": round((k_bytes + ab_out_bytes) / (ab_ms * 1e-3) / 1e9, 1),
                            "ms_per_layer": round(ab_ms / nl, 3)},
         "abstract_append_us": None if append_us is None else round(append_us, 2),
+        "tree_refine": tree,
         "copy_probe_GBps": round(copy_gbs, 1),
     }
 

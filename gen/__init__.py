@@ -12,5 +12,6 @@ from .workloads import (  # noqa: F401
     make_boundaries,
     uniform_boundaries,
     pack_boundaries,
+    make_desert_keys,
 )
 from .quant import quantize_store, tag_four_bit, make_quant_case, QuantCase  # noqa: F401

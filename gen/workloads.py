@@ -301,3 +301,37 @@ def make_case(config: str, layer: int = 0, *, device="cpu", seed: int = BASE_SEE
                 chunk_off=torch.from_numpy(packed).to(device), n_chunks=torch.from_numpy(counts).to(device),
                 c_max=c_max, max_chunks=cfg["max_chunks"], token_budget=cfg["token_budget"], k_max=k_max,
                 planted=planted, extra={"heavy": np.stack(heavy)})
+
+
+def make_desert_keys(batch: int, hkv: int, g: int, n_ctx: int, *, clusters: int = 24, cluster_len=(8, 64),
+                     dtype: str = "bf16", device="cpu", seed: int = BASE_SEED):
+    """Keys and queries with the structure Sec. 3.5 reports for deep layers: a few short runs of
+    tokens that the query attends to, separated by long "attention deserts".
+
+    Per (sequence, kv head): keys 0.1 * N(0,1); `clusters` runs of cluster_len[0]..cluster_len[1]
+    tokens at distinct random places get +6 * q_dir added, q_dir being the unit direction shared by the
+    group's query heads (query head j = that direction * 4 + N(0, 0.05)).  Returns (K [B,Hkv,N,128],
+    q [B,Hkv*g,128], hot bool numpy [B,Hkv,N] marking the planted tokens)."""
+    tdt = _TORCH_DTYPE[dtype]
+    D = 128
+    K = torch.empty(batch, hkv, n_ctx, D, dtype=tdt, device=device)
+    q = torch.empty(batch, hkv * g, D, dtype=tdt, device=device)
+    hot = np.zeros((batch, hkv, n_ctx), dtype=bool)
+    for b in range(batch):
+        for h in range(hkv):
+            rng = _np_rng(seed, "desert", h, b)
+            gen_t = _torch_gen(device, seed, "desert", h, b)
+            direction = torch.randn(D, generator=gen_t, device=device)
+            direction = direction / direction.norm()
+            keys = 0.1 * torch.randn(n_ctx, D, generator=gen_t, device=device)
+            slot = n_ctx // clusters
+            for c in range(clusters):
+                length = int(rng.integers(cluster_len[0], cluster_len[1] + 1))
+                start = c * slot + int(rng.integers(0, max(1, slot - length)))
+                hot[b, h, start:start + length] = True
+            mask = torch.from_numpy(hot[b, h]).to(device)
+            keys[mask] += 6.0 * direction
+            K[b, h] = keys.to(tdt)
+            qs = 4.0 * direction[None, :] + 0.05 * torch.randn(g, D, generator=gen_t, device=device)
+            q[b, h * g:(h + 1) * g] = qs.to(tdt)
+    return K, q, hot

@@ -23,10 +23,12 @@
 // One 1024-lane workgroup per (sequence, kv head) runs every round; the node
 // list (start, size, U, L) lives in the workspace, double-buffered, in position
 // order (a split node is replaced by its two halves at scanned positions).  A
-// wave evaluates a node: element-wise max / min over its key rows (the two
-// abstract rows for an initial chunk), then the bounds in double, rounded once
-// to float.  Latency-bound, exact integer bookkeeping.
+// lane group as wide as a key row evaluates a node - element-wise max / min over
+// its key rows (the two abstract rows for an initial chunk), then the bounds in
+// double, rounded once to float - so a wave has 4 (fp32: 2) nodes in flight.
+// Latency-bound, exact integer bookkeeping.
 #include <cfloat>
+#include <type_traits>
 
 #include "leoam_dev.h"
 
@@ -73,40 +75,57 @@ __device__ __forceinline__ uint32_t tree_block_scan(uint32_t v, uint32_t* wave_t
     return upto - own + incl - v;
 }
 
-// A wave computes the bounds of one node: max / min over `n_rows` rows starting at
-// `rows` (row stride = one key row), then U = max_j sum_d max(q k_max, q k_min) and
-// L = max_j sum_d min(..), each sum in double, rounded once to float.
+// sum of a double over the lanes of a group of kLanes (16 or 32) lanes; every lane gets it
+template <int kLanes> __device__ __forceinline__ double group_sum_d(double v) {
+    auto step = [&](auto ctrl) {
+        constexpr int kCtrl = decltype(ctrl)::value;
+        const uint64_t u = __builtin_bit_cast(uint64_t, v);
+        const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)u, kCtrl, 0xf, 0xf, false);
+        const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)(u >> 32), kCtrl, 0xf, 0xf, false);
+        v += __builtin_bit_cast(double, ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+    };
+    step(std::integral_constant<int, 0xB1>{});       // xor 1
+    step(std::integral_constant<int, 0x4E>{});       // xor 2
+    step(std::integral_constant<int, 0x141>{});      // mirror inside 8 lanes
+    step(std::integral_constant<int, 0x140>{});      // mirror inside 16 lanes
+    if (kLanes == 32) v += shfl_xor_d(v, 16);
+    return v;
+}
+
+// A lane group (the lanes that cover one key row: 16 for 16-bit keys, 32 for fp32)
+// computes the bounds of one node: max / min over `n_rows` rows starting at `rows`,
+// then U = max_j sum_d max(q k_max, q k_min) and L = max_j sum_d min(..), each sum
+// in double, rounded once to float.  A wave evaluates 4 (2) nodes at a time.
 template <typename T>
 __device__ __forceinline__ void tree_eval(const char* rows, int n_rows, const double (*q)[LEOAM_D], int G, float* U,
                                           float* L) {
     constexpr int LPR = Row<T>::kLanesPerRow;
-    constexpr int RPL = Row<T>::kRowsPerLoad;
     constexpr int EPL = T::kEpl;
     constexpr int ROWB = Row<T>::kRowBytes;
-    const int lane = lane_id();
-    const int rgrp = lane / LPR, col = (lane % LPR) * EPL;
+    const int col = (lane_id() % LPR) * EPL;
     float mx[EPL], mn[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) {
         mx[e] = -INFINITY;
         mn[e] = INFINITY;
     }
-#pragma unroll 4
-    for (int r = rgrp; r < n_rows; r += RPL) {
-        float x[EPL];
-        unpack<T>(load16(rows, (size_t)r * ROWB + (size_t)col * T::kBytes), x);
+    // eight rows in flight; a row index past the end re-reads the last row (harmless for max / min,
+    // and the loads stay unconditional)
+    constexpr int kBatch = 8;
+    for (int r0 = 0; r0 < n_rows; r0 += kBatch) {
+        uint4 v[kBatch];
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-            mx[e] = fmaxf(mx[e], x[e]);
-            mn[e] = fminf(mn[e], x[e]);
-        }
-    }
+        for (int j = 0; j < kBatch; ++j)
+            v[j] = load16(rows, (size_t)min(r0 + j, n_rows - 1) * ROWB + (size_t)col * T::kBytes);
 #pragma unroll
-    for (int m = LPR; m < LEOAM_WAVE; m <<= 1) {
+        for (int j = 0; j < kBatch; ++j) {
+            float x[EPL];
+            unpack<T>(v[j], x);
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-            mx[e] = fmaxf(mx[e], shfl_xor_f(mx[e], m));
-            mn[e] = fminf(mn[e], shfl_xor_f(mn[e], m));
+            for (int e = 0; e < EPL; ++e) {
+                mx[e] = fmaxf(mx[e], x[e]);
+                mn[e] = fminf(mn[e], x[e]);
+            }
         }
     }
     float ub = -INFINITY, lb = -INFINITY;
@@ -118,11 +137,8 @@ __device__ __forceinline__ void tree_eval(const char* rows, int n_rows, const do
             u += fmax(a, b);
             l += fmin(a, b);
         }
-#pragma unroll
-        for (int m = 1; m < LPR; m <<= 1) {
-            u += shfl_xor_d(u, m);
-            l += shfl_xor_d(l, m);
-        }
+        u = group_sum_d<LPR>(u);
+        l = group_sum_d<LPR>(l);
         ub = fmaxf(ub, (float)u + 0.0f);
         lb = fmaxf(lb, (float)l + 0.0f);
     }
@@ -135,7 +151,7 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
     const char* __restrict__ q, const char* __restrict__ K, const char* __restrict__ abstract, int chunk_size,
     int k_tokens, int max_rounds, int node_cap, int32_t* __restrict__ ref_off, float* __restrict__ ref_score,
     int32_t* __restrict__ ref_count, int32_t* __restrict__ ref_evals, int32_t* __restrict__ ref_status,
-    TreeNode* nodes_a, TreeNode* nodes_b, int32_t* pos_buf, int n_ctx, int c_max, int n_kv_heads, int G) {
+    TreeNode* nodes_a, TreeNode* nodes_b, int32_t* pos_buf, int32_t* task_buf, int n_ctx, int c_max, int n_kv_heads, int G) {
     constexpr int ROWB = Row<T>::kRowBytes;
     constexpr int EPL = T::kEpl;
     __shared__ TreeLds S;
@@ -147,6 +163,11 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
     TreeNode* cur = nodes_a + bh * (size_t)node_cap;
     TreeNode* nxt = nodes_b + bh * (size_t)node_cap;
     int32_t* pos = pos_buf + bh * (size_t)node_cap;
+    int32_t* task = task_buf + bh * (size_t)node_cap;
+    constexpr int LPR = Row<T>::kLanesPerRow;
+    constexpr int kGroups = kTreeThreads / LPR;              // node evaluations in flight per workgroup
+    const int gid = tid / LPR;
+    const bool g_lead = (tid % LPR) == 0;
     const char* Kbh = K + bh * (size_t)n_ctx * ROWB;
     const char* Abh = abstract + bh * (size_t)c_max * 2 * ROWB;
 
@@ -161,10 +182,10 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
     __syncthreads();
 
     // ---- initial chunks: bounds from the abstract rows (kmax row, kmin row) ----------
-    for (int c = wave; c < m0; c += kTreeWaves) {
+    for (int c = gid; c < m0; c += kGroups) {
         float U, L;
         tree_eval<T>(Abh + (size_t)c * 2 * ROWB, 2, S.q, G, &U, &L);
-        if (lane == 0) {
+        if (g_lead) {
             TreeNode nd;
             nd.start = c * chunk_size;
             nd.size = min(chunk_size, n_ctx - c * chunk_size);
@@ -275,32 +296,25 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
             status = 1;
             break;
         }
-        // ---- a wave takes a node: copy it, or split it and evaluate the halves -----------
-        for (int i = wave; i < n; i += kTreeWaves) {
+        // ---- unsplit nodes move to their new place; split nodes are listed -----------------
+        // (pos[i] - i = number of splits before node i = its slot in the list)
+        for (int i = tid; i < n; i += kTreeThreads) {
             const TreeNode nd = cur[i];
             const int p = pos[i];
-            const bool split = nd.U >= v && !(nd.L > mu) && nd.size > 1;      // wave-uniform
-            if (!split) {
-                if (lane == 0) nxt[p] = nd;
-                continue;
-            }
+            if (nd.U >= v && !(nd.L > mu) && nd.size > 1) task[p - i] = i;
+            else nxt[p] = nd;
+        }
+        __syncthreads();
+        // ---- a lane group takes one half of a listed node and evaluates it from its keys -----
+        for (int t = gid; t < 2 * n_split; t += kGroups) {
+            const int parent = task[t >> 1], second = t & 1;
+            const TreeNode nd = cur[parent];
             const int left = (nd.size + 1) / 2;
-            float U0, L0, U1, L1;
-            tree_eval<T>(Kbh + (size_t)nd.start * ROWB, left, S.q, G, &U0, &L0);
-            tree_eval<T>(Kbh + (size_t)(nd.start + left) * ROWB, nd.size - left, S.q, G, &U1, &L1);
-            if (lane == 0) {
-                TreeNode a, c;
-                a.start = nd.start;
-                a.size = left;
-                a.U = U0;
-                a.L = L0;
-                c.start = nd.start + left;
-                c.size = nd.size - left;
-                c.U = U1;
-                c.L = L1;
-                nxt[p] = a;
-                nxt[p + 1] = c;
-            }
+            TreeNode c;
+            c.start = second ? nd.start + left : nd.start;
+            c.size = second ? nd.size - left : left;
+            tree_eval<T>(Kbh + (size_t)c.start * ROWB, c.size, S.q, G, &c.U, &c.L);
+            if (g_lead) nxt[pos[parent] + second] = c;
         }
         __syncthreads();
         TreeNode* tmp = cur;
@@ -363,7 +377,7 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
 }
 
 size_t tree_workspace_bytes(const leoam_shape* s, int node_cap) {
-    return (size_t)s->batch * s->n_kv_heads * (size_t)node_cap * (2 * sizeof(TreeNode) + sizeof(int32_t));
+    return (size_t)s->batch * s->n_kv_heads * (size_t)node_cap * (2 * sizeof(TreeNode) + 2 * sizeof(int32_t));
 }
 
 hipError_t tree_refine_dispatch(const leoam_shape* s, const void* q, const void* K, const void* abstract,
@@ -374,12 +388,13 @@ hipError_t tree_refine_dispatch(const leoam_shape* s, const void* q, const void*
     TreeNode* a = (TreeNode*)workspace;
     TreeNode* b = a + units * (size_t)node_cap;
     int32_t* pos = (int32_t*)(b + units * (size_t)node_cap);
+    int32_t* task = pos + units * (size_t)node_cap;
     dim3 grid(s->n_kv_heads, s->batch), block(kTreeThreads);
     const int G = s->n_q_heads / s->n_kv_heads;
 #define LEOAM_TREE(TT)                                                                                           \
     hipLaunchKernelGGL(tree_refine_kernel<TT>, grid, block, 0, stream, (const char*)q, (const char*)K,            \
                        (const char*)abstract, chunk_size, k_tokens, max_rounds, node_cap, ref_off, ref_score,    \
-                       ref_count, ref_evals, ref_status, a, b, pos, s->n_ctx, s->c_max, s->n_kv_heads, G)
+                       ref_count, ref_evals, ref_status, a, b, pos, task, s->n_ctx, s->c_max, s->n_kv_heads, G)
     switch (s->kv_dtype) {
     case LEOAM_F32: LEOAM_TREE(F32); break;
     case LEOAM_F16: LEOAM_TREE(F16); break;
