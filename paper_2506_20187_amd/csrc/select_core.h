@@ -70,14 +70,22 @@ __device__ __forceinline__ uint64_t block_excl_scan(uint64_t v, uint64_t* wave_s
     return base + incl - v;
 }
 
+constexpr int kStageItems = 256;                  // items a wave transposes at a time
+constexpr int kStageStride = kStageItems + 4;
+
 // LDS of one selection
 struct SelectLds {
     uint64_t hist[kBins];
     uint64_t wave_sums[kSelWaves];
     uint32_t red_min[kSelWaves], red_max[kSelWaves];
     uint32_t sh_lo, sh_hi, sh_done, sh_nbin, sh_ncand;
-    uint64_t cand_ki[kMaxCand], cand_tot[kMaxCand];
-    uint32_t cand_keep[kMaxCand];
+    union {
+        struct {
+            uint64_t cand_ki[kMaxCand], cand_tot[kMaxCand];
+            uint32_t cand_keep[kMaxCand];
+        };
+        uint32_t stage[kSelWaves][kStageStride];      // load stage only: per-wave transposition buffer
+    };
     uint64_t sh_above;
 };
 
@@ -111,10 +119,61 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
     // condition would be waited for on its own, one memory round trip per chunk)
     int offv[kIpt + 1];
     float sc[kIpt];
+    if constexpr (kIpt < 4) {
 #pragma unroll
-    for (int i = 0; i <= kIpt; ++i) offv[i] = off[min(c0 + i, c_max)];
+        for (int i = 0; i <= kIpt; ++i) offv[i] = off[min(c0 + i, c_max)];
 #pragma unroll
-    for (int i = 0; i < kIpt; ++i) sc[i] = srow[min(c0 + i, c_max - 1)];
+        for (int i = 0; i < kIpt; ++i) sc[i] = srow[min(c0 + i, c_max - 1)];
+    } else {
+        // A lane's kIpt consecutive items are 4*kIpt bytes apart from its neighbour's: read
+        // directly, every load instruction would touch 64 * kIpt * 4 / 128 cache lines.  The
+        // wave reads its 64 * kIpt items with consecutive lanes on consecutive items instead
+        // and transposes them through LDS, 256 items at a time.
+        const int wbase = wave * LEOAM_WAVE * kIpt;
+        float rs[kIpt];
+        int ro[kIpt];
+#pragma unroll
+        for (int j = 0; j < kIpt; ++j) {
+            rs[j] = srow[min(wbase + LEOAM_WAVE * j + lane, c_max - 1)];
+            ro[j] = off[min(wbase + LEOAM_WAVE * j + lane, c_max)];
+        }
+        const int ro_end = off[min(wbase + LEOAM_WAVE * kIpt, c_max)];
+        constexpr int kPerBlock = kStageItems / kIpt;          // lanes whose items a block holds
+        uint32_t* st = L.stage[wave];
+        const int my_block = lane / kPerBlock, base = (lane % kPerBlock) * kIpt;
+        auto wave_sync = [] {
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+            __builtin_amdgcn_wave_barrier();
+        };
+#pragma unroll
+        for (int blk = 0; blk < kIpt / 4; ++blk) {
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) st[LEOAM_WAVE * jj + lane] = float_to_bits(rs[4 * blk + jj]);
+            wave_sync();
+            if (my_block == blk) {
+#pragma unroll
+                for (int i = 0; i < kIpt; ++i) sc[i] = bits_to_float(st[base + i]);
+            }
+            wave_sync();
+        }
+#pragma unroll
+        for (int blk = 0; blk < kIpt / 4; ++blk) {
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) st[LEOAM_WAVE * jj + lane] = (uint32_t)ro[4 * blk + jj];
+            // the boundary after the block's last item: the first item of the next block, or of the next wave
+            int after = ro_end;
+            if constexpr (kIpt > 4) {
+                if (blk + 1 < kIpt / 4) after = ro[4 * (blk + 1 < kIpt / 4 ? blk + 1 : blk)];
+            }
+            if (lane == 0) st[kStageItems] = (uint32_t)after;
+            wave_sync();
+            if (my_block == blk) {
+#pragma unroll
+                for (int i = 0; i <= kIpt; ++i) offv[i] = (int)st[base + i];
+            }
+            wave_sync();
+        }
+    }
     int prev = min(max(offv[0], 0), n_ctx);
     R.first_tok = prev;
 #pragma unroll
