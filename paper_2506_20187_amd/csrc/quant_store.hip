@@ -164,7 +164,8 @@ __global__ __launch_bounds__(kQAbsWaves* LEOAM_WAVE) void abstract_build_q_kerne
 // sparse decode attention over the compressed store (Eq. 1 over the kept chunks)
 // ---------------------------------------------------------------------------
 constexpr int kQGroups = kAttWaves * 4;            // 16-lane groups per workgroup
-constexpr int kQTile = kQGroups * kAttRows;        // tokens per tile (128)
+constexpr int kQRows = 4;                          // rows per lane group per tile
+constexpr int kQTile = kQGroups * kQRows;          // tokens per tile (64)
 constexpr int kQMaxSel = 1024;                     // kept chunks per (b,h) held in LDS
 
 template <int G>
@@ -276,12 +277,12 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_q_kernel(
         }
         __syncthreads();
 
-        float z[kAttRows][G], vx[kAttRows][EPL], sv[kAttRows], zv[kAttRows];
+        float z[kQRows][G], vx[kQRows][EPL], sv[kQRows], zv[kQRows];
         float mt[G];
 #pragma unroll
         for (int g = 0; g < G; ++g) mt[g] = m_run[g];
 #pragma unroll
-        for (int j = 0; j < kAttRows; ++j) {
+        for (int j = 0; j < kQRows; ++j) {
             const int slot = j * kQGroups + wave * 4 + grp;
             const int k = tok_k[slot];
             const int kk = max(k, 0);
@@ -313,7 +314,7 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_q_kernel(
             for (int e = 0; e < EPL; ++e) acc[g][e] *= corr;
         }
 #pragma unroll
-        for (int j = 0; j < kAttRows; ++j) {
+        for (int j = 0; j < kQRows; ++j) {
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 const float p = exp2_or_zero(z[j][g], m_run[g]);

@@ -544,10 +544,12 @@ int attention_recommended_splits(const leoam_shape* s, int max_tokens) {
     if (max_tokens <= 0 || max_tokens > s->n_ctx) max_tokens = s->n_ctx;
     // smallest range a workgroup takes: one tile per lane group (fp32) / one 16-token tile per wave
     const int granule = (s->kv_dtype == LEOAM_F32) ? kAttWaves * 2 * kAttRows
-                        : (s->kv_dtype == LEOAM_Q8Q4) ? kAttWaves * 4 * kAttRows : kMfmaGranule;
+                        : (s->kv_dtype == LEOAM_Q8Q4) ? kAttWaves * 4 * 4 : kMfmaGranule;
     const int by_tokens = (max_tokens + granule - 1) / granule;
     const int units = s->batch * s->n_kv_heads;
-    int want = (768 + units - 1) / units;        // about three resident workgroups per compute unit
+    // about three resident workgroups per compute unit; the quantised kernel holds two
+    const int target = (s->kv_dtype == LEOAM_Q8Q4) ? 512 : 768;
+    int want = (target + units - 1) / units;
     if (want > by_tokens) want = by_tokens;
     if (want > kAttMaxSplits) want = kAttMaxSplits;
     if (want < 1) want = 1;
