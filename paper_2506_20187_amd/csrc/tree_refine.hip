@@ -52,7 +52,7 @@ __device__ __forceinline__ float tree_unkey(uint32_t k) {
 }
 
 struct TreeLds {
-    double q[kTreeMaxG][LEOAM_D];
+    double qpos[kTreeMaxG][LEOAM_D], qneg[kTreeMaxG][LEOAM_D];      // max(q, 0) and min(q, 0)
     uint32_t hist[2][256];
     uint32_t wave_tot[kTreeWaves];
     uint32_t prefix[2], rank[2];
@@ -97,12 +97,12 @@ template <int kLanes> __device__ __forceinline__ double group_sum_d(double v) {
 // then U = max_j sum_d max(q k_max, q k_min) and L = max_j sum_d min(..), each sum
 // in double, rounded once to float.  A wave evaluates 4 (2) nodes at a time.
 template <typename T>
-__device__ __forceinline__ void tree_eval(const char* rows, int n_rows, const double (*q)[LEOAM_D], int G, float* U,
-                                          float* L) {
+__device__ __forceinline__ void tree_eval(const char* rows, int n_rows, const double (*qpos)[LEOAM_D],
+                                          const double (*qneg)[LEOAM_D], int G, float* U, float* L) {
     constexpr int LPR = Row<T>::kLanesPerRow;
     constexpr int EPL = T::kEpl;
     constexpr int ROWB = Row<T>::kRowBytes;
-    const int col = (lane_id() % LPR) * EPL;
+    const int lane_in_row = lane_id() % LPR, col = lane_in_row * EPL;
     float mx[EPL], mn[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) {
@@ -112,6 +112,18 @@ __device__ __forceinline__ void tree_eval(const char* rows, int n_rows, const do
     // eight rows in flight; a row index past the end re-reads the last row (harmless for max / min,
     // and the loads stay unconditional)
     constexpr int kBatch = 8;
+    if (n_rows <= 2) {          // an initial chunk: its kmax row and its kmin row
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            float x[EPL];
+            unpack<T>(load16(rows, (size_t)min(j, n_rows - 1) * ROWB + (size_t)col * T::kBytes), x);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+                mx[e] = fmaxf(mx[e], x[e]);
+                mn[e] = fminf(mn[e], x[e]);
+            }
+        }
+    } else
     for (int r0 = 0; r0 < n_rows; r0 += kBatch) {
         uint4 v[kBatch];
 #pragma unroll
@@ -130,13 +142,19 @@ __device__ __forceinline__ void tree_eval(const char* rows, int n_rows, const do
     }
     float ub = -INFINITY, lb = -INFINITY;
     for (int j = 0; j < G; ++j) {
-        double u = 0.0, l = 0.0;
+        // max(q k_max, q k_min) = max(q,0) k_max + min(q,0) k_min (k_max >= k_min): one of the two
+        // products is zero and every product is exact in double.  Four independent chains.
+        double u0 = 0.0, u1 = 0.0, l0 = 0.0, l1 = 0.0;
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
-            const double a = q[j][col + e] * (double)mx[e], b = q[j][col + e] * (double)mn[e];
-            u += fmax(a, b);
-            l += fmin(a, b);
+            const double qp = qpos[j][e * LPR + lane_in_row], qn = qneg[j][e * LPR + lane_in_row];
+            const double hi = (double)mx[e], lo = (double)mn[e];
+            u0 = fma(qp, hi, u0);
+            u1 = fma(qn, lo, u1);
+            l0 = fma(qp, lo, l0);
+            l1 = fma(qn, hi, l1);
         }
+        double u = u0 + u1, l = l0 + l1;
         u = group_sum_d<LPR>(u);
         l = group_sum_d<LPR>(l);
         ub = fmaxf(ub, (float)u + 0.0f);
@@ -177,14 +195,18 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
         float x[EPL];
         unpack<T>(load16(q, ((size_t)b * n_kv_heads * G + (size_t)h * G + j) * ROWB + (size_t)c * T::kBytes), x);
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) S.q[j][c + e] = (double)x[e];
+        for (int e = 0; e < EPL; ++e) {
+            // channel c + e sits at [e][c / EPL]: the lanes of a row then read consecutive doubles
+            S.qpos[j][e * (LEOAM_D / EPL) + c / EPL] = (double)fmaxf(x[e], 0.f);
+            S.qneg[j][e * (LEOAM_D / EPL) + c / EPL] = (double)fminf(x[e], 0.f);
+        }
     }
     __syncthreads();
 
     // ---- initial chunks: bounds from the abstract rows (kmax row, kmin row) ----------
     for (int c = gid; c < m0; c += kGroups) {
         float U, L;
-        tree_eval<T>(Abh + (size_t)c * 2 * ROWB, 2, S.q, G, &U, &L);
+        tree_eval<T>(Abh + (size_t)c * 2 * ROWB, 2, S.qpos, S.qneg, G, &U, &L);
         if (g_lead) {
             TreeNode nd;
             nd.start = c * chunk_size;
@@ -313,7 +335,7 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
             TreeNode c;
             c.start = second ? nd.start + left : nd.start;
             c.size = second ? nd.size - left : left;
-            tree_eval<T>(Kbh + (size_t)c.start * ROWB, c.size, S.q, G, &c.U, &c.L);
+            tree_eval<T>(Kbh + (size_t)c.start * ROWB, c.size, S.qpos, S.qneg, G, &c.U, &c.L);
             if (g_lead) nxt[pos[parent] + second] = c;
         }
         __syncthreads();
