@@ -179,7 +179,6 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_q_kernel(
     __shared__ float4 ch_par[kQMaxSel];            // scale_k, zero_k, scale_v, zero_v
     __shared__ int32_t ch_bits[kQMaxSel];
     __shared__ int32_t prefix[kQMaxSel + 1];
-    __shared__ int32_t tok_k[kQTile], tok_o[kQTile];   // kept-list position -> (chunk slot, token inside chunk)
     __shared__ float xw[kAttWaves][G][kPartStride];
     __shared__ int32_t sh_total;
 
@@ -258,49 +257,76 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_q_kernel(
         for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
     }
 
-    for (int tb = r0; tb < r1; tb += kQTile) {
-        __syncthreads();
-        for (int i = tid; i < kQTile; i += kAttThreads) {
-            const int x = tb + i;
-            int k = -1, o = 0;
-            if (x < r1) {
-                int lo = 0, hi = cnt;          // largest k with prefix[k] <= x
-                while (hi - lo > 1) {
-                    const int mid = (lo + hi) >> 1;
-                    if (prefix[mid] <= x) lo = mid; else hi = mid;
-                }
-                k = lo;
-                o = x - prefix[lo];
-            }
-            tok_k[i] = k;
-            tok_o[i] = o;
+    // From here on the four waves are independent streams: a wave takes a contiguous quarter of
+    // the split's range and walks it in tiles of 16 tokens, lane group grp holding tokens
+    // 4*grp .. 4*grp+3 of the tile.  The raw codes of the next tile are in flight while this one
+    // is expanded and used.  All loads are unconditional (a token past the end re-reads the last
+    // one and gets weight 0); the chunk slot of a token is found by walking the prefix table
+    // forward from the previous token's slot.
+    const int per_wave = per_split / kAttWaves;
+    const int w0 = min(r1, r0 + wave * per_wave), w1 = min(r1, w0 + per_wave);
+    struct RawRows {
+        uint32_t k0[kQRows], k1[kQRows], v0[kQRows], v1[kQRows];      // two dwords per row and tensor
+        int slot[kQRows];                                             // kept-list slot of the row's chunk, -1 = no token
+    };
+    int lo = 0;
+    if (w0 < w1) {
+        const int x = min(w0 + kQRows * grp, w1 - 1);
+        int hi = cnt;                  // largest k with prefix[k] <= x
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (prefix[mid] <= x) lo = mid; else hi = mid;
         }
-        __syncthreads();
-
-        float z[kQRows][G], vx[kQRows][EPL], sv[kQRows], zv[kQRows];
+    }
+    auto fetch = [&](int tb, RawRows& R) {
+#pragma unroll
+        for (int j = 0; j < kQRows; ++j) {
+            const int x = tb + kQRows * grp + j, xx = min(x, w1 - 1);
+            while (prefix[lo + 1] <= xx) ++lo;      // ends: prefix[cnt] = total > xx
+            const int bits = ch_bits[lo];
+            const size_t row = (size_t)ch_off[lo] + (size_t)(xx - prefix[lo]) * (bits == 8 ? LEOAM_D : LEOAM_D / 2);
+            // 8-bit rows: this lane's 8 bytes as two dwords; 4-bit rows: its 4 bytes (read twice)
+            const size_t a0 = row + (bits == 8 ? 8 : 4) * c16, a1 = a0 + (bits == 8 ? 4 : 0);
+            R.k0[j] = *reinterpret_cast<const uint32_t*>(kblob + a0);
+            R.k1[j] = *reinterpret_cast<const uint32_t*>(kblob + a1);
+            R.v0[j] = *reinterpret_cast<const uint32_t*>(vblob + a0);
+            R.v1[j] = *reinterpret_cast<const uint32_t*>(vblob + a1);
+            R.slot[j] = (x < w1) ? lo : -1;
+        }
+    };
+    auto expand = [&](uint32_t w0_, uint32_t w1_, int bits, float* x) {
+        if (bits == 8) {
+            x[0] = (float)(w0_ & 0xffu); x[1] = (float)((w0_ >> 8) & 0xffu);
+            x[2] = (float)((w0_ >> 16) & 0xffu); x[3] = (float)(w0_ >> 24);
+            x[4] = (float)(w1_ & 0xffu); x[5] = (float)((w1_ >> 8) & 0xffu);
+            x[6] = (float)((w1_ >> 16) & 0xffu); x[7] = (float)(w1_ >> 24);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = (float)((w0_ >> (4 * e)) & 0xfu);
+        }
+    };
+    auto consume = [&](const RawRows& R) {
+        float z[kQRows][G], sv[kQRows], zv[kQRows];
+        int bits_of[kQRows];
         float mt[G];
 #pragma unroll
         for (int g = 0; g < G; ++g) mt[g] = m_run[g];
 #pragma unroll
         for (int j = 0; j < kQRows; ++j) {
-            const int slot = j * kQGroups + wave * 4 + grp;
-            const int k = tok_k[slot];
-            const int kk = max(k, 0);
-            const int bits = ch_bits[kk];
+            const int kk = max(R.slot[j], 0);
             const float4 par = ch_par[kk];
-            const size_t rowoff = (size_t)ch_off[kk] + (size_t)tok_o[slot] * (bits == 8 ? LEOAM_D : LEOAM_D / 2);
-            float kx[EPL];
-            load_codes(kblob + rowoff, bits, c16, kx);
-            load_codes(vblob + rowoff, bits, c16, vx[j]);
+            bits_of[j] = ch_bits[kk];
             sv[j] = par.z;
             zv[j] = par.w;
+            float kx[EPL];
+            expand(R.k0[j], R.k1[j], bits_of[j], kx);
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 float d = 0.f;
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) d = fmaf(qs[g][e], kx[e], d);
                 d = row16_sum(d);
-                z[j][g] = (k >= 0) ? fmaf(par.x, d, par.y * qsum[g]) : -INFINITY;
+                z[j][g] = (R.slot[j] >= 0) ? fmaf(par.x, d, par.y * qsum[g]) : -INFINITY;
                 mt[g] = fmaxf(mt[g], z[j][g]);
             }
         }
@@ -315,6 +341,8 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_q_kernel(
         }
 #pragma unroll
         for (int j = 0; j < kQRows; ++j) {
+            float vx[EPL];
+            expand(R.v0[j], R.v1[j], bits_of[j], vx);
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 const float p = exp2_or_zero(z[j][g], m_run[g]);
@@ -322,8 +350,21 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_q_kernel(
                 accz[g] = fmaf(p, zv[j], accz[g]);
                 const float ps = p * sv[j];
 #pragma unroll
-                for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(ps, vx[j][e], acc[g][e]);
+                for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(ps, vx[e], acc[g][e]);
             }
+        }
+    };
+    if (w0 < w1) {
+        constexpr int kWaveTile = 4 * kQRows;        // tokens of a wave's tile
+        RawRows cur, nxt;
+        fetch(w0, cur);
+        for (int tb = w0; tb < w1; tb += 2 * kWaveTile) {
+            fetch(tb + kWaveTile, nxt);
+            __builtin_amdgcn_sched_barrier(0);       // keep the loads ahead of the tile's arithmetic
+            consume(cur);
+            fetch(tb + 2 * kWaveTile, cur);
+            __builtin_amdgcn_sched_barrier(0);
+            if (tb + kWaveTile < w1) consume(nxt);
         }
     }
     // the zero-point share is the same for every channel: fold it in, then merge as usual
