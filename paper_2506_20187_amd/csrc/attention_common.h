@@ -24,18 +24,35 @@ __device__ __forceinline__ float exp2_or_zero(float x, float m) {
 constexpr int kPartStride = LEOAM_D + 2;
 
 
+// Where the combined result of a (b, q head) goes when the splits are merged inside the launch
+// (arrivals == nullptr: a second kernel merges the partials instead).
+struct MergeInLaunch {
+    int32_t* arrivals;      // one counter per (b, kv head), zero between launches
+    float* out;             // [B, Hq, D]
+    float* lse;             // [B, Hq] or nullptr
+};
+constexpr int kInLaunchMergeBatch = 8;
+
 // Cross-wave combine of the workgroup's online-softmax states into the partial
 // of this split.  xw[w][g] = (acc[D], m, l) of wave w, head g, log2 domain.
-// (Combining the splits in the same launch would need a device-scope release /
-// acquire per workgroup; on this part that is an L2 write-back and invalidate
-// per fence and costs far more than the small second kernel below.)
+//
+// With `mg.arrivals` the splits of a (b, kv head) are also merged in this launch,
+// without device-scope fences (on this part a fence is an L2 write-back and
+// invalidate): the partial is published with agent-scope relaxed atomic stores
+// (write-through), the wave waits for them, one lane takes a ticket from the
+// (b, kv head)'s agent-scope counter, and the workgroup that draws the last
+// ticket reads every partial back with agent-scope atomic loads, folds them in
+// split order (so the result does not depend on which workgroup that is), writes
+// out / lse and resets the counter.  No workgroup waits for another.
 template <int G>
-__device__ __forceinline__ void finish_split(float (*xw)[G][kPartStride], float* __restrict__ partial, int b, int h,
-                                             int split, int n_splits, int n_kv_heads) {
+__device__ __forceinline__ void finish_split(float (*xw)[G][kPartStride], float* partial, int b, int h, int split,
+                                             int n_splits, int n_kv_heads, const MergeInLaunch mg = {nullptr, nullptr, nullptr}) {
+    __shared__ int32_t sh_last;
     const int tid = threadIdx.x;
     const size_t bh = (size_t)b * n_kv_heads + h;
     __syncthreads();
     float* part = partial + bh * G * (size_t)n_splits * kPartStride;
+    const bool in_launch = mg.arrivals != nullptr;
     for (int i = tid; i < G * kPartStride; i += kAttThreads) {
         const int g = i / kPartStride, d = i % kPartStride;
         float m = -INFINITY;
@@ -51,7 +68,56 @@ __device__ __forceinline__ void finish_split(float (*xw)[G][kPartStride], float*
                 v += a * (d < LEOAM_D ? xw[w][g][d] : xw[w][g][LEOAM_D + 1]);
             }
         }
-        part[((size_t)g * n_splits + split) * kPartStride + d] = v;
+        float* dst = &part[((size_t)g * n_splits + split) * kPartStride + d];
+        if (in_launch) __hip_atomic_store(dst, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else *dst = v;
+    }
+    if (!in_launch) return;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wave's stores have been acknowledged
+    __syncthreads();
+    if (tid == 0) {
+        const int ticket = __hip_atomic_fetch_add(&mg.arrivals[bh], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int is_last = ticket == n_splits - 1;
+        if (is_last) __hip_atomic_store(&mg.arrivals[bh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sh_last = is_last;
+    }
+    __syncthreads();
+    if (!sh_last) return;
+    for (int i = tid; i < G * LEOAM_D; i += kAttThreads) {
+        const int g = i / LEOAM_D, d = i % LEOAM_D;
+        const float* base = part + (size_t)g * n_splits * kPartStride;
+        float m = -INFINITY, l = 0.f, o = 0.f;
+        for (int s0 = 0; s0 < n_splits; s0 += kInLaunchMergeBatch) {
+            float ms[kInLaunchMergeBatch], ls[kInLaunchMergeBatch], os[kInLaunchMergeBatch];
+#pragma unroll
+            for (int j = 0; j < kInLaunchMergeBatch; ++j) {
+                const float* p = base + (size_t)min(s0 + j, n_splits - 1) * kPartStride;
+                ms[j] = __hip_atomic_load(&p[LEOAM_D], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ls[j] = __hip_atomic_load(&p[LEOAM_D + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                os[j] = __hip_atomic_load(&p[d], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (s0 + j >= n_splits) {
+                    ms[j] = -INFINITY;
+                    ls[j] = 0.f;
+                    os[j] = 0.f;
+                }
+            }
+            float mb = m;
+#pragma unroll
+            for (int j = 0; j < kInLaunchMergeBatch; ++j) mb = fmaxf(mb, ms[j]);
+            const float c = exp2_or_zero(m, mb);
+            o *= c;
+            l *= c;
+            m = mb;
+#pragma unroll
+            for (int j = 0; j < kInLaunchMergeBatch; ++j) {
+                const float a = exp2_or_zero(ms[j], m);
+                o += a * os[j];
+                l += a * ls[j];
+            }
+        }
+        const size_t bj = bh * G + g;
+        mg.out[bj * LEOAM_D + d] = (l > 0.f) ? o / l : 0.f;
+        if (mg.lse && d == 0) mg.lse[bj] = (l > 0.f) ? (m + log2f(l)) * kLn2 : -INFINITY;
     }
 }
 

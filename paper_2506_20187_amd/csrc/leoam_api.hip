@@ -12,7 +12,7 @@ hipError_t topk_select_dispatch(const leoam_shape*, const float*, const int32_t*
                                 int32_t*, int32_t*, hipStream_t);
 hipError_t attention_dispatch(const leoam_shape*, const void*, const void*, const void*, const void*, const int32_t*,
                               const int32_t*, const int32_t*, const int32_t*, float, float*, float*, void*, size_t,
-                              hipStream_t);
+                              int32_t*, hipStream_t);
 hipError_t abstract_build_q_dispatch(const leoam_shape*, const void*, const void*, const int32_t*, const int32_t*, void*,
                                      hipStream_t);
 int attention_q_max_sel();
@@ -166,7 +166,7 @@ int sparse_chunk_attention_decode(const leoam_shape* shape, const void* q, const
     if (!workspace || workspace_bytes < attention_min_workspace_bytes(shape)) return LEOAM_E_WORKSPACE;
     if (((uintptr_t)workspace & 15u) != 0) return LEOAM_E_WORKSPACE;
     return from_hip(attention_dispatch(shape, q, K, V, qmeta, chunk_off, n_chunks, sel_idx, sel_count, softmax_scale, out, lse,
-                                       workspace, workspace_bytes, (hipStream_t)stream));
+                                       workspace, workspace_bytes, nullptr, (hipStream_t)stream));
 }
 
 int chunk_select_attention_decode(const leoam_shape* shape, const float* score_ub, const void* q, const void* K,

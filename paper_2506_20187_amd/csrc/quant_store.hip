@@ -173,7 +173,7 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_q_kernel(
     const char* __restrict__ q, const unsigned char* __restrict__ kblob, const unsigned char* __restrict__ vblob,
     const QChunk* __restrict__ qmeta, const int32_t* __restrict__ chunk_off, const int32_t* __restrict__ n_chunks,
     const int32_t* __restrict__ sel_idx, const int32_t* __restrict__ sel_count, float scale_log2,
-    float* __restrict__ partial, int n_splits, int c_max, int k_max, int n_kv_heads, int n_ctx) {
+    float* partial, int n_splits, int c_max, int k_max, int n_kv_heads, int n_ctx, MergeInLaunch mg) {
     constexpr int EPL = 8;
     __shared__ long long ch_off[kQMaxSel];
     __shared__ float4 ch_par[kQMaxSel];            // scale_k, zero_k, scale_v, zero_v
@@ -402,7 +402,7 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_q_kernel(
             }
         }
     }
-    finish_split<G>(xw, partial, b, h, split, n_splits, n_kv_heads);
+    finish_split<G>(xw, partial, b, h, split, n_splits, n_kv_heads, mg);
 }
 
 int attention_q_max_sel() { return kQMaxSel; }
@@ -422,12 +422,14 @@ hipError_t abstract_build_q_dispatch(const leoam_shape* s, const void* kblob, co
 hipError_t attention_q_dispatch(const leoam_shape* s, const void* q, const void* K, const void* V, const void* qmeta,
                                 const int32_t* chunk_off, const int32_t* n_chunks, const int32_t* sel_idx,
                                 const int32_t* sel_count, float scale, float* out, float* lse, float* ws, int n_splits,
-                                hipStream_t stream) {
+                                int32_t* arrivals, hipStream_t stream) {
     dim3 grid(n_splits, s->n_kv_heads, s->batch);
+    if (n_splits > 2 * kInLaunchMergeBatch) arrivals = nullptr;      // many splits: the merge kernel is faster
+    const MergeInLaunch mg = {arrivals, out, lse};
 #define LEOAM_ATTQ(GG)                                                                                                  \
     hipLaunchKernelGGL((sparse_attention_q_kernel<GG>), grid, dim3(kAttThreads), 0, stream, (const char*)q,            \
                        (const unsigned char*)K, (const unsigned char*)V, (const QChunk*)qmeta, chunk_off, n_chunks,     \
-                       sel_idx, sel_count, scale * kLog2e, ws, n_splits, s->c_max, s->k_max, s->n_kv_heads, s->n_ctx)
+                       sel_idx, sel_count, scale * kLog2e, ws, n_splits, s->c_max, s->k_max, s->n_kv_heads, s->n_ctx, mg)
     switch (s->n_q_heads / s->n_kv_heads) {
     case 1: LEOAM_ATTQ(1); break;
     case 2: LEOAM_ATTQ(2); break;
@@ -436,7 +438,7 @@ hipError_t attention_q_dispatch(const leoam_shape* s, const void* q, const void*
     }
 #undef LEOAM_ATTQ
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || arrivals) return e;
     return launch_attention_merge(s, ws, n_splits, out, lse, stream);
 }
 

@@ -371,7 +371,7 @@ hipError_t topk_select_dispatch(const leoam_shape*, const float*, const int32_t*
                                 int32_t*, int32_t*, hipStream_t);
 hipError_t attention_dispatch(const leoam_shape*, const void*, const void*, const void*, const void*, const int32_t*,
                               const int32_t*, const int32_t*, const int32_t*, float, float*, float*, void*, size_t,
-                              hipStream_t);
+                              int32_t*, hipStream_t);
 size_t attention_workspace_bytes(const leoam_shape*, int);
 size_t attention_min_workspace_bytes(const leoam_shape*);
 
@@ -463,8 +463,9 @@ hipError_t select_attention_dispatch(const leoam_shape* s, const float* score, c
         hipError_t e = topk_select_dispatch(s, score, chunk_off, n_chunks, max_chunks, token_budget, sel_idx, sel_count,
                                             sel_tokens, stream);
         if (e != hipSuccess) return e;
+        // the attention kernel merges its splits in the same launch, with the arrival counters of this workspace
         return attention_dispatch(s, q, K, V, qmeta, chunk_off, n_chunks, sel_idx, sel_count, scale, out, lse, body,
-                                  body_bytes, stream);
+                                  body_bytes, (int32_t*)workspace, stream);
     }
     size_t n = body_bytes / fused_part_bytes_per_split(s);
     const size_t cap = (size_t)fused_recommended_splits(s, token_budget > 0 ? token_budget : s->n_ctx);

@@ -83,8 +83,8 @@ template <typename T, int G>
 __global__ __launch_bounds__(kAttThreads) void sparse_attention_kernel(
     const char* __restrict__ q, const char* __restrict__ K, const char* __restrict__ V,
     const int32_t* __restrict__ chunk_off, const int32_t* __restrict__ n_chunks, const int32_t* __restrict__ sel_idx,
-    const int32_t* __restrict__ sel_count, float scale_log2, float* __restrict__ partial, int n_splits, int c_max,
-    int k_max, int n_kv_heads, int n_ctx) {
+    const int32_t* __restrict__ sel_count, float scale_log2, float* partial, int n_splits, int c_max,
+    int k_max, int n_kv_heads, int n_ctx, MergeInLaunch mg) {
     constexpr int LPR = Row<T>::kLanesPerRow;
     constexpr int RPL = Row<T>::kRowsPerLoad;          // lane groups per wave
     constexpr int EPL = T::kEpl;
@@ -278,7 +278,7 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_kernel(
             }
         }
     }
-    finish_split<G>(xw, partial, b, h, split, n_splits, n_kv_heads);
+    finish_split<G>(xw, partial, b, h, split, n_splits, n_kv_heads, mg);
 }
 
 
@@ -310,8 +310,8 @@ template <typename T, int G>
 __global__ __launch_bounds__(kAttThreads) void sparse_attention_mfma_kernel(
     const char* __restrict__ q, const char* __restrict__ K, const char* __restrict__ V,
     const int32_t* __restrict__ chunk_off, const int32_t* __restrict__ n_chunks, const int32_t* __restrict__ sel_idx,
-    const int32_t* __restrict__ sel_count, float scale_log2, float* __restrict__ partial, int n_splits, int c_max,
-    int k_max, int n_kv_heads, int n_ctx) {
+    const int32_t* __restrict__ sel_count, float scale_log2, float* partial, int n_splits, int c_max,
+    int k_max, int n_kv_heads, int n_ctx, MergeInLaunch mg) {
     constexpr int ROWB = LEOAM_D * 2;
     constexpr int EPL = 8;
 
@@ -526,7 +526,7 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_mfma_kernel(
             xw[wave][c16][LEOAM_D + 1] = l_run;
         }
     }
-    finish_split<G>(xw, partial, b, h, split, n_splits, n_kv_heads);
+    finish_split<G>(xw, partial, b, h, split, n_splits, n_kv_heads, mg);
 }
 
 hipError_t launch_attention_merge(const leoam_shape* s, const float* partial, int n_splits, float* out, float* lse,
@@ -566,20 +566,23 @@ template <typename T, int G>
 static hipError_t launch_attention(const leoam_shape* s, const void* q, const void* K, const void* V,
                                    const int32_t* chunk_off, const int32_t* n_chunks, const int32_t* sel_idx,
                                    const int32_t* sel_count, float scale, float* out, float* lse, void* workspace,
-                                   int n_splits, hipStream_t stream) {
+                                   int n_splits, int32_t* arrivals, hipStream_t stream) {
     dim3 grid(n_splits, s->n_kv_heads, s->batch);
+    // merging in the launch pays while one workgroup can fetch all partials in a round trip or two
+    if (n_splits > 2 * kInLaunchMergeBatch) arrivals = nullptr;
+    const MergeInLaunch mg = {arrivals, out, lse};
     const size_t dyn = (size_t)(2 * s->k_max + 1) * sizeof(int32_t);
     float* ws = (float*)workspace;
     if constexpr (T::kBytes == 2)
         hipLaunchKernelGGL((sparse_attention_mfma_kernel<T, G>), grid, dim3(kAttThreads), dyn, stream, (const char*)q,
                            (const char*)K, (const char*)V, chunk_off, n_chunks, sel_idx, sel_count, scale * kLog2e, ws,
-                           n_splits, s->c_max, s->k_max, s->n_kv_heads, s->n_ctx);
+                           n_splits, s->c_max, s->k_max, s->n_kv_heads, s->n_ctx, mg);
     else
         hipLaunchKernelGGL((sparse_attention_kernel<T, G>), grid, dim3(kAttThreads), dyn, stream, (const char*)q,
                            (const char*)K, (const char*)V, chunk_off, n_chunks, sel_idx, sel_count, scale * kLog2e, ws,
-                           n_splits, s->c_max, s->k_max, s->n_kv_heads, s->n_ctx);
+                           n_splits, s->c_max, s->k_max, s->n_kv_heads, s->n_ctx, mg);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || arrivals) return e;
     return launch_attention_merge(s, ws, n_splits, out, lse, stream);
 }
 
@@ -587,9 +590,9 @@ template <typename T>
 static hipError_t attention_by_group(const leoam_shape* s, const void* q, const void* K, const void* V,
                                      const int32_t* chunk_off, const int32_t* n_chunks, const int32_t* sel_idx,
                                      const int32_t* sel_count, float scale, float* out, float* lse, void* ws,
-                                     int n_splits, hipStream_t stream) {
+                                     int n_splits, int32_t* arrivals, hipStream_t stream) {
 #define LEOAM_ATT(GG) \
-    launch_attention<T, GG>(s, q, K, V, chunk_off, n_chunks, sel_idx, sel_count, scale, out, lse, ws, n_splits, stream)
+    launch_attention<T, GG>(s, q, K, V, chunk_off, n_chunks, sel_idx, sel_count, scale, out, lse, ws, n_splits, arrivals, stream)
     switch (s->n_q_heads / s->n_kv_heads) {
     case 1: return LEOAM_ATT(1);
     case 2: return LEOAM_ATT(2);
@@ -604,12 +607,12 @@ int attention_max_sel() { return kAttMaxSel; }
 hipError_t attention_q_dispatch(const leoam_shape* s, const void* q, const void* K, const void* V, const void* qmeta,
                                 const int32_t* chunk_off, const int32_t* n_chunks, const int32_t* sel_idx,
                                 const int32_t* sel_count, float scale, float* out, float* lse, float* ws, int n_splits,
-                                hipStream_t stream);      // quant_store.hip
+                                int32_t* arrivals, hipStream_t stream);      // quant_store.hip
 
 hipError_t attention_dispatch(const leoam_shape* s, const void* q, const void* K, const void* V, const void* qmeta,
                               const int32_t* chunk_off, const int32_t* n_chunks, const int32_t* sel_idx,
                               const int32_t* sel_count, float scale, float* out, float* lse, void* workspace,
-                              size_t workspace_bytes, hipStream_t stream) {
+                              size_t workspace_bytes, int32_t* arrivals, hipStream_t stream) {
     size_t n = workspace_bytes / part_bytes_per_split(s);
     const size_t cap = (size_t)attention_recommended_splits(s, s->n_ctx);
     if (n > cap) n = cap;
@@ -618,13 +621,13 @@ hipError_t attention_dispatch(const leoam_shape* s, const void* q, const void* K
     switch (s->kv_dtype) {
     case LEOAM_Q8Q4:
         return attention_q_dispatch(s, q, K, V, qmeta, chunk_off, n_chunks, sel_idx, sel_count, scale, out, lse, (float*)ws,
-                                    n_splits, stream);
+                                    n_splits, arrivals, stream);
     case LEOAM_F32:
-        return attention_by_group<F32>(s, q, K, V, chunk_off, n_chunks, sel_idx, sel_count, scale, out, lse, ws, n_splits, stream);
+        return attention_by_group<F32>(s, q, K, V, chunk_off, n_chunks, sel_idx, sel_count, scale, out, lse, ws, n_splits, arrivals, stream);
     case LEOAM_F16:
-        return attention_by_group<F16>(s, q, K, V, chunk_off, n_chunks, sel_idx, sel_count, scale, out, lse, ws, n_splits, stream);
+        return attention_by_group<F16>(s, q, K, V, chunk_off, n_chunks, sel_idx, sel_count, scale, out, lse, ws, n_splits, arrivals, stream);
     default:
-        return attention_by_group<BF16>(s, q, K, V, chunk_off, n_chunks, sel_idx, sel_count, scale, out, lse, ws, n_splits, stream);
+        return attention_by_group<BF16>(s, q, K, V, chunk_off, n_chunks, sel_idx, sel_count, scale, out, lse, ws, n_splits, arrivals, stream);
     }
 }
 

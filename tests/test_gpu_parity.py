@@ -454,12 +454,16 @@ def test_select_attention_one_call(L, oracle, dtype, G, C):
         assert np.abs(lse[fin] - want_lse[fin]).max() <= 1e-4 if fin.any() else True
         if ws is None:
             ws = ws_used
-    # the same workspace serves call after call without being cleared again
+    # the same workspace serves call after call without being cleared again, and the result does not
+    # depend on which workgroup happens to merge: bit-identical from call to call
     want_sel, want_cnt, want_tok = oracle.topk_select(score, packed, counts, 0, N // 8, k_max)
     want_out, _ = oracle.sparse_attention(q, K, V, packed, want_sel, want_cnt)
-    for _ in range(3):
+    first = None
+    for _ in range(4):
         sel, cnt, tok, out, lse, _ = gpu_select_attend(L, dtype, score, q, K, V, packed, counts, 0, N // 8, k_max, ws=ws)
         assert np.array_equal(sel, want_sel) and np.abs(out - want_out).max() <= TOL[dtype]
+        first = (out, lse) if first is None else first
+        assert np.array_equal(out, first[0]) and np.array_equal(lse, first[1])
     head = (B * Hkv * 4 + 255) // 256 * 256
     assert int(ws[:head].to(torch.int32).sum()) == 0           # counters are back at zero
 
