@@ -41,3 +41,32 @@ def test_host_side_argument_checks_without_gpu():
     assert lib.chunk_score(ctypes.byref(s), None, None, None, None, None, None) == -1
     bad = L.make_shape(1, 32, 8, 128, 131072, 8192, 9000, 2)
     assert lib.chunk_score(ctypes.byref(bad), None, None, None, None, None, None) == -1
+
+
+def test_host_side_checks_of_the_later_entry_points():
+    """Workspace sizes and argument refusals of the one-call step, the abstract maintenance and the tree
+    refinement are host arithmetic: no GPU needed."""
+    import paper_2506_20187_amd as L
+    lib = L.binding._lib
+    s = L.make_shape(16, 32, 8, 128, 131072, 4096, 256, 2)
+    fused, plain = L.leoam_fused_workspace_bytes(s, 4096), L.leoam_workspace_bytes(s, 4096)
+    assert fused >= plain + 16 * 8 * 4                     # arrival counters in front of the partials
+    assert L.leoam_fused_workspace_bytes(L.make_shape(16, 32, 8, 64, 131072, 4096, 256, 2), 4096) == 0
+    # tree refinement: node_cap below the initial chunk count, k outside [1, n_ctx], compressed store
+    t = L.make_shape(1, 4, 1, 128, 4096, 64, 1, 2)
+    assert L.leoam_tree_workspace_bytes(t, 1000) == 1 * 1 * 1000 * (2 * 16 + 2 * 4)
+    args = [None] * 3
+    def refine(shape, cs, k, rounds, cap):
+        return lib.chunk_tree_refine(ctypes.byref(shape), None, None, None, cs, k, rounds, cap, None, None, None, None,
+                                     None, None, 0, None)
+    assert refine(t, 64, 100, 10, 63) == -1                # 64 initial chunks do not fit 63 nodes
+    assert refine(t, 64, 0, 10, 128) == -1 and refine(t, 64, 4097, 10, 128) == -1
+    assert refine(t, 32, 100, 10, 256) == -1               # 128 initial chunks but the abstract has room for 64
+    assert refine(t, 64, 100, -1, 128) == -1
+    assert refine(L.make_shape(1, 4, 1, 128, 4096, 64, 1, 3), 64, 100, 10, 128) == -3
+    assert refine(t, 64, 100, 10, 128) == -1               # shape fine: null pointers are refused next
+    # abstract maintenance
+    assert lib.kv_chunk_abstract_append(ctypes.byref(t), None, None, None, 64, None, None, None) == -1
+    assert lib.kv_chunk_abstract_append(ctypes.byref(L.make_shape(1, 4, 1, 128, 4096, 64, 1, 3)), None, None, None, 64,
+                                        None, None, None) in (-1, -3)
+    assert lib.leoam_workspace_init(None, 16, None) == -1
