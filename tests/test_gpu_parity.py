@@ -538,6 +538,17 @@ def test_tree_refine_ties_and_deserts(L, oracle):
     assert ev[0, 0] < N // 8
 
 
+def test_tree_refine_full_context(L, oracle):
+    """128K tokens per head, chunks of 64, k = 4096 (the shape bench.py times): planted runs, and Gaussian keys
+    with a round limit (the tree then stops unfinished, which must match too)."""
+    K, q, hot = gen.make_desert_keys(1, 2, 4, 131072, clusters=128, cluster_len=(32, 32), dtype="bf16", device="cuda")
+    K, q = K.cpu(), q.cpu()
+    _, _, r_cnt, ev = check_tree(L, oracle, "bf16", q, K, 64, 4096, 64, 32768)
+    assert np.all(r_cnt.cpu().numpy() == 257) and np.all(ev < 131072 // 8)
+    case = gen.make_case("c2", layer=20, hkv=1, hq=4)
+    check_tree(L, oracle, "bf16", case.q, case.K, 64, 4096, 12, 32768)
+
+
 def test_tree_refine_feeds_selection_and_attention(L, oracle):
     """refine -> chunk_topk_select with a budget of k tokens -> attention, read as batch * n_kv_heads
     sequences of one kv head: the attention runs over exactly the k most important tokens."""
