@@ -110,7 +110,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build is a one-GPU path; run it with --gpus 1 "
-              "(sharding by (sequence, kv head) is described in DESIGN.md, not implemented)", file=sys.stderr)
+              "(the path would shard by (sequence, kv head) with no exchange; that is not implemented here)", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch

@@ -57,7 +57,7 @@ struct TreeLds {
     uint32_t wave_tot[kTreeWaves];
     uint32_t prefix[2], rank[2];
     uint32_t ge_weight, below_key, below_any;
-    uint32_t carry, n_split;
+    uint32_t carry;
 };
 
 // exclusive scan of v over the workgroup in lane order; *total = sum
