@@ -245,6 +245,12 @@ __global__ __launch_bounds__(kSelThreads) void select_attention_kernel(
         const int n_tiles = (nb + 15) >> 4, last = n_tiles - 1;
         FusedKvTile cur, nxt;
         fetch(0, cur);
+        if (n_tiles == 1) {
+            // a single tile (small batches spread a (b,h) over many workgroups): nothing to prefetch,
+            // and the pipeline's re-reads of the last tile would triple the load instructions
+            accumulate(logits(cur.k), cur.v, nb);
+            continue;
+        }
         for (int t = 0; t < n_tiles; t += 2) {
             // (no loads under a condition: a tile index past the end re-reads the last tile)
             fetch(min(t + 1, last), nxt);
