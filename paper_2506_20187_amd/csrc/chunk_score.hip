@@ -178,12 +178,21 @@ __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
     const int my_groups = g0 < n_groups ? (n_groups - g0 + stride - 1) / stride : 0;
     const int n_it = 4 * my_groups;
     auto set_of = [&](int it) { return 4 * (g0 + (it >> 2) * stride) + (it & 3); };
-    for (int it = 0; it < n_it; it += 2) {
+    // (n_it is a multiple of four; the last two sets are contracted after the loop, so no set
+    // past the wave's last one is fetched)
+    int it = 0;
+    for (; it + 2 < n_it; it += 2) {
         fetch(set_of(it + 1), nxt);
         __builtin_amdgcn_sched_barrier(0);       // keep the loads ahead of the contraction
         consume(it, set_of(it), cur);
         fetch(set_of(it + 2), cur);
         __builtin_amdgcn_sched_barrier(0);
+        consume(it + 1, set_of(it + 1), nxt);
+    }
+    if (n_it > 0) {
+        fetch(set_of(it + 1), nxt);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(it, set_of(it), cur);
         consume(it + 1, set_of(it + 1), nxt);
     }
     // tail of the row: chunks that do not exist
