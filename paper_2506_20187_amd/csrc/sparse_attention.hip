@@ -307,7 +307,8 @@ struct KvTile {
 };
 
 template <typename T, int G>
-__global__ __launch_bounds__(kAttThreads) void sparse_attention_mfma_kernel(
+__global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(G <= 4 ? 3 : 2)))     // three workgroups per CU
+void sparse_attention_mfma_kernel(
     const char* __restrict__ q, const char* __restrict__ K, const char* __restrict__ V,
     const int32_t* __restrict__ chunk_off, const int32_t* __restrict__ n_chunks, const int32_t* __restrict__ sel_idx,
     const int32_t* __restrict__ sel_count, float scale_log2, float* partial, int n_splits, int c_max,
@@ -495,6 +496,10 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_mfma_kernel(
         const int n_tiles = (nb + 15) >> 4;
         KvTile cur, nxt;
         fetch(0, cur);
+        if (n_tiles == 1) {      // nothing to prefetch: skip the pipeline's re-reads of the last tile
+            consume(cur, nb);
+            continue;
+        }
         for (int t = 0; t < n_tiles; t += 2) {
             // (no loads under a condition: a tile index past the end re-reads the last tile)
             fetch(min(t + 1, n_tiles - 1), nxt);
