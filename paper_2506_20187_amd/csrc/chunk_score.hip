@@ -41,7 +41,9 @@ __device__ __forceinline__ double dpp_ror8_d(double v) {
 }
 
 // kHeadSets = ceil(G / 4); heads beyond G contribute nothing.
-template <typename T, int G, bool kLower>
+// kSingle: a wave takes single row sets instead of groups of four (launches too small to
+// fill the chip: what is waited for then is a wave's own chain of round trips).
+template <typename T, int G, bool kLower, bool kSingle>
 __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
     const char* __restrict__ q, const char* __restrict__ abstract, const int32_t* __restrict__ n_chunks,
     float* __restrict__ score_ub, float* __restrict__ score_lb, int c_max, int n_kv_heads) {
@@ -80,8 +82,8 @@ __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
     // software pipeline: the next row set is in flight while this one is contracted;
     // the first fetch goes out before the queries are converted
     uint4 cur[NLOAD], nxt[NLOAD];
-    const int g0 = blockIdx.x * kScoreWaves + wave;      // this wave's first group of four sets
-    fetch(4 * g0, cur);
+    const int g0 = blockIdx.x * kScoreWaves + wave;      // this wave's first group of four sets (or first set)
+    fetch(kSingle ? g0 : 4 * g0, cur);
 
     // A operands: clamped query values for every step, in double.  They are the same
     // for the four waves and would take 64 registers per lane, so they live in LDS
@@ -157,6 +159,14 @@ __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
             lb = fmin(lb, shfl_xor_d(lb, 32));
         }
         // every lane holds the score of chunk (lane & 7) of this set
+        if constexpr (kSingle) {
+            const int c = set * kChunksPerSet + lane;
+            if (lane < kChunksPerSet && c < C) {
+                score_ub[bh * c_max + c] = (float)ub + 0.0f;
+                if (kLower) score_lb[bh * c_max + c] = (float)lb + 0.0f;
+            }
+            return;
+        }
         const int slot = it & 3;
         if (((lane >> 3) & 3) == slot) {
             pend_ub = (float)ub + 0.0f;
@@ -174,7 +184,13 @@ __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
     // A wave takes groups of four consecutive sets, groups round-robin over the
     // waves of the (b,h).  No loads under a condition inside the loop; sets past
     // the end are computed from clamped rows and store nothing.
-    const int n_groups = (n_sets + 3) >> 2;
+    if constexpr (kSingle) {
+        for (int set = g0; set < n_sets; set += stride) {
+            if (set != g0) fetch(set, cur);          // wave-uniform; normally a wave has one set
+            consume(0, set, cur);
+        }
+    }
+    const int n_groups = kSingle ? 0 : (n_sets + 3) >> 2;
     const int my_groups = g0 < n_groups ? (n_groups - g0 + stride - 1) / stride : 0;
     const int n_it = 4 * my_groups;
     auto set_of = [&](int it) { return 4 * (g0 + (it >> 2) * stride) + (it & 3); };
@@ -211,18 +227,23 @@ static hipError_t launch_score(const leoam_shape* s, const void* q, const void* 
     // that run together then walk the abstract at a power-of-two stride).
     const int sets = (s->c_max + kChunksPerSet - 1) / kChunksPerSet;
     const int units = s->batch * s->n_kv_heads;
-    int gx = (4480 + units - 1) / units;
     const int groups = (sets + 3) / 4;                      // a wave works on groups of four sets
-    const int gx_max = (groups + kScoreWaves - 1) / kScoreWaves;
+    // small launches (groups of four would leave the chip under four waves per SIMD): one set per wave
+    const bool single = (long long)groups * units <= 4096;
+    int gx = (4480 + units - 1) / units;
+    const int gx_max = ((single ? sets : groups) + kScoreWaves - 1) / kScoreWaves;
     if (gx > gx_max) gx = gx_max;
     gx |= 1;
     dim3 grid(gx, s->n_kv_heads, s->batch), block(kScoreWaves * LEOAM_WAVE);
-    if (lb)
-        hipLaunchKernelGGL((chunk_score_kernel<T, G, true>), grid, block, 0, stream, (const char*)q,
-                           (const char*)abstract, n_chunks, ub, lb, s->c_max, s->n_kv_heads);
-    else
-        hipLaunchKernelGGL((chunk_score_kernel<T, G, false>), grid, block, 0, stream, (const char*)q,
-                           (const char*)abstract, n_chunks, ub, lb, s->c_max, s->n_kv_heads);
+#define LEOAM_SCORE(LOWER, SINGLE)                                                                            \
+    hipLaunchKernelGGL((chunk_score_kernel<T, G, LOWER, SINGLE>), grid, block, 0, stream, (const char*)q,      \
+                       (const char*)abstract, n_chunks, ub, lb, s->c_max, s->n_kv_heads)
+    if (lb) {
+        if (single) LEOAM_SCORE(true, true); else LEOAM_SCORE(true, false);
+    } else {
+        if (single) LEOAM_SCORE(false, true); else LEOAM_SCORE(false, false);
+    }
+#undef LEOAM_SCORE
     return hipGetLastError();
 }
 
