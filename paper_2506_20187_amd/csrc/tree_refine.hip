@@ -35,6 +35,7 @@
 namespace leoam {
 
 constexpr int kTreeThreads = 1024;
+constexpr int kTreeCache = 8;          // nodes per thread held in registers through a round
 constexpr int kTreeWaves = kTreeThreads / LEOAM_WAVE;
 constexpr int kTreeMaxG = 8;
 
@@ -221,6 +222,19 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
     int n = m0, evals = m0, status = 0;
     float v = 0.f, mu = 0.f, lambda = 0.f;
     for (int round = 0;; ++round) {
+        // ---- this thread's nodes (tid, tid + 1024, ...) are read once per round; lists longer
+        // than kTreeCache * 1024 nodes re-read the rest from memory in every pass ------------
+        TreeNode cn[kTreeCache];
+#pragma unroll
+        for (int j = 0; j < kTreeCache; ++j) cn[j] = cur[min(tid + j * kTreeThreads, n - 1)];
+        auto for_nodes = [&](auto&& body) {
+#pragma unroll
+            for (int j = 0; j < kTreeCache; ++j) {
+                const int i = tid + j * kTreeThreads;
+                if (i < n) body(i, cn[j]);
+            }
+            for (int i = tid + kTreeCache * kTreeThreads; i < n; i += kTreeThreads) body(i, cur[i]);
+        };
         // ---- v = k-th largest U and lambda = k-th largest L (token-weighted) ---------
         if (tid < 2) {
             S.prefix[tid] = 0;
@@ -231,14 +245,13 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
             for (int i = tid; i < 512; i += kTreeThreads) S.hist[i >> 8][i & 255] = 0;
             __syncthreads();
             const uint32_t pu = S.prefix[0], pl = S.prefix[1];
-            for (int i = tid; i < n; i += kTreeThreads) {
-                const TreeNode nd = cur[i];
+            for_nodes([&](int, const TreeNode& nd) {
                 const uint32_t ku = tree_key(nd.U), kl = tree_key(nd.L);
                 if (pass == 0 || (ku >> (shift + 8)) == (pu >> (shift + 8)))
                     atomicAdd(&S.hist[0][(ku >> shift) & 255], (uint32_t)nd.size);
                 if (pass == 0 || (kl >> (shift + 8)) == (pl >> (shift + 8)))
                     atomicAdd(&S.hist[1][(kl >> shift) & 255], (uint32_t)nd.size);
-            }
+            });
             __syncthreads();
             if (wave < 2) {
                 // lane l owns bins 4l..4l+3; walk from the top bin down
@@ -273,21 +286,34 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
         const uint32_t key_v = S.prefix[0];
         v = tree_unkey(key_v);
         lambda = tree_unkey(S.prefix[1]);
-        // ---- mu = (k+1)-th largest U ---------------------------------------------------
+        // ---- mu = (k+1)-th largest U: each wave folds its lanes, then one atomic per wave -----
         if (tid == 0) {
             S.ge_weight = 0;
             S.below_key = 0;
             S.below_any = 0;
         }
         __syncthreads();
-        for (int i = tid; i < n; i += kTreeThreads) {
-            const TreeNode nd = cur[i];
-            const uint32_t ku = tree_key(nd.U);
-            if (ku >= key_v) {
-                atomicAdd(&S.ge_weight, (uint32_t)nd.size);
-            } else {
-                atomicMax(&S.below_key, ku);
-                S.below_any = 1;
+        {
+            uint32_t ge = 0, below = 0, any = 0;
+            for_nodes([&](int, const TreeNode& nd) {
+                const uint32_t ku = tree_key(nd.U);
+                if (ku >= key_v) {
+                    ge += (uint32_t)nd.size;
+                } else {
+                    below = max(below, ku);
+                    any = 1;
+                }
+            });
+            const uint32_t ge_w =
+                (uint32_t)__builtin_amdgcn_readlane((int)wave_incl_scan_u32(ge), LEOAM_WAVE - 1);
+            const uint32_t below_w = wave_max_u32(below);
+            const bool any_w = __ballot(any != 0) != 0;
+            if (lane == 0) {
+                if (ge_w) atomicAdd(&S.ge_weight, ge_w);
+                if (any_w) {
+                    atomicMax(&S.below_key, below_w);
+                    S.below_any = 1;
+                }
             }
         }
         __syncthreads();
@@ -297,13 +323,9 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
         // ---- which nodes are split, and where everything goes --------------------------
         if (tid == 0) S.carry = 0;
         __syncthreads();
-        for (int base = 0; base < n; base += kTreeThreads) {
-            const int i = base + tid;
-            uint32_t width = 0;
-            if (i < n) {
-                const TreeNode nd = cur[i];
-                width = (nd.U >= v && !(nd.L > mu) && nd.size > 1) ? 2u : 1u;
-            }
+        auto is_split = [&](const TreeNode& nd) { return nd.U >= v && !(nd.L > mu) && nd.size > 1; };
+        auto scan_tile = [&](int i, const TreeNode& nd) {
+            const uint32_t width = i < n ? (is_split(nd) ? 2u : 1u) : 0u;
             uint32_t total;
             const uint32_t before = tree_block_scan(width, S.wave_tot, &total);
             const uint32_t carry = S.carry;
@@ -311,7 +333,12 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
             __syncthreads();
             if (tid == 0) S.carry = carry + total;
             __syncthreads();
-        }
+        };
+#pragma unroll
+        for (int j = 0; j < kTreeCache; ++j)
+            if (j * kTreeThreads < n) scan_tile(tid + j * kTreeThreads, cn[j]);
+        for (int base = kTreeCache * kTreeThreads; base < n; base += kTreeThreads)
+            scan_tile(base + tid, cur[min(base + tid, n - 1)]);
         const int n_new = (int)S.carry, n_split = n_new - n;
         if (n_split == 0) break;
         if (n_new > node_cap) {
@@ -320,12 +347,11 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
         }
         // ---- unsplit nodes move to their new place; split nodes are listed -----------------
         // (pos[i] - i = number of splits before node i = its slot in the list)
-        for (int i = tid; i < n; i += kTreeThreads) {
-            const TreeNode nd = cur[i];
+        for_nodes([&](int i, const TreeNode& nd) {
             const int p = pos[i];
-            if (nd.U >= v && !(nd.L > mu) && nd.size > 1) task[p - i] = i;
+            if (is_split(nd)) task[p - i] = i;
             else nxt[p] = nd;
-        }
+        });
         __syncthreads();
         // ---- a lane group takes one half of a listed node and evaluates it from its keys -----
         for (int t = gid; t < 2 * n_split; t += kGroups) {
