@@ -15,18 +15,24 @@
 //   mu     = (k+1)-th largest U  (-inf when k == n_ctx)
 //   lambda = k-th largest L
 //   confirmed: L > mu;  unimportant: U < lambda;  split: U >= v, not confirmed, size > 1.
-// They are found without sorting: a radix descent (four 8-bit passes over the
-// order-preserving integer image of the floats, token-weighted histograms in
-// LDS) for v and lambda together; mu is v if the chunks with U >= v hold more
-// than k tokens, else the largest U below v.
+// They are found without sorting: a radix descent over the order-preserving
+// integer image of the floats (8-bit digits, token-weighted histogram in LDS;
+// the bits every key shares are skipped, which also spreads the first digit
+// over the bins).  v is needed in every round, lambda only for the final
+// merge; mu is v if the chunks with U >= v hold more than k tokens, else the
+// largest U below v.
 //
 // One 1024-lane workgroup per (sequence, kv head) runs every round; the node
 // list (start, size, U, L) lives in the workspace, double-buffered, in position
-// order (a split node is replaced by its two halves at scanned positions).  A
-// lane group as wide as a key row evaluates a node - element-wise max / min over
-// its key rows (the two abstract rows for an initial chunk), then the bounds in
+// order (a split node is replaced by its two halves at scanned positions); a
+// thread keeps its 8 consecutive nodes in registers through a round.  A lane
+// group as wide as a key row evaluates a node - element-wise max / min over its
+// key rows (the two abstract rows for an initial chunk), then the bounds in
 // double, rounded once to float - so a wave has 4 (fp32: 2) nodes in flight.
-// Latency-bound, exact integer bookkeeping.
+// For four query heads the lanes of a quad trade partial sums so that the
+// cross-lane reduction handles the eight sums of a node together.  The
+// evaluation phase dominates: its first rounds are bound by what one compute
+// unit can fetch, the later ones by the double-precision arithmetic.
 #include <cfloat>
 #include <type_traits>
 
@@ -36,10 +42,11 @@ namespace leoam {
 
 constexpr int kTreeThreads = 1024;
 constexpr int kTreeCache = 8;          // nodes per thread held in registers through a round
+constexpr int kTreeTile = kTreeCache * kTreeThreads;
 constexpr int kTreeWaves = kTreeThreads / LEOAM_WAVE;
 constexpr int kTreeMaxG = 8;
 
-struct TreeNode {
+struct alignas(16) TreeNode {
     int32_t start, size;
     float U, L;
 };
@@ -53,12 +60,17 @@ __device__ __forceinline__ float tree_unkey(uint32_t k) {
 }
 
 struct TreeLds {
-    double qpos[kTreeMaxG][LEOAM_D], qneg[kTreeMaxG][LEOAM_D];      // max(q, 0) and min(q, 0)
-    uint32_t hist[2][256];
+    alignas(16) double qpos[kTreeMaxG][LEOAM_D], qneg[kTreeMaxG][LEOAM_D];      // max(q, 0), min(q, 0); order: q_slot()
+    uint32_t hist[256];
     uint32_t wave_tot[kTreeWaves];
-    uint32_t prefix[2], rank[2];
+    uint32_t key_lo, key_hi, digit, rank;
     uint32_t ge_weight, below_key, below_any;
     uint32_t carry;
+};
+
+// A task of the evaluation phase: a node that is split, and where its halves go.
+struct alignas(16) TreeTask {
+    int32_t start, size, pos, pad;
 };
 
 // exclusive scan of v over the workgroup in lane order; *total = sum
@@ -76,21 +88,32 @@ __device__ __forceinline__ uint32_t tree_block_scan(uint32_t v, uint32_t* wave_t
     return upto - own + incl - v;
 }
 
+// a double from another lane of the 16-lane row (every lane of a row is a valid source here)
+template <int kCtrl> __device__ __forceinline__ double dpp_d(double v) {
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)u, kCtrl, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)(u >> 32), kCtrl, 0xf, 0xf, true);
+    return __builtin_bit_cast(double, ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+template <int kCtrl> __device__ __forceinline__ float tree_dpp_f(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kCtrl, 0xf, 0xf, true));
+}
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppRor4 = 0x124, kDppRor8 = 0x128;
+
 // sum of a double over the lanes of a group of kLanes (16 or 32) lanes; every lane gets it
 template <int kLanes> __device__ __forceinline__ double group_sum_d(double v) {
-    auto step = [&](auto ctrl) {
-        constexpr int kCtrl = decltype(ctrl)::value;
-        const uint64_t u = __builtin_bit_cast(uint64_t, v);
-        const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)u, kCtrl, 0xf, 0xf, false);
-        const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)(u >> 32), kCtrl, 0xf, 0xf, false);
-        v += __builtin_bit_cast(double, ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
-    };
-    step(std::integral_constant<int, 0xB1>{});       // xor 1
-    step(std::integral_constant<int, 0x4E>{});       // xor 2
-    step(std::integral_constant<int, 0x141>{});      // mirror inside 8 lanes
-    step(std::integral_constant<int, 0x140>{});      // mirror inside 16 lanes
+    v += dpp_d<kDppXor1>(v);
+    v += dpp_d<kDppXor2>(v);
+    v += dpp_d<kDppRor4>(v);
+    v += dpp_d<kDppRor8>(v);
     if (kLanes == 32) v += shfl_xor_d(v, 16);
     return v;
+}
+
+// Where channel e of a lane sits in TreeLds::qpos / qneg: a lane reads its channels two at a
+// time (16 bytes) and the lanes of a row then read consecutive 16-byte pieces.
+template <typename T> __device__ __forceinline__ int q_slot(int lane_in_row, int e) {
+    return (e / 2) * (Row<T>::kLanesPerRow * 2) + lane_in_row * 2 + (e % 2);
 }
 
 // A lane group (the lanes that cover one key row: 16 for 16-bit keys, 32 for fp32)
@@ -110,22 +133,10 @@ __device__ __forceinline__ void tree_eval(const char* rows, int n_rows, const do
         mx[e] = -INFINITY;
         mn[e] = INFINITY;
     }
-    // eight rows in flight; a row index past the end re-reads the last row (harmless for max / min,
+    // kBatch rows in flight; a row index past the end re-reads the last row (harmless for max / min,
     // and the loads stay unconditional)
-    constexpr int kBatch = 8;
-    if (n_rows <= 2) {          // an initial chunk: its kmax row and its kmin row
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            float x[EPL];
-            unpack<T>(load16(rows, (size_t)min(j, n_rows - 1) * ROWB + (size_t)col * T::kBytes), x);
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-                mx[e] = fmaxf(mx[e], x[e]);
-                mn[e] = fminf(mn[e], x[e]);
-            }
-        }
-    } else
-    for (int r0 = 0; r0 < n_rows; r0 += kBatch) {
+    auto rows_from = [&](int r0, auto batch) {
+        constexpr int kBatch = decltype(batch)::value;
         uint4 v[kBatch];
 #pragma unroll
         for (int j = 0; j < kBatch; ++j)
@@ -140,26 +151,87 @@ __device__ __forceinline__ void tree_eval(const char* rows, int n_rows, const do
                 mn[e] = fminf(mn[e], x[e]);
             }
         }
+    };
+    // the batch size follows the largest node of the wave, so the lane groups never take
+    // different paths (a group with fewer rows re-reads its last row)
+    int w_rows = n_rows;
+#pragma unroll
+    for (int g = 0; g < LEOAM_WAVE; g += LPR) w_rows = max(w_rows, __builtin_amdgcn_readlane(n_rows, g));
+    if (w_rows <= 2) {          // also an initial chunk: its kmax row and its kmin row
+        rows_from(0, std::integral_constant<int, 2>{});
+    } else if (w_rows <= 4) {
+        rows_from(0, std::integral_constant<int, 4>{});
+    } else {
+        for (int r0 = 0; r0 < w_rows; r0 += 8) rows_from(r0, std::integral_constant<int, 8>{});
     }
-    float ub = -INFINITY, lb = -INFINITY;
-    for (int j = 0; j < G; ++j) {
-        // max(q k_max, q k_min) = max(q,0) k_max + min(q,0) k_min (k_max >= k_min): one of the two
-        // products is zero and every product is exact in double.  Four independent chains.
+    double hi[EPL], lo[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        hi[e] = (double)mx[e];
+        lo[e] = (double)mn[e];
+    }
+    // max(q k_max, q k_min) = max(q,0) k_max + min(q,0) k_min (k_max >= k_min): one of the two
+    // products is zero and every product is exact in double.  Two independent chains per bound.
+    auto head_sums = [&](int j, double* u, double* l) {
         double u0 = 0.0, u1 = 0.0, l0 = 0.0, l1 = 0.0;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-            const double qp = qpos[j][e * LPR + lane_in_row], qn = qneg[j][e * LPR + lane_in_row];
-            const double hi = (double)mx[e], lo = (double)mn[e];
-            u0 = fma(qp, hi, u0);
-            u1 = fma(qn, lo, u1);
-            l0 = fma(qp, lo, l0);
-            l1 = fma(qn, hi, l1);
+        for (int e = 0; e < EPL; e += 2) {
+            const double2 qp = *reinterpret_cast<const double2*>(&qpos[j][q_slot<T>(lane_in_row, e)]);
+            const double2 qn = *reinterpret_cast<const double2*>(&qneg[j][q_slot<T>(lane_in_row, e)]);
+            u0 = fma(qp.x, hi[e], u0);
+            u0 = fma(qn.x, lo[e], u0);
+            l0 = fma(qp.x, lo[e], l0);
+            l0 = fma(qn.x, hi[e], l0);
+            u1 = fma(qp.y, hi[e + 1], u1);
+            u1 = fma(qn.y, lo[e + 1], u1);
+            l1 = fma(qp.y, lo[e + 1], l1);
+            l1 = fma(qn.y, hi[e + 1], l1);
         }
-        double u = u0 + u1, l = l0 + l1;
-        u = group_sum_d<LPR>(u);
-        l = group_sum_d<LPR>(l);
-        ub = fmaxf(ub, (float)u + 0.0f);
-        lb = fmaxf(lb, (float)l + 0.0f);
+        *u = u0 + u1;
+        *l = l0 + l1;
+    };
+    float ub = -INFINITY, lb = -INFINITY;
+    if (G == 4) {
+        // Four heads at once: the lanes of a quad first trade partial sums so that each ends up
+        // with one head's pair (8 -> 4 -> 2 values per lane), the quads of the row are then added.
+        double x[8];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) head_sums(j, &x[2 * j], &x[2 * j + 1]);
+        const bool b0 = lane_in_row & 1, b1 = lane_in_row & 2;
+        double y[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const double keep = b0 ? x[4 + i] : x[i], send = b0 ? x[i] : x[4 + i];
+            y[i] = keep + dpp_d<kDppXor1>(send);
+        }
+        double z[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const double keep = b1 ? y[2 + i] : y[i], send = b1 ? y[i] : y[2 + i];
+            z[i] = keep + dpp_d<kDppXor2>(send);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            z[i] += dpp_d<kDppRor4>(z[i]);
+            z[i] += dpp_d<kDppRor8>(z[i]);
+            if (LPR == 32) z[i] += shfl_xor_d(z[i], 16);
+        }
+        // this lane: head 2 * b0 + b1; the maximum over the quad is the maximum over the heads
+        ub = (float)z[0] + 0.0f;
+        lb = (float)z[1] + 0.0f;
+        ub = fmaxf(ub, tree_dpp_f<kDppXor1>(ub));
+        lb = fmaxf(lb, tree_dpp_f<kDppXor1>(lb));
+        ub = fmaxf(ub, tree_dpp_f<kDppXor2>(ub));
+        lb = fmaxf(lb, tree_dpp_f<kDppXor2>(lb));
+    } else {
+        for (int j = 0; j < G; ++j) {
+            double u, l;
+            head_sums(j, &u, &l);
+            u = group_sum_d<LPR>(u);
+            l = group_sum_d<LPR>(l);
+            ub = fmaxf(ub, (float)u + 0.0f);
+            lb = fmaxf(lb, (float)l + 0.0f);
+        }
     }
     *U = ub;
     *L = lb;
@@ -170,7 +242,7 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
     const char* __restrict__ q, const char* __restrict__ K, const char* __restrict__ abstract, int chunk_size,
     int k_tokens, int max_rounds, int node_cap, int32_t* __restrict__ ref_off, float* __restrict__ ref_score,
     int32_t* __restrict__ ref_count, int32_t* __restrict__ ref_evals, int32_t* __restrict__ ref_status,
-    TreeNode* nodes_a, TreeNode* nodes_b, int32_t* pos_buf, int32_t* task_buf, int n_ctx, int c_max, int n_kv_heads, int G) {
+    TreeNode* nodes_a, TreeNode* nodes_b, int32_t* pos_buf, TreeTask* task_buf, int n_ctx, int c_max, int n_kv_heads, int G) {
     constexpr int ROWB = Row<T>::kRowBytes;
     constexpr int EPL = T::kEpl;
     __shared__ TreeLds S;
@@ -182,7 +254,7 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
     TreeNode* cur = nodes_a + bh * (size_t)node_cap;
     TreeNode* nxt = nodes_b + bh * (size_t)node_cap;
     int32_t* pos = pos_buf + bh * (size_t)node_cap;
-    int32_t* task = task_buf + bh * (size_t)node_cap;
+    TreeTask* task = task_buf + bh * (size_t)((node_cap + 1) / 2);
     constexpr int LPR = Row<T>::kLanesPerRow;
     constexpr int kGroups = kTreeThreads / LPR;              // node evaluations in flight per workgroup
     const int gid = tid / LPR;
@@ -190,25 +262,26 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
     const char* Kbh = K + bh * (size_t)n_ctx * ROWB;
     const char* Abh = abstract + bh * (size_t)c_max * 2 * ROWB;
 
-    // ---- queries of the group in double ------------------------------------------
-    for (int i = tid; i < G * (LEOAM_D / EPL); i += kTreeThreads) {
-        const int j = i / (LEOAM_D / EPL), c = (i % (LEOAM_D / EPL)) * EPL;
+    // ---- queries of the group ------------------------------------------------------
+    for (int i = tid; i < G * LPR; i += kTreeThreads) {
+        const int j = i / LPR, lr = i % LPR;
         float x[EPL];
-        unpack<T>(load16(q, ((size_t)b * n_kv_heads * G + (size_t)h * G + j) * ROWB + (size_t)c * T::kBytes), x);
+        unpack<T>(load16(q, ((size_t)b * n_kv_heads * G + (size_t)h * G + j) * ROWB + (size_t)lr * EPL * T::kBytes), x);
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
-            // channel c + e sits at [e][c / EPL]: the lanes of a row then read consecutive doubles
-            S.qpos[j][e * (LEOAM_D / EPL) + c / EPL] = (double)fmaxf(x[e], 0.f);
-            S.qneg[j][e * (LEOAM_D / EPL) + c / EPL] = (double)fminf(x[e], 0.f);
+            S.qpos[j][q_slot<T>(lr, e)] = (double)fmaxf(x[e], 0.f);
+            S.qneg[j][q_slot<T>(lr, e)] = (double)fminf(x[e], 0.f);
         }
     }
+    for (int i = tid; i < 256; i += kTreeThreads) S.hist[i] = 0;
     __syncthreads();
 
     // ---- initial chunks: bounds from the abstract rows (kmax row, kmin row) ----------
-    for (int c = gid; c < m0; c += kGroups) {
+    for (int c0 = wave * (LEOAM_WAVE / LPR); c0 < m0; c0 += kGroups) {      // uniform over the wave
+        const int c = min(c0 + gid % (LEOAM_WAVE / LPR), m0 - 1);
         float U, L;
         tree_eval<T>(Abh + (size_t)c * 2 * ROWB, 2, S.qpos, S.qneg, G, &U, &L);
-        if (g_lead) {
+        if (g_lead) {        // (a clamped group repeats the last chunk's store)
             TreeNode nd;
             nd.start = c * chunk_size;
             nd.size = min(chunk_size, n_ctx - c * chunk_size);
@@ -220,52 +293,71 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
     __syncthreads();
 
     int n = m0, evals = m0, status = 0;
-    float v = 0.f, mu = 0.f, lambda = 0.f;
-    for (int round = 0;; ++round) {
-        // ---- this thread's nodes (tid, tid + 1024, ...) are read once per round; lists longer
-        // than kTreeCache * 1024 nodes re-read the rest from memory in every pass ------------
-        TreeNode cn[kTreeCache];
+    float v = 0.f, mu = 0.f;
+    // The list is walked in tiles of kTreeTile nodes, kTreeCache consecutive nodes per thread.
+    // The first tile's nodes are read once per round and kept in registers; a longer list
+    // re-reads the other tiles from memory in every pass.
+    TreeNode cn[kTreeCache];
+    auto for_nodes = [&](auto&& body) {
 #pragma unroll
-        for (int j = 0; j < kTreeCache; ++j) cn[j] = cur[min(tid + j * kTreeThreads, n - 1)];
-        auto for_nodes = [&](auto&& body) {
+        for (int j = 0; j < kTreeCache; ++j) {
+            const int i = tid * kTreeCache + j;
+            if (i < n) body(i, cn[j]);
+        }
+        for (int base = kTreeTile; base < n; base += kTreeTile)
 #pragma unroll
             for (int j = 0; j < kTreeCache; ++j) {
-                const int i = tid + j * kTreeThreads;
-                if (i < n) body(i, cn[j]);
+                const int i = base + tid * kTreeCache + j;
+                if (i < n) body(i, cur[i]);
             }
-            for (int i = tid + kTreeCache * kTreeThreads; i < n; i += kTreeThreads) body(i, cur[i]);
-        };
-        // ---- v = k-th largest U and lambda = k-th largest L (token-weighted) ---------
-        if (tid < 2) {
-            S.prefix[tid] = 0;
-            S.rank[tid] = (uint32_t)k_tokens;
+    };
+    // Token-weighted k-th largest key of the list (every thread gets it).  The histogram is
+    // all zero on entry and on return.
+    auto kth_largest = [&](auto&& key_of) -> uint32_t {
+        uint32_t lo = 0xffffffffu, hi = 0;
+        for_nodes([&](int, const TreeNode& nd) {
+            const uint32_t k = key_of(nd);
+            lo = min(lo, k);
+            hi = max(hi, k);
+        });
+        lo = wave_min_u32(lo);
+        hi = wave_max_u32(hi);
+        if (tid == 0) {
+            S.key_lo = 0xffffffffu;
+            S.key_hi = 0;
+            S.rank = (uint32_t)k_tokens;
         }
-        for (int pass = 0; pass < 4; ++pass) {
-            const int shift = 24 - 8 * pass;
-            for (int i = tid; i < 512; i += kTreeThreads) S.hist[i >> 8][i & 255] = 0;
-            __syncthreads();
-            const uint32_t pu = S.prefix[0], pl = S.prefix[1];
+        __syncthreads();
+        if (lane == 0) {
+            atomicMin(&S.key_lo, lo);
+            atomicMax(&S.key_hi, hi);
+        }
+        __syncthreads();
+        lo = S.key_lo;
+        hi = S.key_hi;
+        int bits = (lo ^ hi) ? 32 - __clz((int)(lo ^ hi)) : 0;      // bits below the prefix all keys share
+        uint32_t prefix = (uint32_t)(((uint64_t)hi >> bits) << bits);
+        while (bits > 0) {
+            const int w = min(bits, 8), shift = bits - w;
             for_nodes([&](int, const TreeNode& nd) {
-                const uint32_t ku = tree_key(nd.U), kl = tree_key(nd.L);
-                if (pass == 0 || (ku >> (shift + 8)) == (pu >> (shift + 8)))
-                    atomicAdd(&S.hist[0][(ku >> shift) & 255], (uint32_t)nd.size);
-                if (pass == 0 || (kl >> (shift + 8)) == (pl >> (shift + 8)))
-                    atomicAdd(&S.hist[1][(kl >> shift) & 255], (uint32_t)nd.size);
+                const uint32_t k = key_of(nd);
+                if ((uint32_t)((uint64_t)(k ^ prefix) >> bits) == 0)
+                    atomicAdd(&S.hist[(k >> shift) & ((1u << w) - 1u)], (uint32_t)nd.size);
             });
             __syncthreads();
-            if (wave < 2) {
-                // lane l owns bins 4l..4l+3; walk from the top bin down
-                const uint32_t* hs = S.hist[wave];
+            if (wave == 0) {
+                // lane l owns bins 4l..4l+3 (and clears them); walk from the top bin down
                 uint32_t hb[4], lane_sum = 0;
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    hb[t] = hs[4 * lane + t];
+                    hb[t] = S.hist[4 * lane + t];
+                    S.hist[4 * lane + t] = 0;
                     lane_sum += hb[t];
                 }
                 const uint32_t incl = wave_incl_scan_u32(lane_sum);
                 const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, LEOAM_WAVE - 1);
                 uint32_t above = total - incl;                // weight of the bins above this lane's bins
-                const uint32_t rank = S.rank[wave];
+                const uint32_t rank = S.rank;
                 int found = -1;
                 uint32_t above_found = 0;
 #pragma unroll
@@ -277,15 +369,23 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
                     above += hb[t];
                 }
                 if (found >= 0) {       // exactly one lane: the totals reach the rank
-                    S.prefix[wave] |= (uint32_t)found << shift;
-                    S.rank[wave] = rank - above_found;
+                    S.digit = (uint32_t)found;
+                    S.rank = rank - above_found;
                 }
             }
             __syncthreads();
+            prefix |= S.digit << shift;
+            bits = shift;
         }
-        const uint32_t key_v = S.prefix[0];
+        return prefix;
+    };
+
+    for (int round = 0;; ++round) {
+#pragma unroll
+        for (int j = 0; j < kTreeCache; ++j) cn[j] = cur[min(tid * kTreeCache + j, n - 1)];
+        // ---- v = k-th largest U (token-weighted) -----------------------------------------
+        const uint32_t key_v = kth_largest([](const TreeNode& nd) { return tree_key(nd.U); });
         v = tree_unkey(key_v);
-        lambda = tree_unkey(S.prefix[1]);
         // ---- mu = (k+1)-th largest U: each wave folds its lanes, then one atomic per wave -----
         if (tid == 0) {
             S.ge_weight = 0;
@@ -321,48 +421,79 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
         if (round >= max_rounds) break;
 
         // ---- which nodes are split, and where everything goes --------------------------
-        if (tid == 0) S.carry = 0;
-        __syncthreads();
         auto is_split = [&](const TreeNode& nd) { return nd.U >= v && !(nd.L > mu) && nd.size > 1; };
-        auto scan_tile = [&](int i, const TreeNode& nd) {
-            const uint32_t width = i < n ? (is_split(nd) ? 2u : 1u) : 0u;
-            uint32_t total;
-            const uint32_t before = tree_block_scan(width, S.wave_tot, &total);
-            const uint32_t carry = S.carry;
-            if (i < n) pos[i] = (int32_t)(carry + before);
-            __syncthreads();
-            if (tid == 0) S.carry = carry + total;
-            __syncthreads();
-        };
+        // (a thread's nodes are consecutive: positions = scan of the threads' widths + a running sum)
+        int my_pos[kTreeCache];
+        uint32_t carry = 0;
+        auto scan_tile = [&](int base, auto&& node_of, auto&& put) {
+            uint32_t local[kTreeCache], width = 0;
 #pragma unroll
-        for (int j = 0; j < kTreeCache; ++j)
-            if (j * kTreeThreads < n) scan_tile(tid + j * kTreeThreads, cn[j]);
-        for (int base = kTreeCache * kTreeThreads; base < n; base += kTreeThreads)
-            scan_tile(base + tid, cur[min(base + tid, n - 1)]);
-        const int n_new = (int)S.carry, n_split = n_new - n;
+            for (int j = 0; j < kTreeCache; ++j) {
+                const int i = base + tid * kTreeCache + j;
+                local[j] = width;
+                if (i < n) width += is_split(node_of(i, j)) ? 2u : 1u;
+            }
+            uint32_t total;
+            const uint32_t before = carry + tree_block_scan(width, S.wave_tot, &total);
+#pragma unroll
+            for (int j = 0; j < kTreeCache; ++j) put(base + tid * kTreeCache + j, j, (int)(before + local[j]));
+            carry += total;
+        };
+        scan_tile(0, [&](int, int j) -> const TreeNode& { return cn[j]; }, [&](int, int j, int p) { my_pos[j] = p; });
+        for (int base = kTreeTile; base < n; base += kTreeTile)
+            scan_tile(base, [&](int i, int) { return cur[i]; }, [&](int i, int, int p) {
+                if (i < n) pos[i] = p;
+            });
+        const int n_new = (int)carry, n_split = n_new - n;
         if (n_split == 0) break;
         if (n_new > node_cap) {
             status = 1;
             break;
         }
         // ---- unsplit nodes move to their new place; split nodes are listed -----------------
-        // (pos[i] - i = number of splits before node i = its slot in the list)
-        for_nodes([&](int i, const TreeNode& nd) {
-            const int p = pos[i];
-            if (is_split(nd)) task[p - i] = i;
-            else nxt[p] = nd;
-        });
+        // (position - index = number of splits before the node = its slot in the list)
+        auto place = [&](int i, int p, const TreeNode& nd) {
+            if (is_split(nd)) {
+                TreeTask tk;
+                tk.start = nd.start;
+                tk.size = nd.size;
+                tk.pos = p;
+                tk.pad = 0;
+                task[p - i] = tk;
+            } else {
+                nxt[p] = nd;
+            }
+        };
+#pragma unroll
+        for (int j = 0; j < kTreeCache; ++j) {
+            const int i = tid * kTreeCache + j;
+            if (i < n) place(i, my_pos[j], cn[j]);
+        }
+        for (int base = kTreeTile; base < n; base += kTreeTile)
+#pragma unroll
+            for (int j = 0; j < kTreeCache; ++j) {
+                const int i = base + tid * kTreeCache + j;
+                if (i < n) place(i, pos[i], cur[i]);      // pos[i]: this thread's own store
+            }
         __syncthreads();
-        // ---- a lane group takes one half of a listed node and evaluates it from its keys -----
-        for (int t = gid; t < 2 * n_split; t += kGroups) {
-            const int parent = task[t >> 1], second = t & 1;
-            const TreeNode nd = cur[parent];
-            const int left = (nd.size + 1) / 2;
-            TreeNode c;
-            c.start = second ? nd.start + left : nd.start;
-            c.size = second ? nd.size - left : left;
-            tree_eval<T>(Kbh + (size_t)c.start * ROWB, c.size, S.qpos, S.qneg, G, &c.U, &c.L);
-            if (g_lead) nxt[pos[parent] + second] = c;
+        // ---- a lane group takes one half of a listed node and evaluates it from its keys; the
+        // next task's entry is fetched before the evaluation ----------------------------------
+        // (the loop is uniform over the wave: a lane group past the end evaluates row 0 and stores nothing)
+        {
+            constexpr int kGroupsPerWave = LEOAM_WAVE / LPR;
+            TreeTask tk = task[min(gid >> 1, n_split - 1)];
+            for (int t0 = wave * kGroupsPerWave; t0 < 2 * n_split; t0 += kGroups) {
+                const int t = t0 + gid % kGroupsPerWave;
+                const bool live = t < 2 * n_split;
+                const TreeTask nx = task[min((t + kGroups) >> 1, n_split - 1)];
+                const int second = t & 1, left = (tk.size + 1) / 2;
+                TreeNode c;
+                c.start = live ? (second ? tk.start + left : tk.start) : 0;
+                c.size = live ? (second ? tk.size - left : left) : 1;
+                tree_eval<T>(Kbh + (size_t)c.start * ROWB, c.size, S.qpos, S.qneg, G, &c.U, &c.L);
+                if (g_lead && live) nxt[tk.pos + second] = c;
+                tk = nx;
+            }
         }
         __syncthreads();
         TreeNode* tmp = cur;
@@ -371,6 +502,8 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
         n = n_new;
         evals += 2 * n_split;
     }
+    // lambda = k-th largest L of the final list (cn still holds this thread's nodes of it)
+    const float lambda = tree_unkey(kth_largest([](const TreeNode& nd) { return tree_key(nd.L); }));
 
     // ---- final partition: runs of confirmed chunks and runs of unimportant chunks merge ---
     int32_t* off = ref_off + bh * (size_t)(node_cap + 1);
@@ -425,7 +558,9 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
 }
 
 size_t tree_workspace_bytes(const leoam_shape* s, int node_cap) {
-    return (size_t)s->batch * s->n_kv_heads * (size_t)node_cap * (2 * sizeof(TreeNode) + 2 * sizeof(int32_t));
+    // two node lists, the task list (a split adds a node, so at most node_cap / 2 per round), positions
+    return (size_t)s->batch * s->n_kv_heads *
+           ((size_t)node_cap * (2 * sizeof(TreeNode) + sizeof(int32_t)) + (size_t)((node_cap + 1) / 2) * sizeof(TreeTask));
 }
 
 hipError_t tree_refine_dispatch(const leoam_shape* s, const void* q, const void* K, const void* abstract,
@@ -435,8 +570,8 @@ hipError_t tree_refine_dispatch(const leoam_shape* s, const void* q, const void*
     const size_t units = (size_t)s->batch * s->n_kv_heads;
     TreeNode* a = (TreeNode*)workspace;
     TreeNode* b = a + units * (size_t)node_cap;
-    int32_t* pos = (int32_t*)(b + units * (size_t)node_cap);
-    int32_t* task = pos + units * (size_t)node_cap;
+    TreeTask* task = (TreeTask*)(b + units * (size_t)node_cap);
+    int32_t* pos = (int32_t*)(task + units * (size_t)((node_cap + 1) / 2));
     dim3 grid(s->n_kv_heads, s->batch), block(kTreeThreads);
     const int G = s->n_q_heads / s->n_kv_heads;
 #define LEOAM_TREE(TT)                                                                                           \
