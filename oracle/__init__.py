@@ -333,3 +333,35 @@ def tree_refine(q, K, chunk_size: int, k_tokens: int, max_rounds: int, node_cap:
     if rc != 0:
         raise ValueError("tree_refine: node_cap below the initial chunk count, or k_tokens outside [1, N]")
     return off, score, cnt, evals, status
+
+
+def chunk_compress(K, V, chunk_off, n_chunks, four_bit):
+    """Sec. 4.4 / 6.1 compressed store of K, V [B,Hkv,N,D] (see leoam_oracle.c).  `four_bit` [B,c_max]
+    tags the 4-bit chunks.  Returns (kblob uint8, vblob uint8, qmeta records [B,Hkv,c_max])."""
+    ka, tag = _as_numpy(K)
+    va, tag_v = _as_numpy(V)
+    assert tag == tag_v and ka.shape == va.shape
+    B, Hkv, N, D = ka.shape
+    off, nc = _i32(chunk_off), _i32(n_chunks)
+    c_max = off.shape[1] - 1
+    _check_boundaries(off, nc, N)
+    fb = np.ascontiguousarray(np.asarray(four_bit).astype(np.uint8))
+    assert fb.shape == (B, c_max)
+    cap = B * Hkv * (N * D + 16 * c_max)
+    kblob = np.zeros(cap, dtype=np.uint8)
+    vblob = np.zeros(cap, dtype=np.uint8)
+    qm = np.zeros((B, Hkv, c_max), dtype=QCHUNK_DTYPE)
+    total = np.zeros(1, dtype=np.int64)
+    rc = _load().orc_chunk_compress(tag, B, Hkv, N, D, _ptr(ka), _ptr(va), _ptr(off), _ptr(nc), c_max, _ptr(fb),
+                                    _ptr(kblob), _ptr(vblob), ctypes.c_int64(cap), _ptr(qm), _ptr(total))
+    assert rc == 0
+    n = int(total[0])
+    return kblob[:max(n, 16)].copy(), vblob[:max(n, 16)].copy(), qm
+
+
+def compression_share(n_bytes: float, ratio: float, bandwidth: float, t_other: float, t_compute: float,
+                      decompress_rate: float) -> float:
+    """Sec. 4.4: the share theta of the transmitted bytes that is sent compressed (see leoam_oracle.c)."""
+    fn = _load().orc_compression_share
+    fn.restype = ctypes.c_double
+    return float(fn(*(ctypes.c_double(float(x)) for x in (n_bytes, ratio, bandwidth, t_other, t_compute, decompress_rate))))

@@ -17,6 +17,8 @@
  *                        read from the front) and Sec. 6.1 (load only the
  *                        most important share of the cache).
  *   orc_sparse_attention Sec. 2.1 Eq. (1), restricted to the selected tokens.
+ *   orc_chunk_compress   Sec. 4.4 / 6.1: the compressed (8-bit / 4-bit) store.
+ *   orc_compression_share Sec. 4.4: the share of the data that is sent compressed.
  *
  * All floating-point work is done in double.  Stored fp32/fp16/bf16 inputs
  * are widened exactly.  Pinned by tests/test_oracle_*.py; no function here is
@@ -418,6 +420,102 @@ int orc_dequant(int B, int Hkv, int N, int D, const uint8_t *blob, const orc_qch
         }
     }
     return 0;
+}
+
+/* Sec. 4.4 "Dynamic KV compression" / Sec. 6.1 (KV compressed to INT4): builds the
+ * compressed store from the 16-bit (or fp32) cache.  Per (b, h, chunk, tensor):
+ *     zero  = min over the chunk's elements,  scale = (max - min) / levels,
+ *     code  = round-half-even((x - zero) / scale), kept inside 0..levels,
+ * levels = 255 (8-bit chunk) or 15 (4-bit chunk; two codes per byte, even channel
+ * in the low nibble); scale == 0 (all elements equal) gives code 0 everywhere.
+ * The decision that yields an integer is taken in float (binary32): max - min,
+ * the division by levels, x - zero and the division by scale are single float
+ * operations, each correctly rounded - the precision of the stored scale and zero.
+ * Layout: the chunks of a (b,h) follow each other, each padded to a multiple of
+ * 16 bytes; the (b,h) pairs follow each other; K and V blobs use the same
+ * offsets.  Records of chunks >= n_chunks[b] are zero.  Returns 1 if the blobs
+ * are too small (nothing is written then).  *total_bytes = bytes of one blob. */
+int orc_chunk_compress(int dtype, int B, int Hkv, int N, int D, const void *K, const void *V,
+                       const int32_t *chunk_off, const int32_t *n_chunks, int c_max, const uint8_t *four_bit,
+                       uint8_t *kblob, uint8_t *vblob, int64_t blob_bytes, orc_qchunk *qmeta, int64_t *total_bytes) {
+    int64_t total = 0;
+    for (int b = 0; b < B; ++b) {
+        const int32_t *off = chunk_off + (size_t)b * (c_max + 1);
+        int64_t per_head = 0;
+        for (int c = 0; c < n_chunks[b]; ++c) {
+            int64_t row = four_bit[(size_t)b * c_max + c] ? D / 2 : D;
+            per_head += ((int64_t)(off[c + 1] - off[c]) * row + 15) / 16 * 16;
+        }
+        total += per_head * Hkv;
+    }
+    *total_bytes = total;
+    if (total > blob_bytes) return 1;
+    memset(qmeta, 0, (size_t)B * Hkv * c_max * sizeof(orc_qchunk));
+    int64_t pos = 0;
+    for (int b = 0; b < B; ++b) {
+        const int32_t *off = chunk_off + (size_t)b * (c_max + 1);
+        for (int h = 0; h < Hkv; ++h) {
+            size_t bh = (size_t)b * Hkv + h;
+            for (int c = 0; c < n_chunks[b]; ++c) {
+                orc_qchunk *m = qmeta + bh * c_max + c;
+                int four = four_bit[(size_t)b * c_max + c] != 0;
+                float levels = four ? 15.0f : 255.0f;
+                int64_t row = four ? D / 2 : D, rows = off[c + 1] - off[c];
+                m->byte_off = pos;
+                m->bits = four ? 4 : 8;
+                for (int use_v = 0; use_v < 2; ++use_v) {
+                    const void *X = use_v ? V : K;
+                    uint8_t *blob = use_v ? vblob : kblob;
+                    float lo = INFINITY, hi = -INFINITY;
+                    for (int t = off[c]; t < off[c + 1]; ++t)
+                        for (int d = 0; d < D; ++d) {
+                            float x = (float)widen(X, dtype, (bh * N + t) * D + d);
+                            if (x < lo) lo = x;
+                            if (x > hi) hi = x;
+                        }
+                    float range = hi - lo;
+                    float scale = range / levels;
+                    if (use_v) { m->scale_v = scale; m->zero_v = lo; } else { m->scale_k = scale; m->zero_k = lo; }
+                    for (int t = off[c]; t < off[c + 1]; ++t)
+                        for (int d = 0; d < D; ++d) {
+                            float x = (float)widen(X, dtype, (bh * N + t) * D + d);
+                            int code = 0;
+                            if (scale > 0.0f) {
+                                float diff = x - lo;
+                                float r = rintf(diff / scale);
+                                if (r < 0.0f) r = 0.0f;
+                                if (r > levels) r = levels;
+                                code = (int)r;
+                            }
+                            uint8_t *dst = blob + pos + (int64_t)(t - off[c]) * row;
+                            if (!four) dst[d] = (uint8_t)code;
+                            else if (d & 1) dst[d / 2] = (uint8_t)(dst[d / 2] | (code << 4));
+                            else dst[d / 2] = (uint8_t)code;
+                        }
+                }
+                int64_t bytes = (rows * row + 15) / 16 * 16;
+                for (int64_t i = rows * row; i < bytes; ++i) kblob[pos + i] = vblob[pos + i] = 0;
+                pos += bytes;
+            }
+        }
+    }
+    return 0;
+}
+
+/* Sec. 4.4: share theta of a layer's transmitted KV bytes that is sent compressed.
+ * Sending D bytes at bandwidth B with a share theta compressed to the ratio delta takes
+ * T0 + D (1 - theta + theta delta) / B (T0 = the other evaluation and transmission
+ * time); it hides behind the computation Tc plus the decompression of the compressed
+ * share, D theta / R for a decompression rate R (the "offline hardware test" gives B
+ * and R).  The transmission side falls with theta and the computation side rises, so
+ * the two meet at most once: theta is that point, kept inside [0, 1] (0: already
+ * hidden without compression; 1: not hidden even when everything is compressed). */
+double orc_compression_share(double D, double delta, double B, double T0, double Tc, double R) {
+    double excess = T0 + D / B - Tc;                         /* transmission beyond computation at theta = 0 */
+    double gain = D * (1.0 - delta) / B + D / R;             /* how much one unit of theta closes of it */
+    if (excess <= 0.0) return 0.0;
+    if (excess >= gain) return 1.0;
+    return excess / gain;
 }
 
 /* Sec. 4.3 abstract over the stored values, rounded outward to binary16:
