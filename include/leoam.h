@@ -275,6 +275,48 @@ size_t leoam_workspace_bytes(const leoam_shape* shape, int32_t max_tokens);
 int leoam_validate_boundaries(const leoam_shape* shape, const int32_t* chunk_off, const int32_t* n_chunks,
                               void* stream);
 
+/*
+ * Sec. 4.4 "Dynamic KV compression", Sec. 6.1 (KV held in FP16, compressed to
+ * INT4): builds the compressed store described at leoam_qchunk from an fp16 or
+ * bf16 cache.  Per (b, h, chunk c < n_chunks[b], tensor):
+ *   zero = min over the chunk's elements, scale = (max - min) / levels,
+ *   code = round-half-even((x - zero) / scale) kept inside 0..levels,
+ * levels = 15 where four_bit[b, c] != 0, else 255; max - min, the two divisions
+ * and x - zero are single correctly rounded float operations; scale == 0 (all
+ * elements equal) stores code 0.  Layout: the chunks of a (b,h) follow each
+ * other, then the next (b,h); K and V blobs use the same offsets.
+ *   shape->kv_dtype   dtype of K and V: LEOAM_F16 or LEOAM_BF16 (others: LEOAM_E_UNSUPPORTED)
+ *   K, V      [batch, n_kv_heads, n_ctx, 128]       in
+ *   four_bit  [batch, c_max] bytes                  in   which chunks are 4-bit
+ *   kblob, vblob  blob_bytes bytes each, 16-byte aligned   out
+ *   qmeta     [batch, n_kv_heads, c_max] leoam_qchunk      out  (records of chunks >= n_chunks[b]: all zero)
+ *   total_bytes  device int64, nullable                    out  bytes used of each blob
+ * blob_bytes must be at least leoam_compressed_bytes_bound() (the size with
+ * every chunk 8-bit), else LEOAM_E_WORKSPACE; the bytes past *total_bytes are
+ * not written.  Boundaries must tile the context (chunks that do not are skipped).
+ */
+int kv_chunk_compress(const leoam_shape* shape, const void* K, const void* V, const int32_t* chunk_off,
+                      const int32_t* n_chunks, const uint8_t* four_bit, void* kblob, void* vblob, size_t blob_bytes,
+                      void* qmeta, int64_t* total_bytes, void* stream);
+
+size_t leoam_compressed_bytes_bound(const leoam_shape* shape);
+
+/*
+ * Sec. 4.4: the share theta of a layer's n_bytes transmitted KV bytes that is
+ * sent compressed.  Sent at `bandwidth` bytes/s with a share theta compressed
+ * to `ratio` (compressed / uncompressed size), the data arrives after
+ *   t_other + n_bytes * (1 - theta + theta * ratio) / bandwidth
+ * (t_other: the other evaluation and transmission time); it is hidden while
+ * that does not exceed  t_compute + n_bytes * theta / decompress_rate  (the
+ * computation plus the decompression of the compressed share).  Returns the
+ * theta at which the two are equal, kept inside [0, 1]: 0 if the transfer is
+ * hidden without compression, 1 if it is not hidden even when everything is
+ * compressed.  Host arithmetic only; a negative value reports an invalid
+ * argument (sizes, rates not positive, ratio outside (0, 1]).
+ */
+double leoam_compression_share(double n_bytes, double ratio, double bandwidth, double t_other, double t_compute,
+                               double decompress_rate);
+
 /* Plain device copy of `bytes` bytes (multiple of 16, 16-byte aligned): the
  * known-size kernel that hardware byte counters are scaled against. */
 int leoam_copy_probe(void* dst, const void* src, size_t bytes, void* stream);

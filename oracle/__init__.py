@@ -356,7 +356,7 @@ def chunk_compress(K, V, chunk_off, n_chunks, four_bit):
                                     _ptr(kblob), _ptr(vblob), ctypes.c_int64(cap), _ptr(qm), _ptr(total))
     assert rc == 0
     n = int(total[0])
-    return kblob[:max(n, 16)].copy(), vblob[:max(n, 16)].copy(), qm
+    return kblob[:n].copy(), vblob[:n].copy(), qm
 
 
 def compression_share(n_bytes: float, ratio: float, bandwidth: float, t_other: float, t_compute: float,

@@ -53,6 +53,11 @@ def _load() -> ctypes.CDLL:
     lib.sparse_chunk_attention_decode.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, sz, vp]
     lib.chunk_select_attention_decode.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_float, vp, vp, vp,
                                                   vp, vp, vp, sz, vp]
+    lib.kv_chunk_compress.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp]
+    lib.leoam_compressed_bytes_bound.argtypes = [sp]
+    lib.leoam_compressed_bytes_bound.restype = sz
+    lib.leoam_compression_share.argtypes = [ctypes.c_double] * 6
+    lib.leoam_compression_share.restype = ctypes.c_double
     lib.leoam_workspace_bytes.argtypes = [sp, i32]
     lib.leoam_workspace_bytes.restype = sz
     lib.leoam_fused_workspace_bytes.argtypes = [sp, i32]
@@ -64,8 +69,8 @@ def _load() -> ctypes.CDLL:
     lib.leoam_status_string.restype = ctypes.c_char_p
     lib.leoam_version.restype = ctypes.c_int
     for name in ("kv_chunk_abstract_build", "chunk_score", "chunk_topk_select", "sparse_chunk_attention_decode",
-                 "chunk_select_attention_decode", "kv_chunk_abstract_append", "chunk_tree_refine", "leoam_workspace_init", "leoam_validate_boundaries",
-                 "leoam_copy_probe"):
+                 "chunk_select_attention_decode", "kv_chunk_abstract_append", "chunk_tree_refine", "kv_chunk_compress", "leoam_workspace_init",
+                 "leoam_validate_boundaries", "leoam_copy_probe"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -75,6 +80,7 @@ _lib = _load()
 EXPORTS = ("kv_chunk_abstract_build", "chunk_score", "chunk_topk_select", "sparse_chunk_attention_decode",
            "chunk_select_attention_decode", "leoam_fused_workspace_bytes", "leoam_workspace_init",
            "kv_chunk_abstract_append", "leoam_tree_evaluations", "chunk_tree_refine", "leoam_tree_workspace_bytes",
+           "kv_chunk_compress", "leoam_compressed_bytes_bound", "leoam_compression_share",
            "leoam_workspace_bytes", "leoam_validate_boundaries", "leoam_copy_probe", "leoam_status_string",
            "leoam_version")
 
@@ -130,6 +136,29 @@ def chunk_tree_refine(shape: Shape, q, K, abstract, chunk_size: int, k_tokens: i
                                   int(max_rounds), int(node_cap), _p(ref_off), _p(ref_score), _p(ref_count),
                                   _p(ref_evals), _p(ref_status), _p(workspace), nbytes, _stream(stream)),
            "chunk_tree_refine")
+
+
+def kv_chunk_compress(shape: Shape, K, V, chunk_off, n_chunks, four_bit, kblob, vblob, qmeta, total_bytes=None,
+                      stream=None) -> None:
+    """K, V fp16 / bf16 -> the 8-bit / 4-bit store (kblob, vblob uint8; qmeta int32 [B,Hkv,c_max,8])."""
+    if kblob.numel() * kblob.element_size() != vblob.numel() * vblob.element_size():
+        raise ValueError("kblob and vblob must have the same size")
+    _check(_lib.kv_chunk_compress(ctypes.byref(shape), _p(K), _p(V), _p(chunk_off), _p(n_chunks), _p(four_bit), _p(kblob),
+                                  _p(vblob), kblob.numel() * kblob.element_size(), _p(qmeta), _p(total_bytes),
+                                  _stream(stream)), "kv_chunk_compress")
+
+
+def leoam_compressed_bytes_bound(shape: Shape) -> int:
+    return int(_lib.leoam_compressed_bytes_bound(ctypes.byref(shape)))
+
+
+def leoam_compression_share(n_bytes: float, ratio: float, bandwidth: float, t_other: float, t_compute: float,
+                            decompress_rate: float) -> float:
+    th = float(_lib.leoam_compression_share(float(n_bytes), float(ratio), float(bandwidth), float(t_other),
+                                            float(t_compute), float(decompress_rate)))
+    if th < 0:
+        raise LeoamError(E_INVALID_ARG, "leoam_compression_share")
+    return th
 
 
 def leoam_tree_workspace_bytes(shape: Shape, node_cap: int) -> int:

@@ -1,0 +1,310 @@
+// kv_chunk_compress: builds the compressed KV store from the 16-bit cache
+// (paper Sec. 4.4 "Dynamic KV compression": the share of the data that is sent
+// compressed trades transfer time against decompression on the GPU; Sec. 6.1:
+// KV is held in FP16 and compressed to INT4).
+//
+// Per (b, h, chunk, tensor):  zero = min over the chunk's elements,
+// scale = (max - min) / levels, code = round-half-even((x - zero) / scale) kept
+// inside 0..levels, levels = 255 (8-bit chunk) or 15 (4-bit chunk, two codes per
+// byte, even channel in the low nibble).  Every operation that decides a code is
+// one correctly rounded float operation, in that order, so that the codes are
+// reproducible bit for bit.  scale == 0 (all elements equal) stores code 0.
+//
+// Two launches.  The layout kernel (one workgroup per sequence) turns chunk
+// sizes and 4-bit tags into byte offsets: the chunks of a (b,h) follow each
+// other, then the next (b,h); rows are 128 or 64 bytes, so every chunk starts on
+// a multiple of 16 bytes without padding.  The compression kernel gives one
+// workgroup to a (b, h, chunk): 16 lanes share a token row (16 bytes per lane,
+// 8 channels), the workgroup reduces min / max of K and of V, then encodes and
+// stores 8 (4) bytes per lane, rows contiguous.  Chunks of at most 64 tokens
+// keep their rows in registers between the two steps; longer ones read them a
+// second time (from L2).  Streaming work: bound by HBM.
+#include "leoam_dev.h"
+
+namespace leoam {
+
+struct QRecord {            // device image of leoam_qchunk
+    long long byte_off;
+    int bits;
+    float scale_k, zero_k, scale_v, zero_v;
+    int reserved;
+};
+static_assert(sizeof(QRecord) == sizeof(leoam_qchunk), "record layout");
+
+constexpr int kLayThreads = 1024;
+constexpr int kLayWaves = kLayThreads / LEOAM_WAVE;
+
+// sum of v over the workgroup (every thread gets it); `slots` holds kLayWaves values
+__device__ __forceinline__ unsigned long long layout_block_sum(unsigned long long v, unsigned long long* slots) {
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, LEOAM_WAVE);
+    __syncthreads();
+    if (lane_id() == 0) slots[threadIdx.x / LEOAM_WAVE] = v;
+    __syncthreads();
+    unsigned long long t = 0;
+#pragma unroll
+    for (int w = 0; w < kLayWaves; ++w) t += slots[w];
+    return t;
+}
+
+// bytes of chunk c of a sequence in one blob, for one kv head
+__device__ __forceinline__ int chunk_bytes(const int32_t* off, const uint8_t* four, int c) {
+    return (off[c + 1] - off[c]) * (four[c] ? LEOAM_D / 2 : LEOAM_D);
+}
+
+__global__ __launch_bounds__(kLayThreads) void compress_layout_kernel(
+    const int32_t* __restrict__ chunk_off, const int32_t* __restrict__ n_chunks, const uint8_t* __restrict__ four_bit,
+    QRecord* __restrict__ qmeta, long long* __restrict__ total_bytes, int c_max, int n_kv_heads, int batch) {
+    __shared__ unsigned long long slots[kLayWaves];
+    __shared__ unsigned long long wave_incl[kLayWaves];
+    const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wave = tid / LEOAM_WAVE;
+
+    // bytes of all the sequences before this one
+    unsigned long long before = 0;
+    for (int bb = 0; bb < b; ++bb) {
+        const int32_t* off = chunk_off + (size_t)bb * (c_max + 1);
+        const uint8_t* four = four_bit + (size_t)bb * c_max;
+        const int n = min(max(n_chunks[bb], 0), c_max);
+        unsigned long long part = 0;
+        for (int c = tid; c < n; c += kLayThreads) part += (unsigned long long)chunk_bytes(off, four, c);
+        before += layout_block_sum(part, slots) * (unsigned long long)n_kv_heads;
+    }
+
+    const int32_t* off = chunk_off + (size_t)b * (c_max + 1);
+    const uint8_t* four = four_bit + (size_t)b * c_max;
+    const int n = min(max(n_chunks[b], 0), c_max);
+    // bytes of one head of this sequence
+    unsigned long long part = 0;
+    for (int c = tid; c < n; c += kLayThreads) part += (unsigned long long)chunk_bytes(off, four, c);
+    const unsigned long long per_head = layout_block_sum(part, slots);
+
+    // exclusive scan over the chunks, a tile of 1024 at a time
+    unsigned long long carry = 0;
+    for (int base = 0; base < c_max; base += kLayThreads) {
+        const int c = base + tid;
+        const unsigned long long mine = c < n ? (unsigned long long)chunk_bytes(off, four, c) : 0ull;
+        unsigned long long incl = mine;
+        for (int d = 1; d < LEOAM_WAVE; d <<= 1) {
+            const unsigned long long up = __shfl_up(incl, d, LEOAM_WAVE);
+            if (lane >= d) incl += up;
+        }
+        __syncthreads();
+        if (lane == LEOAM_WAVE - 1) wave_incl[wave] = incl;
+        __syncthreads();
+        unsigned long long wave_before = 0, tile = 0;
+#pragma unroll
+        for (int w = 0; w < kLayWaves; ++w) {
+            if (w < wave) wave_before += wave_incl[w];
+            tile += wave_incl[w];
+        }
+        const unsigned long long within = carry + wave_before + incl - mine;
+        carry += tile;
+        if (c < c_max) {
+            for (int h = 0; h < n_kv_heads; ++h) {
+                QRecord r;
+                if (c < n) {
+                    r.byte_off = (long long)(before + (unsigned long long)h * per_head + within);
+                    r.bits = four[c] ? 4 : 8;
+                } else {
+                    r.byte_off = 0;
+                    r.bits = 0;
+                }
+                r.scale_k = r.zero_k = r.scale_v = r.zero_v = 0.f;
+                r.reserved = 0;
+                qmeta[((size_t)b * n_kv_heads + h) * c_max + c] = r;
+            }
+        }
+    }
+    if (b == batch - 1 && tid == 0 && total_bytes) *total_bytes = (long long)(before + per_head * n_kv_heads);
+}
+
+// ---- compression ---------------------------------------------------------------
+constexpr int kCmpThreads = 256;
+constexpr int kCmpWaves = kCmpThreads / LEOAM_WAVE;
+constexpr int kCmpGroups = kCmpThreads / 16;       // token rows per step
+constexpr int kCmpHeld = 4;                        // rows per lane group kept in registers
+constexpr int kCmpHeldRows = kCmpGroups * kCmpHeld;
+
+__device__ __forceinline__ float wave_min_f(float v) {
+    for (int m = 32; m >= 1; m >>= 1) v = fminf(v, shfl_xor_f(v, m));
+    return v;
+}
+__device__ __forceinline__ float wave_max_f(float v) {
+    for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, shfl_xor_f(v, m));
+    return v;
+}
+
+// the 8 codes of a lane's channels; every step is one correctly rounded float operation
+__device__ __forceinline__ void encode8(const float* x, float zero, float scale, float levels, uint32_t* code) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float r = 0.f;
+        if (scale > 0.f) {
+            const float diff = __fsub_rn(x[e], zero);
+            r = rintf(__fdiv_rn(diff, scale));
+            r = fminf(fmaxf(r, 0.f), levels);
+        }
+        code[e] = (uint32_t)r;
+    }
+}
+
+template <typename T>
+__device__ __forceinline__ void encode_row(const uint4& raw, float zero, float scale, bool four, unsigned char* dst_row,
+                                           int c16) {
+    float x[8];
+    unpack<T>(raw, x);
+    uint32_t code[8];
+    encode8(x, zero, scale, four ? 15.f : 255.f, code);
+    if (four) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) w |= code[e] << (4 * e);
+        *reinterpret_cast<uint32_t*>(dst_row + 4 * c16) = w;
+    } else {
+        uint2 w;
+        w.x = code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);
+        w.y = code[4] | (code[5] << 8) | (code[6] << 16) | (code[7] << 24);
+        *reinterpret_cast<uint2*>(dst_row + 8 * c16) = w;
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kCmpThreads) void compress_kernel(
+    const char* __restrict__ K, const char* __restrict__ V, const int32_t* __restrict__ chunk_off,
+    const int32_t* __restrict__ n_chunks, QRecord* __restrict__ qmeta, unsigned char* __restrict__ kblob,
+    unsigned char* __restrict__ vblob, int c_max, int n_kv_heads, int n_ctx) {
+    static_assert(T::kEpl == 8, "16-bit sources only");
+    constexpr int ROWB = Row<T>::kRowBytes;
+    __shared__ float red[4][kCmpWaves];
+
+    const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    if (c >= min(max(n_chunks[b], 0), c_max)) return;
+    const size_t bh = (size_t)b * n_kv_heads + h;
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid / LEOAM_WAVE;
+    const int grp = tid / 16, c16 = tid % 16;
+    const int32_t* off = chunk_off + (size_t)b * (c_max + 1);
+    const int t0 = off[c], rows = off[c + 1] - t0;
+    if (t0 < 0 || rows <= 0 || t0 + rows > n_ctx) return;        // boundaries that do not tile the context
+    QRecord* rec = qmeta + bh * c_max + c;
+    const long long byte_off = rec->byte_off;
+    const bool four = rec->bits == 4;
+    const char* Kc = K + (bh * (size_t)n_ctx + t0) * ROWB + (size_t)c16 * 16;
+    const char* Vc = V + (bh * (size_t)n_ctx + t0) * ROWB + (size_t)c16 * 16;
+    const bool held = rows <= kCmpHeldRows;
+
+    // ---- min / max of the chunk (a row past the end re-reads the last row) ------------
+    uint4 kr[kCmpHeld], vr[kCmpHeld];
+    float klo = INFINITY, khi = -INFINITY, vlo = INFINITY, vhi = -INFINITY;
+    auto fold = [&](const uint4& a, const uint4& bq) {
+        float x[8], y[8];
+        unpack<T>(a, x);
+        unpack<T>(bq, y);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            klo = fminf(klo, x[e]);
+            khi = fmaxf(khi, x[e]);
+            vlo = fminf(vlo, y[e]);
+            vhi = fmaxf(vhi, y[e]);
+        }
+    };
+#pragma unroll
+    for (int j = 0; j < kCmpHeld; ++j) {
+        const int r = min(grp + j * kCmpGroups, rows - 1);
+        kr[j] = load16(Kc, (size_t)r * ROWB);
+        vr[j] = load16(Vc, (size_t)r * ROWB);
+    }
+#pragma unroll
+    for (int j = 0; j < kCmpHeld; ++j) fold(kr[j], vr[j]);
+    for (int r0 = kCmpHeldRows; r0 < rows; r0 += kCmpHeldRows) {
+        uint4 a[kCmpHeld], bq[kCmpHeld];
+#pragma unroll
+        for (int j = 0; j < kCmpHeld; ++j) {
+            const int r = min(r0 + grp + j * kCmpGroups, rows - 1);
+            a[j] = load16(Kc, (size_t)r * ROWB);
+            bq[j] = load16(Vc, (size_t)r * ROWB);
+        }
+#pragma unroll
+        for (int j = 0; j < kCmpHeld; ++j) fold(a[j], bq[j]);
+    }
+    klo = wave_min_f(klo);
+    khi = wave_max_f(khi);
+    vlo = wave_min_f(vlo);
+    vhi = wave_max_f(vhi);
+    if (lane == 0) {
+        red[0][wave] = klo;
+        red[1][wave] = khi;
+        red[2][wave] = vlo;
+        red[3][wave] = vhi;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kCmpWaves; ++w) {
+        klo = fminf(klo, red[0][w]);
+        khi = fmaxf(khi, red[1][w]);
+        vlo = fminf(vlo, red[2][w]);
+        vhi = fmaxf(vhi, red[3][w]);
+    }
+    const float levels = four ? 15.f : 255.f;
+    const float scale_k = __fdiv_rn(__fsub_rn(khi, klo), levels), scale_v = __fdiv_rn(__fsub_rn(vhi, vlo), levels);
+    if (tid == 0) {
+        rec->scale_k = scale_k;
+        rec->zero_k = klo;
+        rec->scale_v = scale_v;
+        rec->zero_v = vlo;
+    }
+
+    // ---- codes ---------------------------------------------------------------------------
+    const int row_bytes = four ? LEOAM_D / 2 : LEOAM_D;
+    unsigned char* kdst = kblob + byte_off;
+    unsigned char* vdst = vblob + byte_off;
+#pragma unroll
+    for (int j = 0; j < kCmpHeld; ++j) {
+        const int r = grp + j * kCmpGroups;
+        if (r < rows) {
+            encode_row<T>(kr[j], klo, scale_k, four, kdst + (size_t)r * row_bytes, c16);
+            encode_row<T>(vr[j], vlo, scale_v, four, vdst + (size_t)r * row_bytes, c16);
+        }
+    }
+    if (held) return;
+    for (int r0 = kCmpHeldRows; r0 < rows; r0 += kCmpHeldRows) {
+        uint4 a[kCmpHeld], bq[kCmpHeld];
+#pragma unroll
+        for (int j = 0; j < kCmpHeld; ++j) {
+            const int r = min(r0 + grp + j * kCmpGroups, rows - 1);
+            a[j] = load16(Kc, (size_t)r * ROWB);
+            bq[j] = load16(Vc, (size_t)r * ROWB);
+        }
+#pragma unroll
+        for (int j = 0; j < kCmpHeld; ++j) {
+            const int r = r0 + grp + j * kCmpGroups;
+            if (r < rows) {
+                encode_row<T>(a[j], klo, scale_k, four, kdst + (size_t)r * row_bytes, c16);
+                encode_row<T>(bq[j], vlo, scale_v, four, vdst + (size_t)r * row_bytes, c16);
+            }
+        }
+    }
+}
+
+size_t compressed_bytes_bound(const leoam_shape* s) {
+    return (size_t)s->batch * s->n_kv_heads * (size_t)s->n_ctx * LEOAM_D;        // every chunk 8-bit
+}
+
+hipError_t compress_dispatch(const leoam_shape* s, const void* K, const void* V, const int32_t* chunk_off,
+                             const int32_t* n_chunks, const uint8_t* four_bit, void* kblob, void* vblob, void* qmeta,
+                             long long* total_bytes, hipStream_t stream) {
+    hipLaunchKernelGGL(compress_layout_kernel, dim3(s->batch), dim3(kLayThreads), 0, stream, chunk_off, n_chunks,
+                       four_bit, (QRecord*)qmeta, total_bytes, s->c_max, s->n_kv_heads, s->batch);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    dim3 grid(s->c_max, s->n_kv_heads, s->batch), block(kCmpThreads);
+    if (s->kv_dtype == LEOAM_F16)
+        hipLaunchKernelGGL(compress_kernel<F16>, grid, block, 0, stream, (const char*)K, (const char*)V, chunk_off,
+                           n_chunks, (QRecord*)qmeta, (unsigned char*)kblob, (unsigned char*)vblob, s->c_max,
+                           s->n_kv_heads, s->n_ctx);
+    else
+        hipLaunchKernelGGL(compress_kernel<BF16>, grid, block, 0, stream, (const char*)K, (const char*)V, chunk_off,
+                           n_chunks, (QRecord*)qmeta, (unsigned char*)kblob, (unsigned char*)vblob, s->c_max,
+                           s->n_kv_heads, s->n_ctx);
+    return hipGetLastError();
+}
+
+}  // namespace leoam

@@ -28,6 +28,9 @@ hipError_t workspace_zero_dispatch(void*, size_t, hipStream_t);
 size_t tree_workspace_bytes(const leoam_shape*, int);
 hipError_t tree_refine_dispatch(const leoam_shape*, const void*, const void*, const void*, int, int, int, int, int32_t*,
                                 float*, int32_t*, int32_t*, int32_t*, void*, hipStream_t);
+size_t compressed_bytes_bound(const leoam_shape*);
+hipError_t compress_dispatch(const leoam_shape*, const void*, const void*, const int32_t*, const int32_t*, const uint8_t*,
+                             void*, void*, void*, long long*, hipStream_t);
 hipError_t abstract_append_dispatch(const leoam_shape*, const void*, int32_t*, int32_t*, int, void*, int32_t*, hipStream_t);
 
 __global__ void copy_probe_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
@@ -227,6 +230,36 @@ int leoam_validate_boundaries(const leoam_shape* shape, const int32_t* chunk_off
             if (o[c + 1] <= o[c]) return LEOAM_E_BAD_BOUNDARIES;
     }
     return LEOAM_OK;
+}
+
+size_t leoam_compressed_bytes_bound(const leoam_shape* shape) {
+    if (check_shape(shape)) return 0;
+    return compressed_bytes_bound(shape);
+}
+
+int kv_chunk_compress(const leoam_shape* shape, const void* K, const void* V, const int32_t* chunk_off,
+                      const int32_t* n_chunks, const uint8_t* four_bit, void* kblob, void* vblob, size_t blob_bytes,
+                      void* qmeta, int64_t* total_bytes, void* stream) {
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!K || !V || !chunk_off || !n_chunks || !four_bit || !kblob || !vblob || !qmeta) return LEOAM_E_INVALID_ARG;
+    if (shape->kv_dtype != LEOAM_F16 && shape->kv_dtype != LEOAM_BF16) return LEOAM_E_UNSUPPORTED;
+    if (((uintptr_t)kblob & 15u) || ((uintptr_t)vblob & 15u) || ((uintptr_t)qmeta & 15u)) return LEOAM_E_INVALID_ARG;
+    if (blob_bytes < compressed_bytes_bound(shape)) return LEOAM_E_WORKSPACE;
+    return from_hip(compress_dispatch(shape, K, V, chunk_off, n_chunks, four_bit, kblob, vblob, qmeta,
+                                      (long long*)total_bytes, (hipStream_t)stream));
+}
+
+double leoam_compression_share(double n_bytes, double ratio, double bandwidth, double t_other, double t_compute,
+                               double decompress_rate) {
+    if (!(n_bytes > 0.0) || !(bandwidth > 0.0) || !(decompress_rate > 0.0) || !(ratio > 0.0) || ratio > 1.0 ||
+        !(t_other >= 0.0) || !(t_compute >= 0.0))
+        return -1.0;
+    // transfer time beyond the computation with nothing compressed, and what a full share takes off it
+    const double uncovered = t_other + n_bytes / bandwidth - t_compute;
+    const double per_share = n_bytes * (1.0 - ratio) / bandwidth + n_bytes / decompress_rate;
+    if (uncovered <= 0.0) return 0.0;
+    return uncovered >= per_share ? 1.0 : uncovered / per_share;
 }
 
 int leoam_copy_probe(void* dst, const void* src, size_t bytes, void* stream) {

@@ -1,0 +1,186 @@
+"""GPU parity of kv_chunk_compress (Sec. 4.4 dynamic KV compression, Sec. 6.1 INT4)
+against the CPU oracle: byte offsets, formats, scales, zero points and every code
+byte bit-exact (the code decision is taken in float on both sides)."""
+import numpy as np
+import pytest
+import torch
+
+import gen
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def L():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2506_20187_amd as lib
+    return lib
+
+
+def gpu_compress(L, K, V, packed, counts, fb, hq=None, poison=True):
+    B, Hkv, N, _ = K.shape
+    c_max = packed.shape[1] - 1
+    shape = L.make_shape(B, hq or Hkv, Hkv, 128, N, c_max, 1, K.dtype)
+    cap = L.leoam_compressed_bytes_bound(shape)
+    assert cap == B * Hkv * N * 128
+    kb = torch.full((cap,), 0xA5 if poison else 0, dtype=torch.uint8, device="cuda")
+    vb = torch.full((cap,), 0x5A if poison else 0, dtype=torch.uint8, device="cuda")
+    qm = torch.full((B, Hkv, c_max, 8), -7, dtype=torch.int32, device="cuda")
+    total = torch.zeros(1, dtype=torch.int64, device="cuda")
+    L.kv_chunk_compress(shape, K.cuda(), V.cuda(), torch.from_numpy(packed).cuda(), torch.from_numpy(counts).cuda(),
+                        torch.from_numpy(np.ascontiguousarray(fb).astype(np.uint8)).cuda(), kb, vb, qm, total)
+    torch.cuda.synchronize()
+    return kb.cpu().numpy(), vb.cpu().numpy(), qm.cpu().numpy(), int(total.item())
+
+
+def check_against_oracle(oracle, got, K, V, packed, counts, fb):
+    kb, vb, qm, total = got
+    wk, wv, wq = oracle.chunk_compress(K, V, packed, counts, fb)
+    assert total == wk.size == wv.size
+    rec = qm.view(oracle.QCHUNK_DTYPE).reshape(wq.shape)
+    assert np.array_equal(rec.view(np.uint8), wq.view(np.uint8)), "records (offsets, formats, scales, zero points)"
+    assert np.array_equal(kb[:total], wk[:total]), "K codes"
+    assert np.array_equal(vb[:total], wv[:total]), "V codes"
+    # nothing past the used bytes is touched
+    assert (kb[total:] == 0xA5).all() and (vb[total:] == 0x5A).all()
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+@pytest.mark.parametrize("share", [0.0, 0.5, 1.0])
+def test_compress_exact_ragged_chunks(L, oracle, dtype, share):
+    # chunk sizes 1..200: below, at and above the 64 rows a workgroup holds in registers; three tiles of the
+    # layout scan would need c_max > 2048, covered by the full-shape test below
+    rng = np.random.default_rng(int(share * 10) + (dtype == torch.float16))
+    g = torch.Generator().manual_seed(5)
+    B, Hkv, N = 2, 3, 3000
+    K = (torch.randn(B, Hkv, N, 128, generator=g) * 1.9).to(dtype)
+    V = torch.randn(B, Hkv, N, 128, generator=g).to(dtype)
+    offs = [gen.make_boundaries(N, rng, sizes=(1, 2, 15, 16, 63, 64, 65, 130, 200)) for _ in range(B)]
+    packed, counts, c_max = gen.pack_boundaries(offs, N)
+    assert counts.min() < c_max or B == 1                 # some unused record slots
+    fb = rng.random((B, c_max)) < share
+    check_against_oracle(oracle, gpu_compress(L, K, V, packed, counts, fb), K, V, packed, counts, fb)
+
+
+def test_compress_degenerate_values(L, oracle):
+    # constant chunks (scale 0), chunks on the code grid with ties, one huge outlier, negative zero
+    N, B, Hkv = 256, 1, 2
+    g = torch.Generator().manual_seed(9)
+    K = torch.randn(B, Hkv, N, 128, generator=g)
+    V = torch.randn(B, Hkv, N, 128, generator=g)
+    K[:, :, 0:16] = 0.75                                     # constant
+    V[:, :, 0:16] = -0.0
+    K[:, :, 16:32] = torch.arange(16 * 128).reshape(16, 128).remainder(256).float() * 0.5      # ties at k + 1/2 steps
+    K[:, :, 16, 0], K[:, :, 16, 1] = 0.0, 255.0
+    V[:, :, 40, 7] = 60000.0                                 # outlier: everything else collapses to code 0
+    K, V = K.to(torch.float16), V.to(torch.float16)
+    packed = np.array([[0, 16, 32, 48, 256]], dtype=np.int32)
+    counts = np.array([4], dtype=np.int32)
+    for fb in ([[False, False, False, False]], [[True, True, True, True]], [[False, True, False, True]]):
+        fb = np.array(fb)
+        check_against_oracle(oracle, gpu_compress(L, K, V, packed, counts, fb), K, V, packed, counts, fb)
+
+
+def test_compress_then_decode_path(L, oracle):
+    """The store written by the GPU feeds the compressed decode path: abstract, score, selection and attention
+    equal the oracle's on that store."""
+    rng = np.random.default_rng(3)
+    g = torch.Generator().manual_seed(3)
+    B, Hkv, G, N = 2, 2, 4, 2048
+    K = (torch.randn(B, Hkv, N, 128, generator=g) * 1.5).to(torch.float16)
+    V = torch.randn(B, Hkv, N, 128, generator=g).to(torch.float16)
+    q = (torch.randn(B, Hkv * G, 128, generator=g)).to(torch.float16)
+    offs = [gen.make_boundaries(N, rng, sizes=(16, 32, 64, 128)) for _ in range(B)]
+    packed, counts, c_max = gen.pack_boundaries(offs, N)
+    fb = rng.random((B, c_max)) < 0.5
+    kb, vb, qm, total = gpu_compress(L, K, V, packed, counts, fb, hq=Hkv * G, poison=False)
+    lay = L.DecodeLayer(torch.from_numpy(kb).cuda(), torch.from_numpy(vb).cuda(), torch.from_numpy(packed).cuda(),
+                        torch.from_numpy(counts).cuda(), Hkv * G, c_max, 0, 512, qmeta=torch.from_numpy(qm).cuda(),
+                        n_kv_heads=Hkv, n_ctx=N)
+    lay.build_abstract()
+    lay.step(q.cuda())
+    torch.cuda.synchronize()
+    rec = qm.view(oracle.QCHUNK_DTYPE).reshape(B, Hkv, c_max)
+    ab = oracle.abstract_build_q(kb, rec, packed, counts)
+    ub = oracle.chunk_score(q, np.nan_to_num(ab), counts)
+    assert np.array_equal(lay.score.cpu().numpy(), ub)
+    sel, cnt, tok = oracle.topk_select(ub, packed, counts, 0, 512, c_max)
+    assert np.array_equal(lay.sel_idx.cpu().numpy(), sel) and np.array_equal(lay.sel_count.cpu().numpy(), cnt)
+    out, lse = oracle.sparse_attention_q(q, kb, vb, rec, packed, sel, cnt)
+    assert np.abs(lay.out.cpu().numpy().astype(np.float64) - out).max() <= 2e-3
+    # and the store is close to the cache it came from: half a step per element
+    deq = oracle.dequant(kb, rec, packed, counts, N, 128, "k")
+    step = np.zeros((B, Hkv, N))
+    for b in range(B):
+        step[b] = np.repeat(rec["scale_k"][b, :, :counts[b]], np.diff(packed[b, :counts[b] + 1]), axis=1)
+    assert (np.abs(deq - K.double().numpy()) <= step[..., None] * (0.5 + 1e-4) + 1e-12).all()
+
+
+def test_compress_full_shape_sampled(L, oracle):
+    """The compressed-store workload at its full shape (512K tokens, 8 kv heads, chunks of 32..512): the layout
+    is checked everywhere by its defining sums, sampled chunks against the oracle one by one."""
+    case = gen.make_case("c4", layer=3, device="cuda")
+    K, V = case.K, case.V
+    assert K.dtype in (torch.float16, torch.bfloat16)
+    packed, counts = case.chunk_off.cpu().numpy(), case.n_chunks.cpu().numpy()
+    B, Hkv, N, _ = K.shape
+    c_max = packed.shape[1] - 1
+    fb = gen.tag_four_bit(packed, counts, case.extra["heavy"], 0.5)
+    shape = L.make_shape(B, case.hq, Hkv, 128, N, c_max, 1, K.dtype)
+    cap = L.leoam_compressed_bytes_bound(shape)
+    kb = torch.zeros(cap, dtype=torch.uint8, device="cuda")
+    vb = torch.zeros(cap, dtype=torch.uint8, device="cuda")
+    qm = torch.zeros(B, Hkv, c_max, 8, dtype=torch.int32, device="cuda")
+    total = torch.zeros(1, dtype=torch.int64, device="cuda")
+    L.kv_chunk_compress(shape, K, V, case.chunk_off, case.n_chunks, torch.from_numpy(fb.astype(np.uint8)).cuda(), kb, vb,
+                        qm, total)
+    torch.cuda.synchronize()
+    rec = qm.cpu().numpy().view(oracle.QCHUNK_DTYPE).reshape(B, Hkv, c_max)
+    sizes = np.diff(packed.astype(np.int64), axis=1)
+    pos = 0
+    for b in range(B):
+        n = counts[b]
+        nbytes = sizes[b, :n] * np.where(fb[b, :n], 64, 128)
+        within = np.concatenate([[0], np.cumsum(nbytes)[:-1]])
+        for h in range(Hkv):
+            assert np.array_equal(rec["byte_off"][b, h, :n], pos + within)
+            assert np.array_equal(rec["bits"][b, h, :n], np.where(fb[b, :n], 4, 8))
+            pos += int(nbytes.sum())
+        assert not rec[b, :, n:].view(np.uint8).any()
+    assert int(total.item()) == pos
+    rng = np.random.default_rng(0)
+    kb_h, vb_h = kb[:pos].cpu().numpy(), vb[:pos].cpu().numpy()
+    picks = [(0, h, int(c)) for h in range(Hkv) for c in rng.choice(counts[0], size=6, replace=False)]
+    picks += [(0, 0, 0), (0, Hkv - 1, int(counts[0]) - 1), (0, 3, int(np.argmax(sizes[0, :counts[0]])))]
+    for b, h, c in picks:
+        t0, t1 = int(packed[b, c]), int(packed[b, c + 1])
+        wk, wv, wq = oracle.chunk_compress(K[b:b + 1, h:h + 1, t0:t1].cpu(), V[b:b + 1, h:h + 1, t0:t1].cpu(),
+                                           np.array([[0, t1 - t0]], dtype=np.int32), np.array([1], dtype=np.int32),
+                                           np.array([[fb[b, c]]]))
+        r, w = rec[b, h, c], wq[0, 0, 0]
+        for f in ("bits", "scale_k", "zero_k", "scale_v", "zero_v"):
+            assert r[f] == w[f], (b, h, c, f)
+        o = int(r["byte_off"])
+        assert np.array_equal(kb_h[o:o + wk.size], wk) and np.array_equal(vb_h[o:o + wv.size], wv), (b, h, c)
+
+
+def test_compress_error_codes(L):
+    B, Hkv, N, c_max = 1, 2, 64, 4
+    K = torch.zeros(B, Hkv, N, 128, dtype=torch.float16, device="cuda")
+    off = torch.tensor([[0, 16, 32, 48, 64]], dtype=torch.int32, device="cuda")
+    nc = torch.tensor([4], dtype=torch.int32, device="cuda")
+    fb = torch.zeros(B, c_max, dtype=torch.uint8, device="cuda")
+    qm = torch.zeros(B, Hkv, c_max, 8, dtype=torch.int32, device="cuda")
+    shape = L.make_shape(B, Hkv, Hkv, 128, N, c_max, 1, torch.float16)
+    small = torch.zeros(B * Hkv * N * 128 - 16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(L.LeoamError) as e:
+        L.kv_chunk_compress(shape, K, K, off, nc, fb, small, small, qm)
+    assert e.value.status == L.binding.E_WORKSPACE
+    ok = torch.zeros(B * Hkv * N * 128, dtype=torch.uint8, device="cuda")
+    K32 = K.float()
+    with pytest.raises(L.LeoamError) as e:
+        L.kv_chunk_compress(L.make_shape(B, Hkv, Hkv, 128, N, c_max, 1, torch.float32), K32, K32, off, nc, fb, ok, ok, qm)
+    assert e.value.status == L.binding.E_UNSUPPORTED
+    L.kv_chunk_compress(shape, K, K, off, nc, fb, ok, ok, qm)       # all-zero cache: scale 0, codes 0
+    torch.cuda.synchronize()
+    assert not ok.any() and (qm[..., 2] == 8).all() and not qm[..., 3:].any()

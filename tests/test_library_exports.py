@@ -3,6 +3,8 @@ import ctypes
 import os
 import re
 
+import pytest
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
@@ -70,3 +72,33 @@ def test_host_side_checks_of_the_later_entry_points():
     assert lib.kv_chunk_abstract_append(ctypes.byref(L.make_shape(1, 4, 1, 128, 4096, 64, 1, 3)), None, None, None, 64,
                                         None, None, None) in (-1, -3)
     assert lib.leoam_workspace_init(None, 16, None) == -1
+
+
+def test_host_side_checks_of_the_compression_entry_points():
+    """Argument refusals of kv_chunk_compress and the compressed share theta (Sec. 4.4) are host arithmetic."""
+    import paper_2506_20187_amd as L
+    lib = L.binding._lib
+    s = L.make_shape(2, 8, 2, 128, 1000, 64, 16, 1)
+    assert L.leoam_compressed_bytes_bound(s) == 2 * 2 * 1000 * 128
+    none = [None] * 3
+
+    def compress(shape, blob_bytes, ptr=None):
+        return lib.kv_chunk_compress(ctypes.byref(shape), ptr, ptr, ptr, ptr, ptr, ptr, ptr, blob_bytes, ptr, None, None)
+    assert compress(s, 1 << 20) == -1                                        # null pointers
+    fake = ctypes.c_void_p(4096)
+    assert compress(L.make_shape(2, 8, 2, 128, 1000, 64, 16, 0), 1 << 20, fake) == -3      # fp32 source
+    assert compress(s, 2 * 2 * 1000 * 128 - 1, fake) == -4                   # blobs below the bound
+    # theta: equal sides inside (0, 1); the formula's two sides are written out here
+    D, ratio, bw, t0, tc, rate = 64e6, 0.25, 16e9, 0.3e-3, 2.0e-3, 200e9
+    th = L.leoam_compression_share(D, ratio, bw, t0, tc, rate)
+    assert 0 < th < 1
+    assert abs((t0 + D * (1 - th + th * ratio) / bw) - (tc + D * th / rate)) < 1e-12
+    assert L.leoam_compression_share(D, ratio, bw, 0.0, 10e-3, rate) == 0.0
+    assert L.leoam_compression_share(D, ratio, 1e9, t0, 1e-3, rate) == 1.0
+    import oracle
+    for args in ((D, ratio, bw, t0, tc, rate), (1e9, 0.5, 50e9, 0.0, 5e-3, 1e12), (3e8, 0.27, 25e9, 1e-3, 4e-3, 3e11)):
+        assert abs(L.leoam_compression_share(*args) - oracle.compression_share(*args)) <= 1e-15
+    with pytest.raises(L.LeoamError):
+        L.leoam_compression_share(D, 1.5, bw, t0, tc, rate)
+    with pytest.raises(L.LeoamError):
+        L.leoam_compression_share(-1.0, ratio, bw, t0, tc, rate)
