@@ -6,7 +6,10 @@ chunk_select_attention_decode (selection + attention over the kept chunks in
 one call) -- over every resident layer of the workload, inputs already in HBM.
 The separate chunk_topk_select and sparse_chunk_attention_decode calls are
 timed on their own as well.  kv_chunk_abstract_build is the prefill-time call;
-it is timed on its own and reported under "abstract_build".
+it is timed on its own and reported under "abstract_build".  kv_chunk_compress
+(the builder of the 8-bit / 4-bit store; it also writes the compressed
+workload's store here), kv_chunk_abstract_append and chunk_tree_refine are
+timed on their own under "compress", "abstract_append_us" and "tree_refine".
 
 Prints ONE JSON line.  `value` is the algorithmic KV traffic of the step
 (abstracts read + scores written and re-read + kept K/V rows read + q in + out
@@ -106,6 +109,34 @@ def time_calls(fn, reps, torch):
     return start.elapsed_time(stop) / reps
 
 
+def compress_store(B, torch, case, four_bit, timed):
+    """kv_chunk_compress of one layer (Sec. 4.4 / 6.1).  Returns the blobs cut to the used bytes, the records and,
+    if `timed`, the timing record: source bytes read plus code bytes written per second."""
+    import numpy as np
+    nb, hk, n_ctx = case.K.shape[0], case.K.shape[1], case.K.shape[2]
+    c_max = case.chunk_off.shape[1] - 1
+    shape = B.make_shape(nb, case.hq, hk, 128, n_ctx, c_max, 1, case.K.dtype)
+    cap = B.leoam_compressed_bytes_bound(shape)
+    kb = torch.empty(cap, dtype=torch.uint8, device="cuda")
+    vb = torch.empty(cap, dtype=torch.uint8, device="cuda")
+    qm = torch.empty(nb, hk, c_max, 8, dtype=torch.int32, device="cuda")
+    used = torch.zeros(1, dtype=torch.int64, device="cuda")
+    fbd = torch.from_numpy(np.ascontiguousarray(four_bit).astype(np.uint8)).cuda()
+    call = lambda: B.kv_chunk_compress(shape, case.K, case.V, case.chunk_off, case.n_chunks, fbd, kb, vb, qm, used)
+    rec = None
+    if timed:
+        ms = time_calls(call, 5, torch)
+        n = int(used.item())
+        src = 2 * case.K.numel() * case.K.element_size()
+        rec = {"us_per_layer": round(ms * 1e3, 1), "source_bytes": src, "code_bytes": 2 * n, "four_bit_share_of_chunks": 0.5,
+               "GBps_read_plus_written": round((src + 2 * n) / (ms * 1e-3) / 1e9, 1)}
+    else:
+        call()
+        torch.cuda.synchronize()
+        n = int(used.item())
+    return kb[:n].clone(), vb[:n].clone(), qm, rec
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -129,16 +160,22 @@ def main():
 
     t0 = time.time()
     layers, cases, tags = [], [], []
+    compress = None
     quant = args.workload == "c4"
     for lid in layer_ids:
         if quant:
-            qc = gen.make_quant_case("c4", layer=lid, device="cuda")
-            case = qc.case
-            lay = L.DecodeLayer(qc.kblob, qc.vblob, case.chunk_off, case.n_chunks, case.hq, case.k_max,
-                                case.max_chunks, case.token_budget, qmeta=qc.qmeta, n_kv_heads=case.hkv,
+            # the compressed store is written by the library's own compression call (half of the chunks,
+            # those without a heavy token, as 4-bit); the first layer's call is timed
+            case = gen.make_case("c4", layer=lid, device="cuda")
+            case.q = case.q.to(torch.float16)
+            fb = gen.tag_four_bit(case.chunk_off.cpu().numpy(), case.n_chunks.cpu().numpy(), case.extra["heavy"], 0.5)
+            kblob, vblob, qmeta, rec = compress_store(B, torch, case, fb, timed=compress is None)
+            compress = compress or rec
+            lay = L.DecodeLayer(kblob, vblob, case.chunk_off, case.n_chunks, case.hq, case.k_max,
+                                case.max_chunks, case.token_budget, qmeta=qmeta, n_kv_heads=case.hkv,
                                 n_ctx=case.n_ctx)
             case.K = case.V = None          # only the compressed store stays resident
-            tags.append(qc.four_bit)
+            tags.append(fb)
         else:
             case = gen.make_case(args.workload, layer=lid, device="cuda")
             lay = L.DecodeLayer(case.K, case.V, case.chunk_off, case.n_chunks, case.hq, case.k_max, case.max_chunks,
@@ -255,6 +292,12 @@ def main():
                           "node_cap_overflows": int(r_st.sum())}
         del u_ab, r_off, r_score, tws, Kd, qd
 
+    # ---- compression of one layer's cache to the 8-bit / 4-bit store (Sec. 4.4 / 6.1), 16-bit stores -------
+    if not quant and cfg["dtype"] in ("f16", "bf16"):
+        case = cases[0]
+        fb = gen.tag_four_bit(case.chunk_off.cpu().numpy(), case.n_chunks.cpu().numpy(), case.extra["heavy"], 0.5)
+        compress = compress_store(B, torch, case, fb, timed=True)[3]
+
     # ---- plain copy of known size: the "what does this box stream" reference ------
     nbytes = 1 << 30
     src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
@@ -310,6 +353,7 @@ def main():
                            "ms_per_layer": round(ab_ms / nl, 3)},
         "abstract_append_us": None if append_us is None else round(append_us, 2),
         "tree_refine": tree,
+        "compress": compress,
         "copy_probe_GBps": round(copy_gbs, 1),
     }
 

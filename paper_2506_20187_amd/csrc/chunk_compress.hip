@@ -10,15 +10,15 @@
 // one correctly rounded float operation, in that order, so that the codes are
 // reproducible bit for bit.  scale == 0 (all elements equal) stores code 0.
 //
-// Two launches.  The layout kernel (one workgroup per sequence) turns chunk
+// Two launches.  The layout kernel (one workgroup per sequence and kv head) turns chunk
 // sizes and 4-bit tags into byte offsets: the chunks of a (b,h) follow each
 // other, then the next (b,h); rows are 128 or 64 bytes, so every chunk starts on
 // a multiple of 16 bytes without padding.  The compression kernel gives one
-// workgroup to a (b, h, chunk): 16 lanes share a token row (16 bytes per lane,
-// 8 channels), the workgroup reduces min / max of K and of V, then encodes and
-// stores 8 (4) bytes per lane, rows contiguous.  Chunks of at most 64 tokens
-// keep their rows in registers between the two steps; longer ones read them a
-// second time (from L2).  Streaming work: bound by HBM.
+// workgroup to a (b, h, chunk, tensor): 16 lanes share a token row (16 bytes per
+// lane, 8 channels), the workgroup reduces min / max, then encodes and stores
+// 8 (4) bytes per lane, rows contiguous.  The first 64 tokens of a chunk stay in
+// registers between the two steps; the rest is read a second time (from L2).
+// Streaming work: bound by HBM.
 #include "leoam_dev.h"
 
 namespace leoam {
@@ -56,7 +56,8 @@ __global__ __launch_bounds__(kLayThreads) void compress_layout_kernel(
     QRecord* __restrict__ qmeta, long long* __restrict__ total_bytes, int c_max, int n_kv_heads, int batch) {
     __shared__ unsigned long long slots[kLayWaves];
     __shared__ unsigned long long wave_incl[kLayWaves];
-    const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wave = tid / LEOAM_WAVE;
+    // one workgroup per (kv head, sequence): each repeats the sequence's sums and writes its head's records
+    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / LEOAM_WAVE;
 
     // bytes of all the sequences before this one
     unsigned long long before = 0;
@@ -99,22 +100,20 @@ __global__ __launch_bounds__(kLayThreads) void compress_layout_kernel(
         const unsigned long long within = carry + wave_before + incl - mine;
         carry += tile;
         if (c < c_max) {
-            for (int h = 0; h < n_kv_heads; ++h) {
-                QRecord r;
-                if (c < n) {
-                    r.byte_off = (long long)(before + (unsigned long long)h * per_head + within);
-                    r.bits = four[c] ? 4 : 8;
-                } else {
-                    r.byte_off = 0;
-                    r.bits = 0;
-                }
-                r.scale_k = r.zero_k = r.scale_v = r.zero_v = 0.f;
-                r.reserved = 0;
-                qmeta[((size_t)b * n_kv_heads + h) * c_max + c] = r;
+            QRecord r;
+            if (c < n) {
+                r.byte_off = (long long)(before + (unsigned long long)h * per_head + within);
+                r.bits = four[c] ? 4 : 8;
+            } else {
+                r.byte_off = 0;
+                r.bits = 0;
             }
+            r.scale_k = r.zero_k = r.scale_v = r.zero_v = 0.f;
+            r.reserved = 0;
+            qmeta[((size_t)b * n_kv_heads + h) * c_max + c] = r;
         }
     }
-    if (b == batch - 1 && tid == 0 && total_bytes) *total_bytes = (long long)(before + per_head * n_kv_heads);
+    if (b == batch - 1 && h == 0 && tid == 0 && total_bytes) *total_bytes = (long long)(before + per_head * n_kv_heads);
 }
 
 // ---- compression ---------------------------------------------------------------
@@ -133,36 +132,47 @@ __device__ __forceinline__ float wave_max_f(float v) {
     return v;
 }
 
-// the 8 codes of a lane's channels; every step is one correctly rounded float operation
-__device__ __forceinline__ void encode8(const float* x, float zero, float scale, float levels, uint32_t* code) {
+// The 8 codes of a lane's channels, as integer-valued floats: round-half-even of the
+// correctly rounded quotient (x - zero) / scale.  The quotient is first approximated by a
+// multiplication with inv = 1 / scale (0 for scale == 0, which gives code 0): both that
+// product and the rounded quotient lie within 255.5 * 2^-23 < 2^-15 of the true quotient,
+// so whenever the product is at least 2^-13 away from every half-integer the two round to
+// the same integer.  A wave in which some lane is closer (ties among them) redoes its row
+// with the division; the branch is taken by the whole wave so that it stays a branch.
+// No clamp is needed: 0 <= x - zero <= max - min, so the quotient stays below levels + 1/2.
+__device__ __forceinline__ void encode8(const float* x, float zero, float scale, float inv, float* r) {
+    float diff[8], dev = 0.f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        float r = 0.f;
-        if (scale > 0.f) {
-            const float diff = __fsub_rn(x[e], zero);
-            r = rintf(__fdiv_rn(diff, scale));
-            r = fminf(fmaxf(r, 0.f), levels);
-        }
-        code[e] = (uint32_t)r;
+        diff[e] = __fsub_rn(x[e], zero);
+        const float q = __fmul_rn(diff[e], inv);
+        r[e] = rintf(q);
+        dev = fmaxf(dev, fabsf(q - r[e]));
+    }
+    if (__builtin_amdgcn_ballot_w64(!(dev < 0.5f - 0x1p-13f)) != 0) {        // also taken for inf / nan products
+#pragma unroll
+        for (int e = 0; e < 8; ++e) r[e] = scale > 0.f ? rintf(__fdiv_rn(diff[e], scale)) : 0.f;
     }
 }
 
 template <typename T>
-__device__ __forceinline__ void encode_row(const uint4& raw, float zero, float scale, bool four, unsigned char* dst_row,
-                                           int c16) {
-    float x[8];
+__device__ __forceinline__ void encode_row(const uint4& raw, float zero, float scale, float inv, bool four,
+                                           unsigned char* dst_row, int c16) {
+    float x[8], r[8];
     unpack<T>(raw, x);
-    uint32_t code[8];
-    encode8(x, zero, scale, four ? 15.f : 255.f, code);
+    encode8(x, zero, scale, inv, r);
     if (four) {
-        uint32_t w = 0;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) w |= code[e] << (4 * e);
-        *reinterpret_cast<uint32_t*>(dst_row + 4 * c16) = w;
+        // four nibbles make an integer below 65536: exact in float
+        const float h0 = fmaf(r[3], 4096.f, fmaf(r[2], 256.f, fmaf(r[1], 16.f, r[0])));
+        const float h1 = fmaf(r[7], 4096.f, fmaf(r[6], 256.f, fmaf(r[5], 16.f, r[4])));
+        *reinterpret_cast<uint32_t*>(dst_row + 4 * c16) = (uint32_t)h0 | ((uint32_t)h1 << 16);
     } else {
-        uint2 w;
-        w.x = code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);
-        w.y = code[4] | (code[5] << 8) | (code[6] << 16) | (code[7] << 24);
+        uint2 w = make_uint2(0u, 0u);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            w.x = __builtin_amdgcn_cvt_pk_u8_f32(r[e], e, w.x);
+            w.y = __builtin_amdgcn_cvt_pk_u8_f32(r[4 + e], e, w.y);
+        }
         *reinterpret_cast<uint2*>(dst_row + 8 * c16) = w;
     }
 }
@@ -174,9 +184,9 @@ __global__ __launch_bounds__(kCmpThreads) void compress_kernel(
     unsigned char* __restrict__ vblob, int c_max, int n_kv_heads, int n_ctx) {
     static_assert(T::kEpl == 8, "16-bit sources only");
     constexpr int ROWB = Row<T>::kRowBytes;
-    __shared__ float red[4][kCmpWaves];
+    __shared__ float red[2][kCmpWaves];
 
-    const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int c = blockIdx.x, h = blockIdx.y >> 1, is_v = blockIdx.y & 1, b = blockIdx.z;
     if (c >= min(max(n_chunks[b], 0), c_max)) return;
     const size_t bh = (size_t)b * n_kv_heads + h;
     const int tid = threadIdx.x, lane = lane_id(), wave = tid / LEOAM_WAVE;
@@ -187,99 +197,74 @@ __global__ __launch_bounds__(kCmpThreads) void compress_kernel(
     QRecord* rec = qmeta + bh * c_max + c;
     const long long byte_off = rec->byte_off;
     const bool four = rec->bits == 4;
-    const char* Kc = K + (bh * (size_t)n_ctx + t0) * ROWB + (size_t)c16 * 16;
-    const char* Vc = V + (bh * (size_t)n_ctx + t0) * ROWB + (size_t)c16 * 16;
-    const bool held = rows <= kCmpHeldRows;
+    const char* src = (is_v ? V : K) + (bh * (size_t)n_ctx + t0) * ROWB + (size_t)c16 * 16;
 
     // ---- min / max of the chunk (a row past the end re-reads the last row) ------------
-    uint4 kr[kCmpHeld], vr[kCmpHeld];
-    float klo = INFINITY, khi = -INFINITY, vlo = INFINITY, vhi = -INFINITY;
-    auto fold = [&](const uint4& a, const uint4& bq) {
+    uint4 held[kCmpHeld];
+    float lo = INFINITY, hi = -INFINITY;
+    auto fold2 = [&](const uint4& a, const uint4& a2) {       // two rows at a time: three-operand min / max
         float x[8], y[8];
         unpack<T>(a, x);
-        unpack<T>(bq, y);
+        unpack<T>(a2, y);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            klo = fminf(klo, x[e]);
-            khi = fmaxf(khi, x[e]);
-            vlo = fminf(vlo, y[e]);
-            vhi = fmaxf(vhi, y[e]);
+            lo = fminf(fminf(lo, x[e]), y[e]);
+            hi = fmaxf(fmaxf(hi, x[e]), y[e]);
         }
     };
+    static_assert(kCmpHeld % 2 == 0, "rows are folded in pairs");
 #pragma unroll
-    for (int j = 0; j < kCmpHeld; ++j) {
-        const int r = min(grp + j * kCmpGroups, rows - 1);
-        kr[j] = load16(Kc, (size_t)r * ROWB);
-        vr[j] = load16(Vc, (size_t)r * ROWB);
-    }
+    for (int j = 0; j < kCmpHeld; ++j) held[j] = load16(src, (size_t)min(grp + j * kCmpGroups, rows - 1) * ROWB);
 #pragma unroll
-    for (int j = 0; j < kCmpHeld; ++j) fold(kr[j], vr[j]);
+    for (int j = 0; j < kCmpHeld; j += 2) fold2(held[j], held[j + 1]);
     for (int r0 = kCmpHeldRows; r0 < rows; r0 += kCmpHeldRows) {
-        uint4 a[kCmpHeld], bq[kCmpHeld];
+        uint4 a[kCmpHeld];
 #pragma unroll
-        for (int j = 0; j < kCmpHeld; ++j) {
-            const int r = min(r0 + grp + j * kCmpGroups, rows - 1);
-            a[j] = load16(Kc, (size_t)r * ROWB);
-            bq[j] = load16(Vc, (size_t)r * ROWB);
-        }
+        for (int j = 0; j < kCmpHeld; ++j) a[j] = load16(src, (size_t)min(r0 + grp + j * kCmpGroups, rows - 1) * ROWB);
 #pragma unroll
-        for (int j = 0; j < kCmpHeld; ++j) fold(a[j], bq[j]);
+        for (int j = 0; j < kCmpHeld; j += 2) fold2(a[j], a[j + 1]);
     }
-    klo = wave_min_f(klo);
-    khi = wave_max_f(khi);
-    vlo = wave_min_f(vlo);
-    vhi = wave_max_f(vhi);
+    lo = wave_min_f(lo);
+    hi = wave_max_f(hi);
     if (lane == 0) {
-        red[0][wave] = klo;
-        red[1][wave] = khi;
-        red[2][wave] = vlo;
-        red[3][wave] = vhi;
+        red[0][wave] = lo;
+        red[1][wave] = hi;
     }
     __syncthreads();
 #pragma unroll
     for (int w = 0; w < kCmpWaves; ++w) {
-        klo = fminf(klo, red[0][w]);
-        khi = fmaxf(khi, red[1][w]);
-        vlo = fminf(vlo, red[2][w]);
-        vhi = fmaxf(vhi, red[3][w]);
+        lo = fminf(lo, red[0][w]);
+        hi = fmaxf(hi, red[1][w]);
     }
     const float levels = four ? 15.f : 255.f;
-    const float scale_k = __fdiv_rn(__fsub_rn(khi, klo), levels), scale_v = __fdiv_rn(__fsub_rn(vhi, vlo), levels);
+    const float scale = __fdiv_rn(__fsub_rn(hi, lo), levels);
+    const float inv = scale > 0.f ? __fdiv_rn(1.0f, scale) : 0.f;
     if (tid == 0) {
-        rec->scale_k = scale_k;
-        rec->zero_k = klo;
-        rec->scale_v = scale_v;
-        rec->zero_v = vlo;
+        if (is_v) {
+            rec->scale_v = scale;
+            rec->zero_v = lo;
+        } else {
+            rec->scale_k = scale;
+            rec->zero_k = lo;
+        }
     }
 
     // ---- codes ---------------------------------------------------------------------------
     const int row_bytes = four ? LEOAM_D / 2 : LEOAM_D;
-    unsigned char* kdst = kblob + byte_off;
-    unsigned char* vdst = vblob + byte_off;
+    unsigned char* dst = (is_v ? vblob : kblob) + byte_off;
 #pragma unroll
     for (int j = 0; j < kCmpHeld; ++j) {
         const int r = grp + j * kCmpGroups;
-        if (r < rows) {
-            encode_row<T>(kr[j], klo, scale_k, four, kdst + (size_t)r * row_bytes, c16);
-            encode_row<T>(vr[j], vlo, scale_v, four, vdst + (size_t)r * row_bytes, c16);
-        }
+        if (r < rows) encode_row<T>(held[j], lo, scale, inv, four, dst + (size_t)r * row_bytes, c16);
     }
-    if (held) return;
     for (int r0 = kCmpHeldRows; r0 < rows; r0 += kCmpHeldRows) {
-        uint4 a[kCmpHeld], bq[kCmpHeld];
+        uint4 a[kCmpHeld];
 #pragma unroll
-        for (int j = 0; j < kCmpHeld; ++j) {
-            const int r = min(r0 + grp + j * kCmpGroups, rows - 1);
-            a[j] = load16(Kc, (size_t)r * ROWB);
-            bq[j] = load16(Vc, (size_t)r * ROWB);
-        }
+        for (int j = 0; j < kCmpHeld; ++j) a[j] = load16(src, (size_t)min(r0 + grp + j * kCmpGroups, rows - 1) * ROWB);
 #pragma unroll
         for (int j = 0; j < kCmpHeld; ++j) {
             const int r = r0 + grp + j * kCmpGroups;
-            if (r < rows) {
-                encode_row<T>(a[j], klo, scale_k, four, kdst + (size_t)r * row_bytes, c16);
-                encode_row<T>(bq[j], vlo, scale_v, four, vdst + (size_t)r * row_bytes, c16);
-            }
+            if (r < rows) encode_row<T>(a[j], lo, scale, inv, four, dst + (size_t)r * row_bytes, c16);
         }
     }
 }
@@ -291,11 +276,11 @@ size_t compressed_bytes_bound(const leoam_shape* s) {
 hipError_t compress_dispatch(const leoam_shape* s, const void* K, const void* V, const int32_t* chunk_off,
                              const int32_t* n_chunks, const uint8_t* four_bit, void* kblob, void* vblob, void* qmeta,
                              long long* total_bytes, hipStream_t stream) {
-    hipLaunchKernelGGL(compress_layout_kernel, dim3(s->batch), dim3(kLayThreads), 0, stream, chunk_off, n_chunks,
+    hipLaunchKernelGGL(compress_layout_kernel, dim3(s->n_kv_heads, s->batch), dim3(kLayThreads), 0, stream, chunk_off, n_chunks,
                        four_bit, (QRecord*)qmeta, total_bytes, s->c_max, s->n_kv_heads, s->batch);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    dim3 grid(s->c_max, s->n_kv_heads, s->batch), block(kCmpThreads);
+    dim3 grid(s->c_max, s->n_kv_heads * 2, s->batch), block(kCmpThreads);      // y: (kv head, K or V)
     if (s->kv_dtype == LEOAM_F16)
         hipLaunchKernelGGL(compress_kernel<F16>, grid, block, 0, stream, (const char*)K, (const char*)V, chunk_off,
                            n_chunks, (QRecord*)qmeta, (unsigned char*)kblob, (unsigned char*)vblob, s->c_max,
