@@ -506,8 +506,8 @@ int orc_chunk_compress(int dtype, int B, int Hkv, int N, int D, const void *K, c
  * Sending D bytes at bandwidth B with a share theta compressed to the ratio delta takes
  * T0 + D (1 - theta + theta delta) / B (T0 = the other evaluation and transmission
  * time); it hides behind the computation Tc plus the decompression of the compressed
- * share, D theta / R for a decompression rate R (the "offline hardware test" gives B
- * and R).  The transmission side falls with theta and the computation side rises, so
+ * share, D theta / R for a decompression rate R (B and R come from a hardware
+ * measurement made beforehand).  The transmission side falls with theta and the computation side rises, so
  * the two meet at most once: theta is that point, kept inside [0, 1] (0: already
  * hidden without compression; 1: not hidden even when everything is compressed). */
 double orc_compression_share(double D, double delta, double B, double T0, double Tc, double R) {
