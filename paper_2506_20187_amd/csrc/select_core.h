@@ -49,11 +49,21 @@ __device__ __forceinline__ uint64_t wave_incl_scan(uint64_t v) {
     return ((uint64_t)hi << 32) | lo;
 }
 
-// exclusive scan over the whole workgroup in lane order; *total gets the sum
+// sum of the 16 per-wave totals in wave_sums (every lane gets it)
+__device__ __forceinline__ uint64_t wave_sums_total(const uint64_t* wave_sums) {
+    const uint64_t s = wave_sums[lane_id() & (kSelWaves - 1)];
+    const uint32_t lo = row16_incl_scan_u32((uint32_t)s), hi = row16_incl_scan_u32((uint32_t)(s >> 32));
+    return ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)hi, kSelWaves - 1) << 32) |
+           (uint32_t)__builtin_amdgcn_readlane((int)lo, kSelWaves - 1);
+}
+
+// exclusive scan over the whole workgroup in lane order; *total gets the sum.  kGuard: a
+// barrier first, for callers that cannot rule out a lane still reading wave_sums.
+template <bool kGuard = true>
 __device__ __forceinline__ uint64_t block_excl_scan(uint64_t v, uint64_t* wave_sums, uint64_t* total) {
     const int lane = lane_id(), wave = threadIdx.x / LEOAM_WAVE;
     const uint64_t incl = wave_incl_scan(v);
-    __syncthreads();                       // wave_sums may still be read from a previous call
+    if (kGuard) __syncthreads();           // wave_sums may still be read from a previous call
     if (lane == LEOAM_WAVE - 1) wave_sums[wave] = incl;
     __syncthreads();
     // second level: lane w of a row holds wave w's sum, a row scan gives the prefixes
@@ -77,6 +87,7 @@ constexpr int kStageStride = kStageItems + 4;
 struct SelectLds {
     uint64_t hist[kBins];
     uint64_t wave_sums[kSelWaves];
+    uint64_t wave_sums2[kSelWaves];     // the final scan's own slots: written while wave_sums may still be read
     uint32_t red_min[kSelWaves], red_max[kSelWaves];
     uint32_t sh_lo, sh_hi, sh_done, sh_nbin, sh_ncand;
     union {
@@ -108,6 +119,10 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
     uint32_t max_cnt = (uint32_t)k_max;
     if (max_chunks > 0 && (uint32_t)max_chunks < max_cnt) max_cnt = (uint32_t)max_chunks;
     const uint32_t max_tok = token_budget > 0 ? (uint32_t)token_budget : 0xffffffffu;
+
+    // (cleared here, published by the first barrier below)
+    if (tid < kBins) L.hist[tid] = 0;
+    if (tid == 0) L.sh_ncand = 0;
 
     // ---- load this lane's chunks -------------------------------------------
     uint32_t key[kIpt];
@@ -193,15 +208,19 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
         }
     }
 
-    // ---- range of keys and grand total -------------------------------------
+    // ---- range of keys and grand total: one barrier publishes the per-wave values ----
     kmin = wave_min_u32(kmin);
     kmaxv = wave_max_u32(kmaxv);
+    {
+        const uint64_t incl = wave_incl_scan(mine);
+        if (lane == LEOAM_WAVE - 1) L.wave_sums[wave] = incl;
+    }
     if (lane == 0) {
         L.red_min[wave] = kmin;
         L.red_max[wave] = kmaxv;
     }
-    uint64_t grand;
-    block_excl_scan(mine, L.wave_sums, &grand);          // contains the barriers that publish red_*
+    __syncthreads();
+    const uint64_t grand = wave_sums_total(L.wave_sums);
     uint32_t lo = row0_min_u32(L.red_min[lane & (kSelWaves - 1)]);
     uint32_t hi = row0_max_u32(L.red_max[lane & (kSelWaves - 1)]);
 
@@ -214,8 +233,7 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
         for (int pass = 0; pass < 5; ++pass) {
             const uint32_t span = hi - lo;
             const int sh = span < kBins ? 0 : (32 - __clz(span)) - 8;   // (span >> sh) < 256
-            for (int i = tid; i < kBins; i += kSelThreads) L.hist[i] = 0;
-            __syncthreads();
+            // (the histogram is all zero here: cleared at the start, and by the walk below after every pass)
 #pragma unroll
             for (int i = 0; i < kIpt; ++i) {
                 if (valid[i] && key[i] >= lo && key[i] <= hi)
@@ -230,6 +248,7 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     hb[k] = L.hist[4 * lane + k];
+                    L.hist[4 * lane + k] = 0;
                     lane_sum += hb[k];
                 }
                 // suffix over lanes: sum of lanes > this lane
@@ -269,7 +288,8 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
             above = L.sh_above;
             const bool done = L.sh_done != 0;
             const uint32_t nbin = L.sh_nbin;
-            __syncthreads();
+            // (no barrier: wave 0 writes these again only after the next pass's barrier, which every
+            // lane reaches after these reads)
             if (nbin <= (uint32_t)kMaxCand) {
                 use_cand = true;
                 break;
@@ -287,9 +307,7 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
     if (!take_all && use_cand) {
         // ---- few chunks left: the running totals of each come from comparing it with
         // all the others; the n*n comparisons are spread over the whole workgroup
-        if (tid == 0) L.sh_ncand = 0;
-        __syncthreads();
-        uint32_t mypos[kIpt];
+        uint32_t mypos[kIpt];                             // (sh_ncand was cleared at the start)
 #pragma unroll
         for (int i = 0; i < kIpt; ++i) {
             mypos[i] = 0xffffffffu;
@@ -346,7 +364,7 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
 #pragma unroll
     for (int i = 0; i < kIpt; ++i)
         if (R.keep[i]) kept_mine += pack_tot(1, R.size[i]);
-    R.kept_before = block_excl_scan(kept_mine, L.wave_sums, &R.kept_total);
+    R.kept_before = block_excl_scan<false>(kept_mine, L.wave_sums2, &R.kept_total);      // (nothing has read these slots yet)
 }
 
 }  // namespace leoam
