@@ -302,6 +302,18 @@ int kv_chunk_compress(const leoam_shape* shape, const void* K, const void* V, co
 size_t leoam_compressed_bytes_bound(const leoam_shape* shape);
 
 /*
+ * Sec. 4.4 (the compressed share) with Sec. 4.2 (chunks ordered by importance): the
+ * paper fixes the size of the share, not which data it holds.  Here a chunk is
+ * tagged 4-bit unless some kv head of its sequence keeps it in the selection
+ * (sel_idx / sel_count as written by chunk_topk_select, e.g. with a token budget of
+ * (1 - theta) * n_ctx):
+ *   four_bit [batch, c_max] bytes   out   1 = 4-bit, 0 = kept chunk or slot >= n_chunks[b]
+ * Ids outside [0, n_chunks[b]) and entries past sel_count are ignored.
+ */
+int chunk_compression_tags(const leoam_shape* shape, const int32_t* n_chunks, const int32_t* sel_idx,
+                           const int32_t* sel_count, uint8_t* four_bit, void* stream);
+
+/*
  * Sec. 4.4: the share theta of a layer's n_bytes transmitted KV bytes that is
  * sent compressed.  Sent at `bandwidth` bytes/s with a share theta compressed
  * to `ratio` (compressed / uncompressed size), the data arrives after

@@ -365,3 +365,21 @@ def compression_share(n_bytes: float, ratio: float, bandwidth: float, t_other: f
     fn = _load().orc_compression_share
     fn.restype = ctypes.c_double
     return float(fn(*(ctypes.c_double(float(x)) for x in (n_bytes, ratio, bandwidth, t_other, t_compute, decompress_rate))))
+
+
+def compression_tags(n_chunks, sel_idx, sel_count, c_max: int) -> np.ndarray:
+    """Sec. 4.4: which chunks form the compressed share, given a selection of the chunks that matter most
+    (Sec. 4.2 order).  A chunk of a sequence is stored 4-bit unless some kv head keeps it: uint8 [B, c_max],
+    1 = 4-bit, 0 for kept chunks and for slots >= n_chunks[b].  Plain loops."""
+    nc, sel, cnt = _i32(n_chunks), _i32(sel_idx), _i32(sel_count)
+    B, Hkv, _ = sel.shape
+    out = np.zeros((B, c_max), dtype=np.uint8)
+    for b in range(B):
+        for c in range(min(int(nc[b]), c_max)):
+            kept = False
+            for h in range(Hkv):
+                for i in range(int(cnt[b, h])):
+                    if int(sel[b, h, i]) == c:
+                        kept = True
+            out[b, c] = 0 if kept else 1
+    return out

@@ -54,6 +54,7 @@ def _load() -> ctypes.CDLL:
     lib.chunk_select_attention_decode.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_float, vp, vp, vp,
                                                   vp, vp, vp, sz, vp]
     lib.kv_chunk_compress.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp]
+    lib.chunk_compression_tags.argtypes = [sp, vp, vp, vp, vp, vp]
     lib.leoam_compressed_bytes_bound.argtypes = [sp]
     lib.leoam_compressed_bytes_bound.restype = sz
     lib.leoam_compression_share.argtypes = [ctypes.c_double] * 6
@@ -69,7 +70,7 @@ def _load() -> ctypes.CDLL:
     lib.leoam_status_string.restype = ctypes.c_char_p
     lib.leoam_version.restype = ctypes.c_int
     for name in ("kv_chunk_abstract_build", "chunk_score", "chunk_topk_select", "sparse_chunk_attention_decode",
-                 "chunk_select_attention_decode", "kv_chunk_abstract_append", "chunk_tree_refine", "kv_chunk_compress", "leoam_workspace_init",
+                 "chunk_select_attention_decode", "kv_chunk_abstract_append", "chunk_tree_refine", "kv_chunk_compress", "chunk_compression_tags", "leoam_workspace_init",
                  "leoam_validate_boundaries", "leoam_copy_probe"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
@@ -80,7 +81,7 @@ _lib = _load()
 EXPORTS = ("kv_chunk_abstract_build", "chunk_score", "chunk_topk_select", "sparse_chunk_attention_decode",
            "chunk_select_attention_decode", "leoam_fused_workspace_bytes", "leoam_workspace_init",
            "kv_chunk_abstract_append", "leoam_tree_evaluations", "chunk_tree_refine", "leoam_tree_workspace_bytes",
-           "kv_chunk_compress", "leoam_compressed_bytes_bound", "leoam_compression_share",
+           "kv_chunk_compress", "chunk_compression_tags", "leoam_compressed_bytes_bound", "leoam_compression_share",
            "leoam_workspace_bytes", "leoam_validate_boundaries", "leoam_copy_probe", "leoam_status_string",
            "leoam_version")
 
@@ -146,6 +147,11 @@ def kv_chunk_compress(shape: Shape, K, V, chunk_off, n_chunks, four_bit, kblob, 
     _check(_lib.kv_chunk_compress(ctypes.byref(shape), _p(K), _p(V), _p(chunk_off), _p(n_chunks), _p(four_bit), _p(kblob),
                                   _p(vblob), kblob.numel() * kblob.element_size(), _p(qmeta), _p(total_bytes),
                                   _stream(stream)), "kv_chunk_compress")
+
+
+def chunk_compression_tags(shape: Shape, n_chunks, sel_idx, sel_count, four_bit, stream=None) -> None:
+    _check(_lib.chunk_compression_tags(ctypes.byref(shape), _p(n_chunks), _p(sel_idx), _p(sel_count), _p(four_bit),
+                                       _stream(stream)), "chunk_compression_tags")
 
 
 def leoam_compressed_bytes_bound(shape: Shape) -> int:

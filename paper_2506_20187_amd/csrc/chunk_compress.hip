@@ -269,6 +269,41 @@ __global__ __launch_bounds__(kCmpThreads) void compress_kernel(
     }
 }
 
+// ---- which chunks form the compressed share --------------------------------------------
+// Sec. 4.4 fixes how large the compressed share is, not which data it holds.  Here a chunk is
+// stored 4-bit unless some kv head of its sequence keeps it in the given selection (Sec. 4.2
+// order): one workgroup per sequence marks the kept chunks in an LDS byte map and writes the
+// row out.
+constexpr int kTagThreads = 1024;
+constexpr int kTagMax = 16384;      // c_max limit of the library
+
+__global__ __launch_bounds__(kTagThreads) void compression_tags_kernel(
+    const int32_t* __restrict__ n_chunks, const int32_t* __restrict__ sel_idx, const int32_t* __restrict__ sel_count,
+    uint8_t* __restrict__ four_bit, int c_max, int k_max, int n_kv_heads) {
+    __shared__ uint8_t tag[kTagMax];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int n = min(max(n_chunks[b], 0), c_max);
+    for (int c = tid; c < c_max; c += kTagThreads) tag[c] = c < n ? 1 : 0;
+    __syncthreads();
+    for (int h = 0; h < n_kv_heads; ++h) {
+        const size_t bh = (size_t)b * n_kv_heads + h;
+        const int cnt = min(max(sel_count[bh], 0), k_max);
+        for (int i = tid; i < cnt; i += kTagThreads) {
+            const int id = sel_idx[bh * k_max + i];
+            if (id >= 0 && id < n) tag[id] = 0;         // several lanes may clear the same byte
+        }
+    }
+    __syncthreads();
+    for (int c = tid; c < c_max; c += kTagThreads) four_bit[(size_t)b * c_max + c] = tag[c];
+}
+
+hipError_t compression_tags_dispatch(const leoam_shape* s, const int32_t* n_chunks, const int32_t* sel_idx,
+                                     const int32_t* sel_count, uint8_t* four_bit, hipStream_t stream) {
+    hipLaunchKernelGGL(compression_tags_kernel, dim3(s->batch), dim3(kTagThreads), 0, stream, n_chunks, sel_idx,
+                       sel_count, four_bit, s->c_max, s->k_max, s->n_kv_heads);
+    return hipGetLastError();
+}
+
 size_t compressed_bytes_bound(const leoam_shape* s) {
     return (size_t)s->batch * s->n_kv_heads * (size_t)s->n_ctx * LEOAM_D;        // every chunk 8-bit
 }

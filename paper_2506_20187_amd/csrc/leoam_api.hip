@@ -29,6 +29,7 @@ size_t tree_workspace_bytes(const leoam_shape*, int);
 hipError_t tree_refine_dispatch(const leoam_shape*, const void*, const void*, const void*, int, int, int, int, int32_t*,
                                 float*, int32_t*, int32_t*, int32_t*, void*, hipStream_t);
 size_t compressed_bytes_bound(const leoam_shape*);
+hipError_t compression_tags_dispatch(const leoam_shape*, const int32_t*, const int32_t*, const int32_t*, uint8_t*, hipStream_t);
 hipError_t compress_dispatch(const leoam_shape*, const void*, const void*, const int32_t*, const int32_t*, const uint8_t*,
                              void*, void*, void*, long long*, hipStream_t);
 hipError_t abstract_append_dispatch(const leoam_shape*, const void*, int32_t*, int32_t*, int, void*, int32_t*, hipStream_t);
@@ -248,6 +249,14 @@ int kv_chunk_compress(const leoam_shape* shape, const void* K, const void* V, co
     if (blob_bytes < compressed_bytes_bound(shape)) return LEOAM_E_WORKSPACE;
     return from_hip(compress_dispatch(shape, K, V, chunk_off, n_chunks, four_bit, kblob, vblob, qmeta,
                                       (long long*)total_bytes, (hipStream_t)stream));
+}
+
+int chunk_compression_tags(const leoam_shape* shape, const int32_t* n_chunks, const int32_t* sel_idx,
+                           const int32_t* sel_count, uint8_t* four_bit, void* stream) {
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!n_chunks || !sel_idx || !sel_count || !four_bit) return LEOAM_E_INVALID_ARG;
+    return from_hip(compression_tags_dispatch(shape, n_chunks, sel_idx, sel_count, four_bit, (hipStream_t)stream));
 }
 
 double leoam_compression_share(double n_bytes, double ratio, double bandwidth, double t_other, double t_compute,

@@ -184,3 +184,51 @@ def test_compress_error_codes(L):
     L.kv_chunk_compress(shape, K, K, off, nc, fb, ok, ok, qm)       # all-zero cache: scale 0, codes 0
     torch.cuda.synchronize()
     assert not ok.any() and (qm[..., 2] == 8).all() and not qm[..., 3:].any()
+
+
+def test_compression_tags_exact_and_policy_loop(L, oracle):
+    """chunk_compression_tags against the oracle on ragged selections, then the whole policy loop on the GPU:
+    theta from the latency condition -> token budget (1 - theta) N -> selection by score -> tags -> compressed
+    store, every step equal to the oracle's."""
+    rng = np.random.default_rng(17)
+    g = torch.Generator().manual_seed(17)
+    B, Hkv, G, N = 3, 2, 4, 4096
+    offs = [gen.make_boundaries(N, rng, sizes=(8, 16, 32, 64)) for _ in range(B)]
+    packed, counts, c_max = gen.pack_boundaries(offs, N)
+    shape = L.make_shape(B, Hkv * G, Hkv, 128, N, c_max, c_max, torch.float16)
+    d_off, d_nc = torch.from_numpy(packed).cuda(), torch.from_numpy(counts).cuda()
+    # (a) hand-made selections: empty rows, everything, duplicates across heads, ids out of range, stale tail entries
+    sel = np.full((B, Hkv, c_max), -1, dtype=np.int32)
+    cnt = np.zeros((B, Hkv), dtype=np.int32)
+    sel[0, 0, :counts[0]] = np.arange(counts[0]); cnt[0, 0] = counts[0]
+    sel[1, 0, :5] = [0, 3, 4, c_max + 7, -2]; cnt[1, 0] = 5
+    sel[1, 1, :6] = [3, 9, 9, 11, 2, 1]; cnt[1, 1] = 4                  # entries 4, 5 are stale
+    tags = torch.full((B, c_max), 9, dtype=torch.uint8, device="cuda")
+    L.chunk_compression_tags(shape, d_nc, torch.from_numpy(sel).cuda(), torch.from_numpy(cnt).cuda(), tags)
+    torch.cuda.synchronize()
+    assert np.array_equal(tags.cpu().numpy(), oracle.compression_tags(counts, sel, cnt, c_max))
+    # (b) the loop
+    theta = L.leoam_compression_share(2.0 * B * Hkv * N * 256, 0.25, 20e9, 0.2e-3, 0.5e-3, 400e9)
+    assert 0 < theta < 1 and abs(theta - oracle.compression_share(2.0 * B * Hkv * N * 256, 0.25, 20e9, 0.2e-3, 0.5e-3, 400e9)) < 1e-15
+    budget = int((1 - theta) * N)
+    K = (torch.randn(B, Hkv, N, 128, generator=g) * 1.5).to(torch.float16)
+    V = torch.randn(B, Hkv, N, 128, generator=g).to(torch.float16)
+    q = torch.randn(B, Hkv * G, 128, generator=g).to(torch.float16)
+    lay = L.DecodeLayer(K.cuda(), V.cuda(), d_off, d_nc, Hkv * G, c_max, 0, budget)
+    lay.build_abstract()
+    lay.step_separate(q.cuda())
+    L.chunk_compression_tags(shape, d_nc, lay.sel_idx, lay.sel_count, tags)
+    torch.cuda.synchronize()
+    ab = oracle.abstract_build(K, packed, counts)
+    ub = oracle.chunk_score(q, np.nan_to_num(ab), counts)
+    osel, ocnt, otok = oracle.topk_select(ub, packed, counts, 0, budget, c_max)
+    assert np.array_equal(lay.sel_idx.cpu().numpy(), osel)
+    want = oracle.compression_tags(counts, osel, ocnt, c_max)
+    got = tags.cpu().numpy()
+    assert np.array_equal(got, want)
+    # every head keeps at most (1 - theta) N tokens, so at least the share theta - (Hkv - 1)(1 - theta) of the tokens is 4-bit
+    sizes = np.diff(packed.astype(np.int64), axis=1)
+    for b in range(B):
+        four_tokens = int((sizes[b, :counts[b]] * got[b, :counts[b]]).sum())
+        assert four_tokens >= N - Hkv * budget
+    check_against_oracle(oracle, gpu_compress(L, K, V, packed, counts, got.astype(bool)), K, V, packed, counts, got.astype(bool))

@@ -206,3 +206,33 @@ def test_compression_share_balances_the_two_sides():
     assert oracle.compression_share(D, delta, B, T0, Tc, 2 * R) > th
     # no gain from compressing (delta = 1): the only effect of theta is the decompression time -> stays hidden iff it was
     assert oracle.compression_share(D, 1.0, B, T0, 10e-3, R) == 0.0
+
+
+def test_compression_tags_follow_the_selection():
+    # closed forms: everything kept -> nothing 4-bit; nothing kept -> every valid chunk 4-bit; slots past
+    # n_chunks stay 0; with uniform chunks and one head a token budget of (1 - theta) N keeps exactly that share
+    c_max, n = 40, 32
+    nc = np.array([n, n - 5], dtype=np.int32)
+    all_ids = np.tile(np.arange(c_max, dtype=np.int32), (2, 1, 1))
+    full = oracle.compression_tags(nc, all_ids, np.array([[n], [n - 5]], dtype=np.int32), c_max)
+    assert not full.any()
+    none = oracle.compression_tags(nc, all_ids, np.zeros((2, 1), dtype=np.int32), c_max)
+    assert none[0, :n].all() and not none[0, n:].any() and none[1, :n - 5].all() and not none[1, n - 5:].any()
+    # selection by score with a budget: the top (1 - theta) share stays 8-bit
+    rng = np.random.default_rng(2)
+    score = rng.standard_normal((1, 1, c_max)).astype(np.float32)
+    off = (np.arange(c_max + 1, dtype=np.int32) * 16)[None, :]
+    theta = 0.75
+    sel, cnt, tok = oracle.topk_select(score, off, np.array([c_max], dtype=np.int32), 0, int((1 - theta) * c_max * 16), c_max)
+    tags = oracle.compression_tags(np.array([c_max], dtype=np.int32), sel, cnt, c_max)
+    assert tags.sum() == int(theta * c_max)
+    assert set(np.flatnonzero(tags[0] == 0)) == set(np.argsort(-score[0, 0], kind="stable")[: c_max - int(theta * c_max)])
+    # two heads: a chunk kept by either head stays 8-bit (union)
+    sel2 = np.full((1, 2, c_max), -1, dtype=np.int32)
+    sel2[0, 0, :3] = [1, 5, 9]
+    sel2[0, 1, :2] = [5, 30]
+    t2 = oracle.compression_tags(np.array([n], dtype=np.int32), sel2, np.array([[3, 2]], dtype=np.int32), c_max)
+    assert set(np.flatnonzero(t2[0] == 0)) == {1, 5, 9, 30} | set(range(n, c_max))
+    # entries past sel_count are ignored
+    sel2[0, 0, 3] = 7
+    assert np.array_equal(oracle.compression_tags(np.array([n], dtype=np.int32), sel2, np.array([[3, 2]], dtype=np.int32), c_max), t2)
