@@ -31,7 +31,7 @@ struct MergeInLaunch {
     float* out;             // [B, Hq, D]
     float* lse;             // [B, Hq] or nullptr
 };
-constexpr int kInLaunchMergeBatch = 8;
+constexpr int kInLaunchMaxSplits = 16;      // more splits than this: a second kernel merges (measured faster from 32 on)
 
 // Cross-wave combine of the workgroup's online-softmax states into the partial
 // of this split.  xw[w][g] = (acc[D], m, l) of wave w, head g, log2 domain.
@@ -41,9 +41,10 @@ constexpr int kInLaunchMergeBatch = 8;
 // invalidate): the partial is published with agent-scope relaxed atomic stores
 // (write-through), the wave waits for them, one lane takes a ticket from the
 // (b, kv head)'s agent-scope counter, and the workgroup that draws the last
-// ticket reads every partial back with agent-scope atomic loads, folds them in
-// split order (so the result does not depend on which workgroup that is), writes
-// out / lse and resets the counter.  No workgroup waits for another.
+// ticket reads every partial back with agent-scope atomic loads (all of them in
+// one round trip), folds them in split order (so the result does not depend on
+// which workgroup that is), writes out / lse and resets the counter.  No
+// workgroup waits for another.  At most kInLaunchMaxSplits splits.
 template <int G>
 __device__ __forceinline__ void finish_split(float (*xw)[G][kPartStride], float* partial, int b, int h, int split,
                                              int n_splits, int n_kv_heads, const MergeInLaunch mg = {nullptr, nullptr, nullptr}) {
@@ -83,42 +84,62 @@ __device__ __forceinline__ void finish_split(float (*xw)[G][kPartStride], float*
     }
     __syncthreads();
     if (!sh_last) return;
-    for (int i = tid; i < G * LEOAM_D; i += kAttThreads) {
-        const int g = i / LEOAM_D, d = i % LEOAM_D;
-        const float* base = part + (size_t)g * n_splits * kPartStride;
-        float m = -INFINITY, l = 0.f, o = 0.f;
-        for (int s0 = 0; s0 < n_splits; s0 += kInLaunchMergeBatch) {
-            float ms[kInLaunchMergeBatch], ls[kInLaunchMergeBatch], os[kInLaunchMergeBatch];
+    // The (m, l) pairs of every (head, split) go through LDS, one load per lane; the accumulator
+    // columns of up to two (head, channel) pairs per lane are fetched in the same round trip.
+    __shared__ float sh_m[G][kInLaunchMaxSplits], sh_l[G][kInLaunchMaxSplits];
+    auto merge = [&](auto width) {
+        constexpr int kW = decltype(width)::value;            // >= n_splits
+        constexpr int kCols = 2;
+        float os[kCols][kW];
+        auto load_cols = [&](int c0) {          // (a column past the end re-reads the last one)
 #pragma unroll
-            for (int j = 0; j < kInLaunchMergeBatch; ++j) {
-                const float* p = base + (size_t)min(s0 + j, n_splits - 1) * kPartStride;
-                ms[j] = __hip_atomic_load(&p[LEOAM_D], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                ls[j] = __hip_atomic_load(&p[LEOAM_D + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                os[j] = __hip_atomic_load(&p[d], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (s0 + j >= n_splits) {
-                    ms[j] = -INFINITY;
-                    ls[j] = 0.f;
-                    os[j] = 0.f;
+            for (int c = 0; c < kCols; ++c) {
+                const int col = min(c0 + c * kAttThreads, G * LEOAM_D - 1), g = col / LEOAM_D, d = col % LEOAM_D;
+                const float* base = part + (size_t)g * n_splits * kPartStride;
+#pragma unroll
+                for (int j = 0; j < kW; ++j)
+                    os[c][j] = __hip_atomic_load(&base[(size_t)min(j, n_splits - 1) * kPartStride + d], __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
+            }
+        };
+        auto fold_cols = [&](int c0) {
+#pragma unroll
+            for (int c = 0; c < kCols; ++c) {
+                const int col = c0 + c * kAttThreads;
+                if (col >= G * LEOAM_D) continue;
+                const int g = col / LEOAM_D, d = col % LEOAM_D;
+                float m = -INFINITY;
+                for (int j = 0; j < n_splits; ++j) m = fmaxf(m, sh_m[g][j]);
+                float l = 0.f, o = 0.f;
+#pragma unroll
+                for (int j = 0; j < kW; ++j) {
+                    if (j < n_splits) {
+                        const float a = exp2_or_zero(sh_m[g][j], m);
+                        o += a * os[c][j];
+                        l += a * sh_l[g][j];
+                    }
                 }
+                const size_t bj = bh * G + g;
+                mg.out[bj * LEOAM_D + d] = (l > 0.f) ? o / l : 0.f;
+                if (mg.lse && d == 0) mg.lse[bj] = (l > 0.f) ? (m + log2f(l)) * kLn2 : -INFINITY;
             }
-            float mb = m;
-#pragma unroll
-            for (int j = 0; j < kInLaunchMergeBatch; ++j) mb = fmaxf(mb, ms[j]);
-            const float c = exp2_or_zero(m, mb);
-            o *= c;
-            l *= c;
-            m = mb;
-#pragma unroll
-            for (int j = 0; j < kInLaunchMergeBatch; ++j) {
-                const float a = exp2_or_zero(ms[j], m);
-                o += a * os[j];
-                l += a * ls[j];
-            }
+        };
+        load_cols(tid);
+        for (int i = tid; i < G * n_splits; i += kAttThreads) {
+            const int g = i / n_splits, sp = i % n_splits;
+            const float* p = part + ((size_t)g * n_splits + sp) * kPartStride;
+            sh_m[g][sp] = __hip_atomic_load(&p[LEOAM_D], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sh_l[g][sp] = __hip_atomic_load(&p[LEOAM_D + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        const size_t bj = bh * G + g;
-        mg.out[bj * LEOAM_D + d] = (l > 0.f) ? o / l : 0.f;
-        if (mg.lse && d == 0) mg.lse[bj] = (l > 0.f) ? (m + log2f(l)) * kLn2 : -INFINITY;
-    }
+        __syncthreads();       // every lane of the merging workgroup is here
+        fold_cols(tid);
+        for (int c0 = tid + kCols * kAttThreads; c0 < G * LEOAM_D; c0 += kCols * kAttThreads) {
+            load_cols(c0);
+            fold_cols(c0);
+        }
+    };
+    if (n_splits <= 8) merge(std::integral_constant<int, 8>{});
+    else merge(std::integral_constant<int, kInLaunchMaxSplits>{});
 }
 
 

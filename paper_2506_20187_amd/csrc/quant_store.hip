@@ -405,6 +405,336 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_q_kernel(
     finish_split<G>(xw, partial, b, h, split, n_splits, n_kv_heads, mg);
 }
 
+// ---------------------------------------------------------------------------
+// The same attention with q K^T on the matrix cores (group sizes 1, 2, 4).
+//
+// v_mfma_f32_16x16x32_f16: A lane = (token = lane%16, 8 of the 32 channels of the
+// step: 8*(lane/16)..+8), B lane = (head = lane%16, same channels), D lane =
+// (head = lane%16, tokens 4*(lane/16)..+4).  The codes of a lane's 8 channels are
+// one or two dwords; they become the f16 operand without a conversion
+// instruction per element: the bytes (nibbles spread to bytes for a 4-bit row)
+// are paired into the 16-bit halves of a dword by v_perm_b32, or-ed with 0x6400
+// (the f16 1024, whose low mantissa bits then hold the code) and a packed
+// subtraction of 1024 leaves the exact codes.  Both formats produce the channel
+// order (0,2,4,6,1,3,5,7) inside a lane's 8 channels - the per-lane selector of
+// the byte permutation differs, nothing else - and the query operand is stored in
+// that order, so a tile may mix 8-bit and 4-bit tokens.  The logit of a token is
+// scale_k * (q . code) + zero_k * sum(q), applied to the MFMA result.  P V stays
+// on the vector ALU in fp32 as in the dense kernel: v_cvt_f32_ubyte turns codes
+// into floats, the weight is pre-multiplied by scale_v, and zero_v's share is
+// accumulated once per token.
+// ---------------------------------------------------------------------------
+constexpr int kQmBlock = 256;                      // positions a wave maps to chunk slots at a time
+constexpr int kQmGranule = kAttWaves * 16;         // a split is a multiple of this many tokens
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+// two codes (0..255) in the 16-bit halves of p -> the same two values as f16
+__device__ __forceinline__ uint32_t codes_to_f16x2(uint32_t p) {
+    const half2_t h = __builtin_bit_cast(half2_t, p | 0x64006400u) - half2_t{(_Float16)1024.f, (_Float16)1024.f};
+    return __builtin_bit_cast(uint32_t, h);
+}
+
+// one 16-token tile of a wave as loaded: the K dwords of token 16t + c16 (four steps), the V
+// dwords of tokens 16t + 4grp + i, their kept-list slots (-1: no token) and formats
+struct QmTile {
+    uint32_t k0[4], k1[4], v0[4], v1[4];
+    int vslot[4];
+    bool kfour, vfour[4];
+};
+
+template <int G>
+__global__ __launch_bounds__(kAttThreads) void sparse_attention_qm_kernel(
+    const char* __restrict__ q, const unsigned char* __restrict__ kblob, const unsigned char* __restrict__ vblob,
+    const QChunk* __restrict__ qmeta, const int32_t* __restrict__ chunk_off, const int32_t* __restrict__ n_chunks,
+    const int32_t* __restrict__ sel_idx, const int32_t* __restrict__ sel_count, float scale_log2,
+    float* partial, int n_splits, int c_max, int k_max, int n_kv_heads, int n_ctx, MergeInLaunch mg) {
+    static_assert(G <= 4, "one MFMA column per head, four accumulator sets per lane");
+    constexpr int EPL = 8;
+    __shared__ long long ch_off[kQMaxSel];
+    __shared__ float4 ch_par[kQMaxSel];            // scale_k, zero_k, scale_v, zero_v
+    __shared__ int32_t ch_bits[kQMaxSel];
+    __shared__ int32_t prefix[kQMaxSel + 1];
+    __shared__ int32_t pos_slot[kAttWaves][kQmBlock], pos_tin[kAttWaves][kQmBlock];
+    __shared__ float xw[kAttWaves][G][kPartStride];
+    __shared__ int32_t sh_total;
+
+    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid / LEOAM_WAVE;
+    const int grp = lane >> 4, c16 = lane & 15;
+    const size_t bh = (size_t)b * n_kv_heads + h;
+    const int C = min(max(n_chunks[b], 0), c_max);
+    const int cnt = min(min(max(sel_count[bh], 0), k_max), kQMaxSel);
+    const int32_t* off = chunk_off + (size_t)b * (c_max + 1);
+    const int32_t* sel = sel_idx + bh * (size_t)k_max;
+
+    // ---- B operand: the group's queries in the channel order of the code operand; sum_d q per head ----
+    uint4 qb[4];
+    float qsum = 0.f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        qb[s] = make_uint4(0, 0, 0, 0);
+        if (c16 < G) {
+            const size_t qrow = ((size_t)b * n_kv_heads * G + (size_t)h * G + c16) * (LEOAM_D * 2);
+            const uint4 raw = load16(q, qrow + 64 * s + 16 * grp);          // channels 32s + 8grp + 0..7
+            qb[s].x = __builtin_amdgcn_perm(raw.y, raw.x, 0x05040100u);       // (0, 2)
+            qb[s].y = __builtin_amdgcn_perm(raw.w, raw.z, 0x05040100u);       // (4, 6)
+            qb[s].z = __builtin_amdgcn_perm(raw.y, raw.x, 0x07060302u);       // (1, 3)
+            qb[s].w = __builtin_amdgcn_perm(raw.w, raw.z, 0x07060302u);       // (5, 7)
+            float x[EPL];
+            unpack<F16>(raw, x);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) qsum += x[e];
+        }
+    }
+    qsum += shfl_xor_f(qsum, 16);
+    qsum += shfl_xor_f(qsum, 32);
+
+    // ---- kept chunks: records and token prefix ------------------------------------------
+    for (int i = tid; i < cnt; i += kAttThreads) {
+        const int id = sel[i];
+        int sz = 0;
+        QChunk m = {0, 8, 0.f, 0.f, 0.f, 0.f, 0};
+        if (id >= 0 && id < C) {
+            const int t0 = min(max(off[id], 0), n_ctx);
+            sz = min(max(off[id + 1], t0), n_ctx) - t0;
+            m = qmeta[bh * c_max + id];
+        }
+        ch_off[i] = m.byte_off;
+        ch_bits[i] = m.bits;
+        ch_par[i] = make_float4(m.scale_k, m.zero_k, m.scale_v, m.zero_v);
+        prefix[i + 1] = sz;
+    }
+    if (tid == 0) prefix[0] = 0;
+    __syncthreads();
+    if (wave == 0) {
+        const int per = (cnt + LEOAM_WAVE - 1) / LEOAM_WAVE;
+        const int i0 = 1 + lane * per, i1 = min(cnt + 1, i0 + per);
+        int s = 0;
+        for (int i = i0; i < i1; ++i) s += prefix[i];
+        int incl = s;
+#pragma unroll
+        for (int d = 1; d < LEOAM_WAVE; d <<= 1) {
+            const int o = __shfl_up(incl, d, LEOAM_WAVE);
+            if (lane >= d) incl += o;
+        }
+        int run = incl - s;
+        for (int i = i0; i < i1; ++i) {
+            run += prefix[i];
+            prefix[i] = run;
+        }
+        if (lane == LEOAM_WAVE - 1) sh_total = incl;
+    }
+    __syncthreads();
+    const int total = sh_total;
+    int per_split = (total + n_splits - 1) / n_splits;
+    per_split = ((per_split + kQmGranule - 1) / kQmGranule) * kQmGranule;
+    const int r0 = min(total, split * per_split), r1 = min(total, r0 + per_split);
+    const int per_wave = per_split / kAttWaves;
+    const int w0 = min(r1, r0 + wave * per_wave), w1 = min(r1, w0 + per_wave);
+    int32_t* my_slot = pos_slot[wave];
+    int32_t* my_tin = pos_tin[wave];
+
+    // lanes (grp, head) carry the softmax state of `head`; every lane carries the accumulators of
+    // all heads for the V rows of its group and its 8 channels (in the order 0,2,4,6,1,3,5,7)
+    float m_run = -INFINITY, l_run = 0.f;
+    float acc[G][EPL], accz[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        accz[g] = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+    }
+
+    auto fetch = [&](int t, QmTile& kv) {
+        // unconditional loads: a position past the end reads the block's last token and gets weight 0
+        {
+            const int p = 16 * t + c16;
+            const int raw = my_slot[p], slot = raw ^ (raw >> 31);       // a complemented slot: past the end
+            const bool four = ch_bits[slot] == 4;
+            const size_t row = (size_t)ch_off[slot] + (size_t)my_tin[p] * (four ? LEOAM_D / 2 : LEOAM_D) + (four ? 4 : 8) * grp;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const size_t a0 = row + (four ? 16 : 32) * s;
+                kv.k0[s] = *reinterpret_cast<const uint32_t*>(kblob + a0);
+                kv.k1[s] = *reinterpret_cast<const uint32_t*>(kblob + a0 + (four ? 0 : 4));      // 4-bit: the same dword again
+            }
+            kv.kfour = four;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int p = 16 * t + 4 * grp + i;
+            kv.vslot[i] = my_slot[p];
+            const int slot = kv.vslot[i] ^ (kv.vslot[i] >> 31);
+            const bool four = ch_bits[slot] == 4;
+            const size_t a0 = (size_t)ch_off[slot] + (size_t)my_tin[p] * (four ? LEOAM_D / 2 : LEOAM_D) + (four ? 4 : 8) * c16;
+            kv.v0[i] = *reinterpret_cast<const uint32_t*>(vblob + a0);
+            kv.v1[i] = *reinterpret_cast<const uint32_t*>(vblob + a0 + (four ? 0 : 4));
+            kv.vfour[i] = four;
+        }
+    };
+
+    auto consume = [&](const QmTile& kv) {
+        // ---- codes of token c16 -> f16 operand, four steps of 32 channels ----
+        const uint32_t kmask = kv.kfour ? 0x0f0f0f0fu : 0xffffffffu, kshift = kv.kfour ? 4u : 0u;
+        const uint32_t s0 = kv.kfour ? 0x0c010c00u : 0x0c020c00u, s1 = kv.kfour ? 0x0c030c02u : 0x0c060c04u;
+        const uint32_t s2 = kv.kfour ? 0x0c050c04u : 0x0c030c01u, s3 = kv.kfour ? 0x0c070c06u : 0x0c070c05u;
+        f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const uint32_t lo4 = kv.k0[s] & kmask, hi4 = (kv.k1[s] >> kshift) & kmask;
+            uint4 a;
+            a.x = codes_to_f16x2(__builtin_amdgcn_perm(hi4, lo4, s0));
+            a.y = codes_to_f16x2(__builtin_amdgcn_perm(hi4, lo4, s1));
+            a.z = codes_to_f16x2(__builtin_amdgcn_perm(hi4, lo4, s2));
+            a.w = codes_to_f16x2(__builtin_amdgcn_perm(hi4, lo4, s3));
+            sacc = mfma_16x16x32<F16>(a, qb[s], sacc);
+        }
+        // ---- logits of tokens 4grp + r, head c16 ----
+        float z[4], sv[4], zv[4];
+        float mloc = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float4 par = ch_par[kv.vslot[r] ^ (kv.vslot[r] >> 31)];
+            sv[r] = par.z;
+            zv[r] = par.w;
+            z[r] = (kv.vslot[r] >= 0) ? fmaf(par.x, sacc[r], par.y * qsum) * scale_log2 : -INFINITY;
+            mloc = fmaxf(mloc, z[r]);
+        }
+        mloc = fmaxf(mloc, shfl_xor_f(mloc, 16));
+        mloc = fmaxf(mloc, shfl_xor_f(mloc, 32));
+        const float m_new = fmaxf(m_run, mloc);
+        const float corr = exp2_or_zero(m_run, m_new);
+        const bool changed = (c16 < G) && (m_new > m_run);
+        m_run = m_new;
+        float psum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            z[r] = exp2_or_zero(z[r], m_new);     // now the weight
+            psum += z[r];
+        }
+        l_run = l_run * corr + psum;
+        if (__ballot(changed) != 0ull) {
+            static_for<0, G>([&](auto gc) {
+                constexpr int g = decltype(gc)::value;
+                const float cg = row_bcast<g>(corr);
+                accz[g] *= cg;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[g][e] *= cg;
+            });
+        }
+        // ---- P V: the V codes of tokens 4grp + i, this lane's 8 channels ----
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t vmask = kv.vfour[i] ? 0x0f0f0f0fu : 0xffffffffu, vshift = kv.vfour[i] ? 4u : 0u;
+            const uint32_t lo4 = kv.v0[i] & vmask, hi4 = (kv.v1[i] >> vshift) & vmask;
+            // 8-bit rows: (0,1,2,3),(4,5,6,7) -> (0,2,4,6),(1,3,5,7), the order a 4-bit row already has
+            const uint32_t te = __builtin_amdgcn_perm(hi4, lo4, kv.vfour[i] ? 0x03020100u : 0x06040200u);
+            const uint32_t to = __builtin_amdgcn_perm(hi4, lo4, kv.vfour[i] ? 0x07060504u : 0x07050301u);
+            float x[EPL];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {      // (v_cvt_f32_ubyte0..3)
+                x[e] = (float)((te >> (8 * e)) & 0xffu);
+                x[4 + e] = (float)((to >> (8 * e)) & 0xffu);
+            }
+            static_for<0, G>([&](auto gc) {
+                constexpr int g = decltype(gc)::value;
+                const float p = row_bcast<g>(z[i]);
+                accz[g] = fmaf(p, zv[i], accz[g]);
+                const float ps = p * sv[i];
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(ps, x[e], acc[g][e]);
+            });
+        }
+    };
+
+    for (int blk = w0; blk < w1; blk += kQmBlock) {
+        const int nb = min(kQmBlock, w1 - blk);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");      // earlier reads of the tables are done
+        {
+            // a lane maps kQmBlock/64 consecutive positions: one search, then a walk
+            constexpr int PER = kQmBlock / LEOAM_WAVE;
+            const int i0 = lane * PER;
+            int lo = 0;
+            if (i0 < nb) {
+                const int x = blk + i0;
+                int hi = cnt;                  // largest k with prefix[k] <= x
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (prefix[mid] <= x) lo = mid; else hi = mid;
+                }
+            }
+            int last_slot = 0, last_tin = 0;
+#pragma unroll
+            for (int j = 0; j < PER; ++j) {
+                if (i0 + j < nb) {
+                    const int x = blk + i0 + j;
+                    while (prefix[lo + 1] <= x) ++lo;      // ends: prefix[cnt] = total > x
+                    last_slot = lo;
+                    last_tin = x - prefix[lo];
+                    my_slot[i0 + j] = last_slot;
+                    my_tin[i0 + j] = last_tin;
+                }
+            }
+            // positions past the end point at the block's last token, slot stored complemented (< 0):
+            // their loads stay inside the store and their weight is 0
+            const int owner = (nb - 1) / PER;
+            last_slot = __shfl(last_slot, owner, LEOAM_WAVE);
+            last_tin = __shfl(last_tin, owner, LEOAM_WAVE);
+#pragma unroll
+            for (int j = 0; j < PER; ++j) {
+                if (i0 + j >= nb) {
+                    my_slot[i0 + j] = ~last_slot;
+                    my_tin[i0 + j] = last_tin;
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");      // tables visible to the whole wave
+        __builtin_amdgcn_wave_barrier();
+
+        const int n_tiles = (nb + 15) >> 4;
+        QmTile cur, nxt;
+        fetch(0, cur);
+        if (n_tiles == 1) {
+            consume(cur);
+            continue;
+        }
+        for (int t = 0; t < n_tiles; t += 2) {
+            fetch(min(t + 1, n_tiles - 1), nxt);
+            __builtin_amdgcn_sched_barrier(0);       // keep the loads ahead of the tile's arithmetic
+            consume(cur);
+            fetch(min(t + 2, n_tiles - 1), cur);
+            __builtin_amdgcn_sched_barrier(0);
+            if (t + 1 < n_tiles) consume(nxt);
+        }
+    }
+
+    // ---- fold the four lane groups (same m everywhere in the wave); zero_v's share is the same for
+    // every channel ---------------------------------------------------------------------------------
+    l_run += shfl_xor_f(l_run, 16);
+    l_run += shfl_xor_f(l_run, 32);
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+            acc[g][e] += accz[g];
+            acc[g][e] += shfl_xor_f(acc[g][e], 16);
+            acc[g][e] += shfl_xor_f(acc[g][e], 32);
+        }
+    if (grp == 0) {
+        constexpr int kChan[EPL] = {0, 2, 4, 6, 1, 3, 5, 7};
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) xw[wave][g][c16 * EPL + kChan[e]] = acc[g][e];
+        if (c16 < G) {
+            xw[wave][c16][LEOAM_D] = m_run;
+            xw[wave][c16][LEOAM_D + 1] = l_run;
+        }
+    }
+    finish_split<G>(xw, partial, b, h, split, n_splits, n_kv_heads, mg);
+}
+
 int attention_q_max_sel() { return kQMaxSel; }
 
 hipError_t abstract_build_q_dispatch(const leoam_shape* s, const void* kblob, const void* qmeta,
@@ -424,19 +754,24 @@ hipError_t attention_q_dispatch(const leoam_shape* s, const void* q, const void*
                                 const int32_t* sel_count, float scale, float* out, float* lse, float* ws, int n_splits,
                                 int32_t* arrivals, hipStream_t stream) {
     dim3 grid(n_splits, s->n_kv_heads, s->batch);
-    if (n_splits > 2 * kInLaunchMergeBatch) arrivals = nullptr;      // many splits: the merge kernel is faster
+    if (n_splits > kInLaunchMaxSplits) arrivals = nullptr;      // many splits: the merge kernel is faster
     const MergeInLaunch mg = {arrivals, out, lse};
 #define LEOAM_ATTQ(GG)                                                                                                  \
     hipLaunchKernelGGL((sparse_attention_q_kernel<GG>), grid, dim3(kAttThreads), 0, stream, (const char*)q,            \
                        (const unsigned char*)K, (const unsigned char*)V, (const QChunk*)qmeta, chunk_off, n_chunks,     \
                        sel_idx, sel_count, scale * kLog2e, ws, n_splits, s->c_max, s->k_max, s->n_kv_heads, s->n_ctx, mg)
+#define LEOAM_ATTQM(GG)                                                                                                 \
+    hipLaunchKernelGGL((sparse_attention_qm_kernel<GG>), grid, dim3(kAttThreads), 0, stream, (const char*)q,           \
+                       (const unsigned char*)K, (const unsigned char*)V, (const QChunk*)qmeta, chunk_off, n_chunks,     \
+                       sel_idx, sel_count, scale * kLog2e, ws, n_splits, s->c_max, s->k_max, s->n_kv_heads, s->n_ctx, mg)
     switch (s->n_q_heads / s->n_kv_heads) {
-    case 1: LEOAM_ATTQ(1); break;
-    case 2: LEOAM_ATTQ(2); break;
-    case 4: LEOAM_ATTQ(4); break;
+    case 1: LEOAM_ATTQM(1); break;
+    case 2: LEOAM_ATTQM(2); break;
+    case 4: LEOAM_ATTQM(4); break;
     default: LEOAM_ATTQ(8); break;
     }
 #undef LEOAM_ATTQ
+#undef LEOAM_ATTQM
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || arrivals) return e;
     return launch_attention_merge(s, ws, n_splits, out, lse, stream);

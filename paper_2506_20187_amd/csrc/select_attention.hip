@@ -36,7 +36,7 @@ constexpr int kFusedGranule = kFusedWaves * 16;        // a split is a multiple 
 constexpr int kFusedMaxSel = 2048;                     // kept chunks per (b,h) whose ranges fit the LDS tables
 constexpr int kFusedMaxSplits = 64;
 constexpr int kFusedTargetWgs = 256;                   // one workgroup per compute unit
-constexpr int kFusedMergeBatch = 8;
+constexpr int kFusedMergeBatch = 16;
 constexpr size_t kArrivalAlign = 256;
 
 // one 16-token tile of a wave: K operand (4 x 16 B per lane) and V rows (4 x 16 B per lane)
@@ -324,10 +324,13 @@ __global__ __launch_bounds__(kSelThreads) void select_attention_kernel(
         m = -INFINITY;
         l = 0.f;
         o = 0.f;
-        for (int s0 = 0; s0 < n_splits; s0 += kFusedMergeBatch) {
-            float ms[kFusedMergeBatch], ls[kFusedMergeBatch], os[kFusedMergeBatch];
+        // partials are fetched a batch at a time (one memory round trip each); two splits need a
+        // small batch, the many splits of a small batch of sequences a large one
+        auto merge_batch = [&](int s0, auto width) {
+            constexpr int kW = decltype(width)::value;
+            float ms[kW], ls[kW], os[kW];
 #pragma unroll
-            for (int i = 0; i < kFusedMergeBatch; ++i) {
+            for (int i = 0; i < kW; ++i) {
                 const float* p = base + (size_t)min(s0 + i, n_splits - 1) * kPartStride;
                 ms[i] = __hip_atomic_load(&p[LEOAM_D], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 ls[i] = __hip_atomic_load(&p[LEOAM_D + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -340,17 +343,22 @@ __global__ __launch_bounds__(kSelThreads) void select_attention_kernel(
             }
             float mb = m;
 #pragma unroll
-            for (int i = 0; i < kFusedMergeBatch; ++i) mb = fmaxf(mb, ms[i]);
+            for (int i = 0; i < kW; ++i) mb = fmaxf(mb, ms[i]);
             const float c = exp2_or_zero(m, mb);
             o *= c;
             l *= c;
             m = mb;
 #pragma unroll
-            for (int i = 0; i < kFusedMergeBatch; ++i) {
+            for (int i = 0; i < kW; ++i) {
                 const float a = exp2_or_zero(ms[i], m);
                 o += a * os[i];
                 l += a * ls[i];
             }
+        };
+        if (n_splits <= 4) {
+            merge_batch(0, std::integral_constant<int, 4>{});
+        } else {
+            for (int s0 = 0; s0 < n_splits; s0 += kFusedMergeBatch) merge_batch(s0, std::integral_constant<int, kFusedMergeBatch>{});
         }
     }
     if (!owner) return;

@@ -552,8 +552,11 @@ int attention_recommended_splits(const leoam_shape* s, int max_tokens) {
                         : (s->kv_dtype == LEOAM_Q8Q4) ? kAttWaves * 4 * 4 : kMfmaGranule;
     const int by_tokens = (max_tokens + granule - 1) / granule;
     const int units = s->batch * s->n_kv_heads;
-    // about three resident workgroups per compute unit; the quantised kernel holds two
-    const int target = (s->kv_dtype == LEOAM_Q8Q4) ? 512 : 768;
+    // about three resident workgroups per compute unit; the compressed store is latency-bound at the
+    // sizes it is used at (a split pays two dependent table look-ups before its first row arrives), and
+    // one workgroup per compute unit with twice the tokens measured faster than two
+    const int g = s->n_q_heads / s->n_kv_heads;
+    const int target = (s->kv_dtype == LEOAM_Q8Q4) ? (g <= 4 ? 256 : 512) : 768;
     int want = (target + units - 1) / units;
     if (want > by_tokens) want = by_tokens;
     if (want > kAttMaxSplits) want = kAttMaxSplits;
@@ -574,7 +577,7 @@ static hipError_t launch_attention(const leoam_shape* s, const void* q, const vo
                                    int n_splits, int32_t* arrivals, hipStream_t stream) {
     dim3 grid(n_splits, s->n_kv_heads, s->batch);
     // merging in the launch pays while one workgroup can fetch all partials in a round trip or two
-    if (n_splits > 2 * kInLaunchMergeBatch) arrivals = nullptr;
+    if (n_splits > kInLaunchMaxSplits) arrivals = nullptr;
     const MergeInLaunch mg = {arrivals, out, lse};
     const size_t dyn = (size_t)(2 * s->k_max + 1) * sizeof(int32_t);
     float* ws = (float*)workspace;

@@ -93,7 +93,7 @@ def test_quant_abstract_and_attention_random_store(L, oracle, share):
     assert np.abs(lse.cpu().numpy().astype(np.float64)[fin] - want_lse[fin]).max() <= 1e-3
 
 
-@pytest.mark.parametrize("layer,G", [(0, 4), (31, 4), (12, 1)])
+@pytest.mark.parametrize("layer,G", [(0, 4), (31, 4), (12, 1), (5, 2), (20, 8)])
 def test_quant_path_c4_reduced(L, oracle, layer, G):
     qc = gen.make_quant_case("c4", layer=layer, n_ctx=32768 + 77, hq=2 * G, hkv=2, token_budget=2048)
     check_quant_path(L, oracle, qc)
