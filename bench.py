@@ -335,7 +335,7 @@ def main():
                                       "sparse_chunk_attention_decode": round(attn_us, 2),
                                       "chunk_select_attention_decode": round(fused_us, 2)},
         "roofline": {
-            "kernel": "quantised select + attention (topk_select_kernel, sparse_attention_q_kernel, attention_merge_kernel)"
+            "kernel": "select_attention_q_kernel (layers over 8192 chunks: sixteen chunks per lane)"
             if quant else "select_attention_kernel",
             "bound": "hbm",
             "achieved": round(attn_gbs, 1),

@@ -13,17 +13,9 @@
 // Row layout: 8-bit chunks have 128-byte rows, 4-bit chunks 64-byte rows with
 // channel 2i in the low nibble of byte i.  In both kernels 16 lanes share a row
 // and a lane owns 8 consecutive channels (8 or 4 bytes).
-#include "attention_common.h"
+#include "quant_common.h"
 
 namespace leoam {
-
-struct QChunk {             // device image of leoam_qchunk
-    long long byte_off;
-    int bits;
-    float scale_k, zero_k, scale_v, zero_v;
-    int reserved;
-};
-static_assert(sizeof(QChunk) == sizeof(leoam_qchunk), "record layout");
 
 // the 8 codes of this lane's channels [8*c16, 8*c16+8) of the row at `row`
 __device__ __forceinline__ void load_codes(const unsigned char* row, int bits, int c16, float* x) {
@@ -427,22 +419,6 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_q_kernel(
 constexpr int kQmBlock = 256;                      // positions a wave maps to chunk slots at a time
 constexpr int kQmGranule = kAttWaves * 16;         // a split is a multiple of this many tokens
 
-typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
-
-// two codes (0..255) in the 16-bit halves of p -> the same two values as f16
-__device__ __forceinline__ uint32_t codes_to_f16x2(uint32_t p) {
-    const half2_t h = __builtin_bit_cast(half2_t, p | 0x64006400u) - half2_t{(_Float16)1024.f, (_Float16)1024.f};
-    return __builtin_bit_cast(uint32_t, h);
-}
-
-// one 16-token tile of a wave as loaded: the K dwords of token 16t + c16 (four steps), the V
-// dwords of tokens 16t + 4grp + i, their kept-list slots (-1: no token) and formats
-struct QmTile {
-    uint32_t k0[4], k1[4], v0[4], v1[4];
-    int vslot[4];
-    bool kfour, vfour[4];
-};
-
 template <int G>
 __global__ __launch_bounds__(kAttThreads) void sparse_attention_qm_kernel(
     const char* __restrict__ q, const unsigned char* __restrict__ kblob, const unsigned char* __restrict__ vblob,
@@ -477,10 +453,7 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_qm_kernel(
         if (c16 < G) {
             const size_t qrow = ((size_t)b * n_kv_heads * G + (size_t)h * G + c16) * (LEOAM_D * 2);
             const uint4 raw = load16(q, qrow + 64 * s + 16 * grp);          // channels 32s + 8grp + 0..7
-            qb[s].x = __builtin_amdgcn_perm(raw.y, raw.x, 0x05040100u);       // (0, 2)
-            qb[s].y = __builtin_amdgcn_perm(raw.w, raw.z, 0x05040100u);       // (4, 6)
-            qb[s].z = __builtin_amdgcn_perm(raw.y, raw.x, 0x07060302u);       // (1, 3)
-            qb[s].w = __builtin_amdgcn_perm(raw.w, raw.z, 0x07060302u);       // (5, 7)
+            qb[s] = query_operand(raw);
             float x[EPL];
             unpack<F16>(raw, x);
 #pragma unroll
@@ -575,21 +548,7 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_qm_kernel(
     };
 
     auto consume = [&](const QmTile& kv) {
-        // ---- codes of token c16 -> f16 operand, four steps of 32 channels ----
-        const uint32_t kmask = kv.kfour ? 0x0f0f0f0fu : 0xffffffffu, kshift = kv.kfour ? 4u : 0u;
-        const uint32_t s0 = kv.kfour ? 0x0c010c00u : 0x0c020c00u, s1 = kv.kfour ? 0x0c030c02u : 0x0c060c04u;
-        const uint32_t s2 = kv.kfour ? 0x0c050c04u : 0x0c030c01u, s3 = kv.kfour ? 0x0c070c06u : 0x0c070c05u;
-        f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const uint32_t lo4 = kv.k0[s] & kmask, hi4 = (kv.k1[s] >> kshift) & kmask;
-            uint4 a;
-            a.x = codes_to_f16x2(__builtin_amdgcn_perm(hi4, lo4, s0));
-            a.y = codes_to_f16x2(__builtin_amdgcn_perm(hi4, lo4, s1));
-            a.z = codes_to_f16x2(__builtin_amdgcn_perm(hi4, lo4, s2));
-            a.w = codes_to_f16x2(__builtin_amdgcn_perm(hi4, lo4, s3));
-            sacc = mfma_16x16x32<F16>(a, qb[s], sacc);
-        }
+        const f32x4_t sacc = code_logits(kv, [&](int s) { return qb[s]; });
         // ---- logits of tokens 4grp + r, head c16 ----
         float z[4], sv[4], zv[4];
         float mloc = -INFINITY;
@@ -626,17 +585,8 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_qm_kernel(
         // ---- P V: the V codes of tokens 4grp + i, this lane's 8 channels ----
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const uint32_t vmask = kv.vfour[i] ? 0x0f0f0f0fu : 0xffffffffu, vshift = kv.vfour[i] ? 4u : 0u;
-            const uint32_t lo4 = kv.v0[i] & vmask, hi4 = (kv.v1[i] >> vshift) & vmask;
-            // 8-bit rows: (0,1,2,3),(4,5,6,7) -> (0,2,4,6),(1,3,5,7), the order a 4-bit row already has
-            const uint32_t te = __builtin_amdgcn_perm(hi4, lo4, kv.vfour[i] ? 0x03020100u : 0x06040200u);
-            const uint32_t to = __builtin_amdgcn_perm(hi4, lo4, kv.vfour[i] ? 0x07060504u : 0x07050301u);
             float x[EPL];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {      // (v_cvt_f32_ubyte0..3)
-                x[e] = (float)((te >> (8 * e)) & 0xffu);
-                x[4 + e] = (float)((to >> (8 * e)) & 0xffu);
-            }
+            value_codes(kv.v0[i], kv.v1[i], kv.vfour[i], x);
             static_for<0, G>([&](auto gc) {
                 constexpr int g = decltype(gc)::value;
                 const float p = row_bcast<g>(z[i]);
@@ -722,11 +672,10 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_qm_kernel(
             acc[g][e] += shfl_xor_f(acc[g][e], 32);
         }
     if (grp == 0) {
-        constexpr int kChan[EPL] = {0, 2, 4, 6, 1, 3, 5, 7};
 #pragma unroll
         for (int g = 0; g < G; ++g)
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) xw[wave][g][c16 * EPL + kChan[e]] = acc[g][e];
+            for (int e = 0; e < EPL; ++e) xw[wave][g][c16 * EPL + code_channel(e)] = acc[g][e];
         if (c16 < G) {
             xw[wave][c16][LEOAM_D] = m_run;
             xw[wave][c16][LEOAM_D + 1] = l_run;

@@ -25,18 +25,15 @@
 // (as in sparse_attention.hip); P V in fp32 on the vector ALU.  With sixteen
 // waves per workgroup a wave has 128 registers: two K/V tiles in flight and the
 // accumulators; the queries (the matrix core's B operand) stay in LDS.
-#include "attention_common.h"
-#include "select_core.h"
+#include "fused_tail.h"
 
 namespace leoam {
 
-constexpr int kFusedWaves = kSelWaves;                 // 16
 constexpr int kFusedBlock = 128;                       // tokens a wave maps to rows at a time
 constexpr int kFusedGranule = kFusedWaves * 16;        // a split is a multiple of this many tokens
 constexpr int kFusedMaxSel = 2048;                     // kept chunks per (b,h) whose ranges fit the LDS tables
 constexpr int kFusedMaxSplits = 64;
 constexpr int kFusedTargetWgs = 256;                   // one workgroup per compute unit
-constexpr int kFusedMergeBatch = 16;
 constexpr size_t kArrivalAlign = 256;
 
 // one 16-token tile of a wave: K operand (4 x 16 B per lane) and V rows (4 x 16 B per lane)
@@ -285,85 +282,7 @@ __global__ __launch_bounds__(kSelThreads) void select_attention_kernel(
     }
     __syncthreads();
 
-    // ---- fold the waves: lane (g, d) gets the split's (m, l, o[d]) ----------------
-    const int g = tid >> 7, d = tid & (LEOAM_D - 1);
-    const bool owner = tid < G * LEOAM_D;
-    float m = -INFINITY, l = 0.f, o = 0.f;
-    if (owner) {
-#pragma unroll
-        for (int w = 0; w < kFusedWaves; ++w) m = fmaxf(m, ph.xw[w][g][LEOAM_D]);
-#pragma unroll
-        for (int w = 0; w < kFusedWaves; ++w) {
-            const float a = exp2_or_zero(ph.xw[w][g][LEOAM_D], m);
-            l += a * ph.xw[w][g][LEOAM_D + 1];
-            o += a * ph.xw[w][g][d];
-        }
-    }
-    const size_t bj = bh * G + g;
-    if (n_splits > 1) {
-        // publish the partial, take a ticket; the last workgroup to arrive merges
-        float* mine = partial + (bj * (size_t)n_splits + split) * kPartStride;
-        if (owner) {
-            __hip_atomic_store(&mine[d], o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (d == 0) {
-                __hip_atomic_store(&mine[LEOAM_D], m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(&mine[LEOAM_D + 1], l, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wave's stores have been acknowledged
-        __syncthreads();
-        if (tid == 0) {
-            const int ticket = __hip_atomic_fetch_add(&arrivals[bh], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const int is_last = ticket == n_splits - 1;
-            if (is_last) __hip_atomic_store(&arrivals[bh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            sh_last = is_last;
-        }
-        __syncthreads();
-        if (!sh_last || !owner) return;
-        const float* base = partial + bj * (size_t)n_splits * kPartStride;
-        m = -INFINITY;
-        l = 0.f;
-        o = 0.f;
-        // partials are fetched a batch at a time (one memory round trip each); two splits need a
-        // small batch, the many splits of a small batch of sequences a large one
-        auto merge_batch = [&](int s0, auto width) {
-            constexpr int kW = decltype(width)::value;
-            float ms[kW], ls[kW], os[kW];
-#pragma unroll
-            for (int i = 0; i < kW; ++i) {
-                const float* p = base + (size_t)min(s0 + i, n_splits - 1) * kPartStride;
-                ms[i] = __hip_atomic_load(&p[LEOAM_D], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                ls[i] = __hip_atomic_load(&p[LEOAM_D + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                os[i] = __hip_atomic_load(&p[d], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (s0 + i >= n_splits) {
-                    ms[i] = -INFINITY;
-                    ls[i] = 0.f;
-                    os[i] = 0.f;
-                }
-            }
-            float mb = m;
-#pragma unroll
-            for (int i = 0; i < kW; ++i) mb = fmaxf(mb, ms[i]);
-            const float c = exp2_or_zero(m, mb);
-            o *= c;
-            l *= c;
-            m = mb;
-#pragma unroll
-            for (int i = 0; i < kW; ++i) {
-                const float a = exp2_or_zero(ms[i], m);
-                o += a * os[i];
-                l += a * ls[i];
-            }
-        };
-        if (n_splits <= 4) {
-            merge_batch(0, std::integral_constant<int, 4>{});
-        } else {
-            for (int s0 = 0; s0 < n_splits; s0 += kFusedMergeBatch) merge_batch(s0, std::integral_constant<int, kFusedMergeBatch>{});
-        }
-    }
-    if (!owner) return;
-    out[bj * LEOAM_D + d] = (l > 0.f) ? o / l : 0.f;
-    if (lse && d == 0) lse[bj] = (l > 0.f) ? (m + log2f(l)) * kLn2 : -INFINITY;
+    fused_tail<G>(ph.xw, sh_last, partial, arrivals, out, lse, bh, split, n_splits);
 }
 
 // zero fill (arrival counters of a fresh workspace)
@@ -388,6 +307,12 @@ hipError_t attention_dispatch(const leoam_shape*, const void*, const void*, cons
                               int32_t*, hipStream_t);
 size_t attention_workspace_bytes(const leoam_shape*, int);
 size_t attention_min_workspace_bytes(const leoam_shape*);
+
+bool select_attention_q_is_fused(const leoam_shape*);
+int fused_q_recommended_splits(const leoam_shape*, int);
+hipError_t select_attention_q_dispatch(const leoam_shape*, const float*, const void*, const void*, const void*, const void*,
+                                       const int32_t*, const int32_t*, int, int, float, int32_t*, int32_t*, int32_t*,
+                                       float*, float*, float*, int32_t*, int, hipStream_t);
 
 static inline size_t arrival_bytes(const leoam_shape* s) {
     const size_t n = (size_t)s->batch * s->n_kv_heads * sizeof(int32_t);
@@ -423,11 +348,15 @@ size_t select_attention_workspace_bytes(const leoam_shape* s, int max_tokens) {
         const size_t f = fused_part_bytes_per_split(s) * (size_t)fused_recommended_splits(s, max_tokens);
         if (f > body) body = f;
     }
+    if (select_attention_q_is_fused(s)) {
+        const size_t f = fused_part_bytes_per_split(s) * (size_t)fused_q_recommended_splits(s, max_tokens);
+        if (f > body) body = f;
+    }
     return arrival_bytes(s) + body;
 }
 
 size_t select_attention_min_workspace_bytes(const leoam_shape* s) {
-    return arrival_bytes(s) + (select_attention_is_fused(s) ? 0 : attention_min_workspace_bytes(s));
+    return arrival_bytes(s) + ((select_attention_is_fused(s) || select_attention_q_is_fused(s)) ? 0 : attention_min_workspace_bytes(s));
 }
 
 template <typename T, int G>
@@ -473,6 +402,16 @@ hipError_t select_attention_dispatch(const leoam_shape* s, const float* score, c
     const size_t head = arrival_bytes(s);
     char* body = (char*)workspace + head;
     const size_t body_bytes = workspace_bytes - head;
+    if (select_attention_q_is_fused(s)) {
+        // the compressed store's one-launch kernel (select_attention_q.hip)
+        size_t n = body_bytes / fused_part_bytes_per_split(s);
+        const size_t cap = (size_t)fused_q_recommended_splits(s, token_budget > 0 ? token_budget : s->n_ctx);
+        if (n > cap) n = cap;
+        if (n < 1) n = 1;
+        return select_attention_q_dispatch(s, score, q, K, V, qmeta, chunk_off, n_chunks, max_chunks, token_budget, scale,
+                                           sel_idx, sel_count, sel_tokens, out, lse, (float*)body, (int32_t*)workspace,
+                                           (int)n, stream);
+    }
     if (!select_attention_is_fused(s)) {
         hipError_t e = topk_select_dispatch(s, score, chunk_off, n_chunks, max_chunks, token_budget, sel_idx, sel_count,
                                             sel_tokens, stream);

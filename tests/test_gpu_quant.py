@@ -116,3 +116,37 @@ def test_quant_error_codes(L):
         L.sparse_chunk_attention_decode(shape, t, t, t, t, t, t, t, 1.0, t, None, ws, qmeta=t)
     assert e.value.status == -3
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("n_ctx,G", [(32768 + 77, 4), (32768 + 77, 1), (589824, 4)])
+def test_quant_one_call_equals_separate_calls(L, oracle, n_ctx, G):
+    """The one-launch kernel of the compressed store (selection inside the launch, splits merged by the last
+    workgroup) against the separate select / attention calls and the oracle; the larger context has more than
+    8192 chunks (sixteen chunks per lane in the selection).  The workspace's partials start as garbage, the
+    second call must leave the same bits as the first."""
+    qc = gen.make_quant_case("c4", layer=9, n_ctx=n_ctx, hq=G, hkv=1, token_budget=4096, device="cuda")
+    c = qc.case
+    lay = L.DecodeLayer(qc.kblob, qc.vblob, c.chunk_off, c.n_chunks, c.hq, c.k_max, c.max_chunks, c.token_budget,
+                        qmeta=qc.qmeta, n_kv_heads=c.hkv, n_ctx=c.n_ctx)
+    if n_ctx > 500000:
+        assert lay.shape.c_max > 8192
+    lay.build_abstract()
+    head = 256                                   # arrival counters stay zero, the partials behind them do not matter
+    lay.workspace[head:].fill_(0x7f)
+    lay.step(c.q)
+    torch.cuda.synchronize()
+    one = [t.clone() for t in (lay.sel_idx, lay.sel_count, lay.sel_tokens, lay.out, lay.lse)]
+    assert not lay.workspace[:head].any()        # counters reset by the merging workgroups
+    lay.step(c.q)
+    torch.cuda.synchronize()
+    for a, b in zip(one, (lay.sel_idx, lay.sel_count, lay.sel_tokens, lay.out, lay.lse)):
+        assert torch.equal(a, b)
+    lay.step_separate(c.q)
+    torch.cuda.synchronize()
+    assert torch.equal(one[0], lay.sel_idx) and torch.equal(one[1], lay.sel_count) and torch.equal(one[2], lay.sel_tokens)
+    assert (one[3] - lay.out).abs().max().item() <= 1e-4
+    off, nc = c.chunk_off.cpu(), c.n_chunks.cpu()
+    kb, vb, qm = qc.kblob.cpu(), qc.vblob.cpu(), qc.qmeta.cpu()
+    out, lse = oracle.sparse_attention_q(c.q.cpu(), kb, vb, qm, off, one[0].cpu().numpy(), one[1].cpu().numpy())
+    assert np.abs(one[3].cpu().numpy().astype(np.float64) - out).max() <= TOL
+    assert np.abs(one[4].cpu().numpy().astype(np.float64) - lse).max() <= 1e-3
