@@ -194,6 +194,19 @@ int chunk_score(const leoam_shape* shape, const void* q, const void* abstract, c
                 float* score_ub, float* score_lb, void* stream);
 
 /*
+ * Always-kept chunks.  The paper forces no tokens into the selection; a caller
+ * that wants the first chunks of a sequence (attention sink) or its last chunks
+ * (the most recent tokens, among them the tail chunk that decoding appends to,
+ * Sec. 2.1) kept whatever the query says marks them here: for every kv head the
+ * scores of chunks [0, sink_chunks) and [n_chunks[b] - tail_chunks, n_chunks[b])
+ * become FLT_MAX, which puts them at the front of the Sec. 4.2 order (ties by
+ * index), so the selection keeps them first - as far as they fit the budget.
+ * Counts beyond n_chunks[b] mark every chunk; negative counts are invalid.
+ */
+int chunk_score_pin(const leoam_shape* shape, const int32_t* n_chunks, int32_t sink_chunks, int32_t tail_chunks,
+                    float* score_ub, void* stream);
+
+/*
  * Sec. 4.2 (priority queue ordered by upper bound, read from the front) and
  * Sec. 6.1 (only the most important share of the cache is loaded).  Per (b,h):
  * order chunks by (score descending, chunk index ascending); keep the longest

@@ -383,3 +383,18 @@ def compression_tags(n_chunks, sel_idx, sel_count, c_max: int) -> np.ndarray:
                         kept = True
             out[b, c] = 0 if kept else 1
     return out
+
+
+def score_pin(score, n_chunks, sink_chunks: int, tail_chunks: int) -> np.ndarray:
+    """Always-kept chunks (the paper forces none; Sec. 2.1 decoding appends to the tail chunk): a copy of the
+    score rows [B,Hkv,c_max] with the first `sink_chunks` and the last `tail_chunks` chunks of every sequence
+    set to the largest float, which the Sec. 4.2 order then reads first."""
+    out = np.array(score, dtype=np.float32, copy=True)
+    nc = _i32(n_chunks)
+    big = np.finfo(np.float32).max
+    for b in range(out.shape[0]):
+        n = min(int(nc[b]), out.shape[2])
+        for c in range(n):
+            if c < sink_chunks or c >= n - tail_chunks:
+                out[b, :, c] = big
+    return out

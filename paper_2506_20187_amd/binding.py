@@ -43,6 +43,7 @@ def _load() -> ctypes.CDLL:
     sp = ctypes.POINTER(Shape)
     lib.kv_chunk_abstract_build.argtypes = [sp, vp, vp, vp, vp, vp, vp]
     lib.chunk_score.argtypes = [sp, vp, vp, vp, vp, vp, vp]
+    lib.chunk_score_pin.argtypes = [sp, vp, i32, i32, vp, vp]
     lib.kv_chunk_abstract_append.argtypes = [sp, vp, vp, vp, i32, vp, vp, vp]
     lib.chunk_tree_refine.argtypes = [sp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.leoam_tree_workspace_bytes.argtypes = [sp, i32]
@@ -69,7 +70,7 @@ def _load() -> ctypes.CDLL:
     lib.leoam_status_string.argtypes = [ctypes.c_int]
     lib.leoam_status_string.restype = ctypes.c_char_p
     lib.leoam_version.restype = ctypes.c_int
-    for name in ("kv_chunk_abstract_build", "chunk_score", "chunk_topk_select", "sparse_chunk_attention_decode",
+    for name in ("kv_chunk_abstract_build", "chunk_score", "chunk_score_pin", "chunk_topk_select", "sparse_chunk_attention_decode",
                  "chunk_select_attention_decode", "kv_chunk_abstract_append", "chunk_tree_refine", "kv_chunk_compress", "chunk_compression_tags", "leoam_workspace_init",
                  "leoam_validate_boundaries", "leoam_copy_probe"):
         getattr(lib, name).restype = ctypes.c_int
@@ -78,7 +79,7 @@ def _load() -> ctypes.CDLL:
 
 _lib = _load()
 
-EXPORTS = ("kv_chunk_abstract_build", "chunk_score", "chunk_topk_select", "sparse_chunk_attention_decode",
+EXPORTS = ("kv_chunk_abstract_build", "chunk_score", "chunk_score_pin", "chunk_topk_select", "sparse_chunk_attention_decode",
            "chunk_select_attention_decode", "leoam_fused_workspace_bytes", "leoam_workspace_init",
            "kv_chunk_abstract_append", "leoam_tree_evaluations", "chunk_tree_refine", "leoam_tree_workspace_bytes",
            "kv_chunk_compress", "chunk_compression_tags", "leoam_compressed_bytes_bound", "leoam_compression_share",
@@ -137,6 +138,11 @@ def chunk_tree_refine(shape: Shape, q, K, abstract, chunk_size: int, k_tokens: i
                                   int(max_rounds), int(node_cap), _p(ref_off), _p(ref_score), _p(ref_count),
                                   _p(ref_evals), _p(ref_status), _p(workspace), nbytes, _stream(stream)),
            "chunk_tree_refine")
+
+
+def chunk_score_pin(shape: Shape, n_chunks, sink_chunks: int, tail_chunks: int, score_ub, stream=None) -> None:
+    _check(_lib.chunk_score_pin(ctypes.byref(shape), _p(n_chunks), int(sink_chunks), int(tail_chunks), _p(score_ub),
+                                _stream(stream)), "chunk_score_pin")
 
 
 def kv_chunk_compress(shape: Shape, K, V, chunk_off, n_chunks, four_bit, kblob, vblob, qmeta, total_bytes=None,

@@ -34,6 +34,17 @@ hipError_t compress_dispatch(const leoam_shape*, const void*, const void*, const
                              void*, void*, void*, long long*, hipStream_t);
 hipError_t abstract_append_dispatch(const leoam_shape*, const void*, int32_t*, int32_t*, int, void*, int32_t*, hipStream_t);
 
+// scores of the first `sink` and the last `tail` chunks of every (b, h) row become FLT_MAX
+__global__ void score_pin_kernel(const int32_t* __restrict__ n_chunks, int sink, int tail, float* __restrict__ score,
+                                 int c_max, int n_kv_heads) {
+    const int bh = blockIdx.x, b = bh / n_kv_heads;
+    const int n = min(max(n_chunks[b], 0), c_max);
+    float* row = score + (size_t)bh * c_max;
+    const int head_end = min(sink, n), tail_begin = max(n - min(tail, n), head_end);
+    for (int c = threadIdx.x; c < head_end; c += blockDim.x) row[c] = 3.402823466e+38f;
+    for (int c = tail_begin + threadIdx.x; c < n; c += blockDim.x) row[c] = 3.402823466e+38f;
+}
+
 __global__ void copy_probe_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
         dst[i] = src[i];
@@ -140,6 +151,17 @@ int chunk_score(const leoam_shape* shape, const void* q, const void* abstract, c
     if (rc) return rc;
     if (!q || !abstract || !n_chunks || !score_ub) return LEOAM_E_INVALID_ARG;
     return from_hip(chunk_score_dispatch(shape, q, abstract, n_chunks, score_ub, score_lb, (hipStream_t)stream));
+}
+
+int chunk_score_pin(const leoam_shape* shape, const int32_t* n_chunks, int32_t sink_chunks, int32_t tail_chunks,
+                    float* score_ub, void* stream) {
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!n_chunks || !score_ub || sink_chunks < 0 || tail_chunks < 0) return LEOAM_E_INVALID_ARG;
+    if (sink_chunks == 0 && tail_chunks == 0) return LEOAM_OK;
+    hipLaunchKernelGGL(score_pin_kernel, dim3(shape->batch * shape->n_kv_heads), dim3(256), 0, (hipStream_t)stream,
+                       n_chunks, sink_chunks, tail_chunks, score_ub, shape->c_max, shape->n_kv_heads);
+    return from_hip(hipGetLastError());
 }
 
 int chunk_topk_select(const leoam_shape* shape, const float* score_ub, const int32_t* chunk_off,

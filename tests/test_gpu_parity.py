@@ -587,6 +587,34 @@ def test_tree_refine_feeds_selection_and_attention(L, oracle):
 # ---------------------------------------------------------------------------
 # error paths (host-visible faults are refused before any launch)
 # ---------------------------------------------------------------------------
+@pytest.mark.parametrize("sink,tail", [(0, 0), (1, 1), (4, 2), (10000, 0), (0, 10000)])
+def test_score_pin_exact_and_selection(L, oracle, sink, tail):
+    """chunk_score_pin against the oracle on ragged sequence lengths, and the selection that follows it."""
+    rng = np.random.default_rng(sink * 7 + tail)
+    B, Hkv, c_max, N = 3, 2, 1500, 24000
+    nc = np.array([1500, 700, 3], dtype=np.int32)
+    off = np.zeros((B, c_max + 1), dtype=np.int32)
+    for b in range(B):
+        cuts = np.sort(rng.choice(np.arange(1, N), size=nc[b] - 1, replace=False))
+        off[b, 1:nc[b]] = cuts
+        off[b, nc[b]:] = N
+    score = rng.standard_normal((B, Hkv, c_max)).astype(np.float32)
+    shape = L.make_shape(B, Hkv, Hkv, 128, N, c_max, c_max, torch.float16)
+    d_score, d_nc, d_off = torch.from_numpy(score).cuda(), torch.from_numpy(nc).cuda(), torch.from_numpy(off).cuda()
+    L.chunk_score_pin(shape, d_nc, sink, tail, d_score)
+    torch.cuda.synchronize()
+    want = oracle.score_pin(score, nc, sink, tail)
+    assert np.array_equal(d_score.cpu().numpy(), want)
+    sel = torch.empty(B, Hkv, c_max, dtype=torch.int32, device="cuda")
+    cnt = torch.empty(B, Hkv, dtype=torch.int32, device="cuda")
+    tok = torch.empty_like(cnt)
+    L.chunk_topk_select(shape, d_score, d_off, d_nc, 0, 2048, sel, cnt, tok)
+    torch.cuda.synchronize()
+    osel, ocnt, otok = oracle.topk_select(want, off, nc, 0, 2048, c_max)
+    assert np.array_equal(sel.cpu().numpy(), osel) and np.array_equal(cnt.cpu().numpy(), ocnt)
+    assert np.array_equal(tok.cpu().numpy(), otok)
+
+
 def test_error_codes(L):
     t = torch.zeros(16, device="cuda")
     ok = L.make_shape(1, 8, 8, 128, 64, 4, 4, torch.float32)
