@@ -14,10 +14,13 @@
 // sizes and 4-bit tags into byte offsets: the chunks of a (b,h) follow each
 // other, then the next (b,h); rows are 128 or 64 bytes, so every chunk starts on
 // a multiple of 16 bytes without padding.  The compression kernel gives one
-// workgroup to a (b, h, chunk, tensor): 16 lanes share a token row (16 bytes per
+// workgroup (two waves) to a (b, h, chunk, tensor): 16 lanes share a token row (16 bytes per
 // lane, 8 channels), the workgroup reduces min / max, then encodes and stores
-// 8 (4) bytes per lane, rows contiguous.  The first 64 tokens of a chunk stay in
-// registers between the two steps; the rest is read a second time (from L2).
+// 8 (4) bytes per lane, rows contiguous.  The first 32 tokens of a chunk stay in
+// registers between the two steps (loads are unconditional: a step past the
+// chunk's end re-reads its last row; loading under a condition measured 20 % slower); the rest is read a second time (from L2).
+// 128 lanes per workgroup measured best: twice as many workgroups are in
+// different phases (load, reduce, encode, store) on a compute unit.
 // Streaming work: bound by HBM.
 #include "leoam_dev.h"
 
@@ -117,7 +120,7 @@ __global__ __launch_bounds__(kLayThreads) void compress_layout_kernel(
 }
 
 // ---- compression ---------------------------------------------------------------
-constexpr int kCmpThreads = 256;
+constexpr int kCmpThreads = 128;
 constexpr int kCmpWaves = kCmpThreads / LEOAM_WAVE;
 constexpr int kCmpGroups = kCmpThreads / 16;       // token rows per step
 constexpr int kCmpHeld = 4;                        // rows per lane group kept in registers
