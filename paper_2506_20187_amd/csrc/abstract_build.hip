@@ -4,13 +4,14 @@
 // HBM-bound: every key is read once (2*D*e bytes of abstract written per chunk).
 // One wavefront owns one chunk at a time.  A lane moves 16 bytes of a key row,
 // so a wave-wide load covers 1 KiB = 4 rows (16-bit keys) or 2 rows (fp32) of
-// contiguous memory; the row groups are folded together once per chunk.
+// contiguous memory; eight such loads are in flight per lane, none of them under
+// a condition; the row groups are folded together once per chunk.
 #include "leoam_dev.h"
 
 namespace leoam {
 
 constexpr int kAbsWaves = 4;     // waves (= chunks in flight) per workgroup
-constexpr int kAbsUnroll = 4;    // independent 1 KiB loads per wave iteration
+constexpr int kAbsUnroll = 8;    // independent 1 KiB loads per wave iteration
 
 template <typename T>
 __global__ __launch_bounds__(kAbsWaves* LEOAM_WAVE) void abstract_build_kernel(
@@ -31,39 +32,40 @@ __global__ __launch_bounds__(kAbsWaves* LEOAM_WAVE) void abstract_build_kernel(
     const int rgrp = lane / LPR;                    // which row of a wave-wide load
     const int col_bytes = (lane % LPR) * 16;
 
-    for (int c = blockIdx.x * kAbsWaves + wave; c < C; c += gridDim.x * kAbsWaves) {
-        const int t0 = min(max(off[c], 0), n_ctx);
-        const int t1 = min(max(off[c + 1], t0), n_ctx);
+    // the boundaries of the wave's next chunk are fetched while this one streams
+    const int c_first = blockIdx.x * kAbsWaves + wave, c_step = gridDim.x * kAbsWaves;
+    int o0 = off[min(c_first, c_max)], o1 = off[min(c_first + 1, c_max)];
+    for (int c = c_first; c < C; c += c_step) {
+        const int t0 = min(max(o0, 0), n_ctx);
+        const int t1 = min(max(o1, t0), n_ctx);
+        o0 = off[min(c + c_step, c_max)];
+        o1 = off[min(c + c_step + 1, c_max)];
         float mx[EPL], mn[EPL];
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
             mx[e] = -INFINITY;
             mn[e] = INFINITY;
         }
-        int t = t0 + rgrp;
-        // main loop: kAbsUnroll loads in flight per lane
-        for (; t + (kAbsUnroll - 1) * RPL < t1; t += kAbsUnroll * RPL) {
-            uint4 v[kAbsUnroll];
+        // kAbsUnroll loads in flight per lane, all unconditional: a row past the chunk's end re-reads
+        // its last row (harmless for max / min), so a chunk costs ceil(rows / (kAbsUnroll * RPL))
+        // memory round trips and no load waits on a loop test
+        if (t1 > t0) {
+            for (int t = t0 + rgrp; t < t1; t += kAbsUnroll * RPL) {
+                uint4 v[kAbsUnroll];
 #pragma unroll
-            for (int u = 0; u < kAbsUnroll; ++u) v[u] = load16(Kbh, (size_t)(t + u * RPL) * ROWB + col_bytes);
+                for (int u = 0; u < kAbsUnroll; ++u)
+                    v[u] = load16(Kbh, (size_t)min(t + u * RPL, t1 - 1) * ROWB + col_bytes);
 #pragma unroll
-            for (int u = 0; u < kAbsUnroll; ++u) {
-                float x[EPL];
-                unpack<T>(v[u], x);
+                for (int u = 0; u < kAbsUnroll; u += 2) {
+                    float x[EPL], y[EPL];
+                    unpack<T>(v[u], x);
+                    unpack<T>(v[u + 1], y);
 #pragma unroll
-                for (int e = 0; e < EPL; ++e) {
-                    mx[e] = fmaxf(mx[e], x[e]);
-                    mn[e] = fminf(mn[e], x[e]);
+                    for (int e = 0; e < EPL; ++e) {
+                        mx[e] = fmaxf(fmaxf(mx[e], x[e]), y[e]);
+                        mn[e] = fminf(fminf(mn[e], x[e]), y[e]);
+                    }
                 }
-            }
-        }
-        for (; t < t1; t += RPL) {
-            float x[EPL];
-            unpack<T>(load16(Kbh, (size_t)t * ROWB + col_bytes), x);
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-                mx[e] = fmaxf(mx[e], x[e]);
-                mn[e] = fminf(mn[e], x[e]);
             }
         }
         // fold the row groups (lanes that hold the same columns)
