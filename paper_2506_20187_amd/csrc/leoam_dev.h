@@ -186,5 +186,14 @@ __device__ __forceinline__ float rows_sum4(float a, float b, float c, float d) {
     permlane16_swap(u, w);
     return u + w;
 }
+// The maximum of v over lanes j, j+16, j+32, j+48, in all four (two swaps on the
+// vector ALU instead of two round trips through the LDS crossbar).
+__device__ __forceinline__ float rows_max4(float v) {
+    float a = v, b = v;
+    permlane32_swap(a, b);      // a: lower half everywhere, b: upper half everywhere
+    float u = fmaxf(a, b), w = u;
+    permlane16_swap(u, w);      // u: rows 0,0,2,2; w: rows 1,1,3,3 (rows 0 = 2 and 1 = 3 by now)
+    return fmaxf(u, w);
+}
 
 }  // namespace leoam

@@ -560,8 +560,7 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_qm_kernel(
             z[r] = (kv.vslot[r] >= 0) ? fmaf(par.x, sacc[r], par.y * qsum) * scale_log2 : -INFINITY;
             mloc = fmaxf(mloc, z[r]);
         }
-        mloc = fmaxf(mloc, shfl_xor_f(mloc, 16));
-        mloc = fmaxf(mloc, shfl_xor_f(mloc, 32));
+        mloc = rows_max4(mloc);
         const float m_new = fmaxf(m_run, mloc);
         const float corr = exp2_or_zero(m_run, m_new);
         const bool changed = (c16 < G) && (m_new > m_run);

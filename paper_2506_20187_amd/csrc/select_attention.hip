@@ -173,8 +173,7 @@ __global__ __launch_bounds__(kSelThreads) void select_attention_kernel(
             z[r] = (4 * grp + r < n_valid) ? sacc[r] * scale_log2 : -INFINITY;
             mloc = fmaxf(mloc, z[r]);
         }
-        mloc = fmaxf(mloc, shfl_xor_f(mloc, 16));
-        mloc = fmaxf(mloc, shfl_xor_f(mloc, 32));
+        mloc = rows_max4(mloc);
         const float m_new = fmaxf(m_run, mloc);
         const float corr = exp2_or_zero(m_run, m_new);
         const bool changed = (c16 < G) && (m_new > m_run);
