@@ -31,6 +31,7 @@ namespace leoam {
 constexpr int kScoreWaves = 4;
 constexpr int kRowsPerSet = 16;    // abstract rows per MFMA = 8 chunks
 constexpr int kChunksPerSet = 8;
+constexpr size_t kScoreLdsPerWg = 40 * 1024;    // static + dynamic LDS of a workgroup in large launches
 
 __device__ __forceinline__ double dpp_ror8_d(double v) {
     // value of the lane 8 places away inside the 16-lane row (rotation by 8 is its own inverse)
@@ -152,12 +153,8 @@ __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
                 lb = fmin(lb, real ? ls : INFINITY);
             }
         }
-        ub = fmax(ub, shfl_xor_d(ub, 16));
-        ub = fmax(ub, shfl_xor_d(ub, 32));
-        if (kLower) {
-            lb = fmin(lb, shfl_xor_d(lb, 16));
-            lb = fmin(lb, shfl_xor_d(lb, 32));
-        }
+        ub = rows_extreme4_d<true>(ub);
+        if (kLower) lb = rows_extreme4_d<false>(lb);
         // every lane holds the score of chunk (lane & 7) of this set
         if constexpr (kSingle) {
             const int c = set * kChunksPerSet + lane;
@@ -235,8 +232,13 @@ static hipError_t launch_score(const leoam_shape* s, const void* q, const void* 
     if (gx > gx_max) gx = gx_max;
     gx |= 1;
     dim3 grid(gx, s->n_kv_heads, s->batch), block(kScoreWaves * LEOAM_WAVE);
-#define LEOAM_SCORE(LOWER, SINGLE)                                                                            \
-    hipLaunchKernelGGL((chunk_score_kernel<T, G, LOWER, SINGLE>), grid, block, 0, stream, (const char*)q,      \
+    // Large launches ask for unused dynamic LDS up to 40 KiB per workgroup, which holds a compute
+    // unit to four workgroups: with the seven that registers allow, the requests of more waves
+    // interleave in the memory system and the kernel measured 4 % slower on MI355X (three: 15 % slower).
+    const size_t a_bytes = (size_t)((G + 3) / 4) * 32 * LEOAM_WAVE * sizeof(double) * (lb ? 2 : 1);
+    const size_t lds_pad = (!single && a_bytes < kScoreLdsPerWg) ? kScoreLdsPerWg - a_bytes : 0;
+#define LEOAM_SCORE(LOWER, SINGLE)                                                                              \
+    hipLaunchKernelGGL((chunk_score_kernel<T, G, LOWER, SINGLE>), grid, block, lds_pad, stream, (const char*)q,  \
                        (const char*)abstract, n_chunks, ub, lb, s->c_max, s->n_kv_heads)
     if (lb) {
         if (single) LEOAM_SCORE(true, true); else LEOAM_SCORE(true, false);

@@ -195,5 +195,29 @@ __device__ __forceinline__ float rows_max4(float v) {
     permlane16_swap(u, w);      // u: rows 0,0,2,2; w: rows 1,1,3,3 (rows 0 = 2 and 1 = 3 by now)
     return fmaxf(u, w);
 }
+// The same for doubles: both halves of a double travel through the same swaps.
+__device__ __forceinline__ void permlane32_swap_d(double& a, double& b) {
+    uint64_t ua = __builtin_bit_cast(uint64_t, a), ub = __builtin_bit_cast(uint64_t, b);
+    uint32_t al = (uint32_t)ua, ah = (uint32_t)(ua >> 32), bl = (uint32_t)ub, bh = (uint32_t)(ub >> 32);
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\tv_permlane32_swap_b32 %2, %3\n\ts_nop 1"
+                 : "+v"(al), "+v"(bl), "+v"(ah), "+v"(bh));
+    a = __builtin_bit_cast(double, ((uint64_t)ah << 32) | al);
+    b = __builtin_bit_cast(double, ((uint64_t)bh << 32) | bl);
+}
+__device__ __forceinline__ void permlane16_swap_d(double& a, double& b) {
+    uint64_t ua = __builtin_bit_cast(uint64_t, a), ub = __builtin_bit_cast(uint64_t, b);
+    uint32_t al = (uint32_t)ua, ah = (uint32_t)(ua >> 32), bl = (uint32_t)ub, bh = (uint32_t)(ub >> 32);
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\tv_permlane16_swap_b32 %2, %3\n\ts_nop 1"
+                 : "+v"(al), "+v"(bl), "+v"(ah), "+v"(bh));
+    a = __builtin_bit_cast(double, ((uint64_t)ah << 32) | al);
+    b = __builtin_bit_cast(double, ((uint64_t)bh << 32) | bl);
+}
+template <bool kMax> __device__ __forceinline__ double rows_extreme4_d(double v) {
+    double a = v, b = v;
+    permlane32_swap_d(a, b);
+    double u = kMax ? fmax(a, b) : fmin(a, b), w = u;
+    permlane16_swap_d(u, w);
+    return kMax ? fmax(u, w) : fmin(u, w);
+}
 
 }  // namespace leoam
