@@ -5,7 +5,8 @@
 // One wavefront owns one chunk at a time.  A lane moves 16 bytes of a key row,
 // so a wave-wide load covers 1 KiB = 4 rows (16-bit keys) or 2 rows (fp32) of
 // contiguous memory; eight such loads are in flight per lane, none of them under
-// a condition; the row groups are folded together once per chunk.
+// a condition; the row groups are folded together once per chunk (16-bit keys: by
+// lane swaps on the vector ALU, every lane then stores 4 bytes of the abstract).
 #include "leoam_dev.h"
 
 namespace leoam {
@@ -68,18 +69,31 @@ __global__ __launch_bounds__(kAbsWaves* LEOAM_WAVE) void abstract_build_kernel(
                 }
             }
         }
-        // fold the row groups (lanes that hold the same columns)
+        if constexpr (LPR == 16) {
+            // fold the four row groups on the vector ALU; row group r ends up with the
+            // totals of elements 2r and 2r+1 of its columns and stores those 4 bytes
+            float hi[EPL] = {}, lo[EPL] = {};
+            hi[0] = rows_extreme_quad<true>(mx[0], mx[4], mx[2], mx[6]);
+            hi[1] = rows_extreme_quad<true>(mx[1], mx[5], mx[3], mx[7]);
+            lo[0] = rows_extreme_quad<false>(mn[0], mn[4], mn[2], mn[6]);
+            lo[1] = rows_extreme_quad<false>(mn[1], mn[5], mn[3], mn[7]);
+            char* row = Abh + (size_t)c * 2 * ROWB + col_bytes + 4 * rgrp;
+            *reinterpret_cast<uint32_t*>(row) = pack<T>(hi).x;
+            *reinterpret_cast<uint32_t*>(row + ROWB) = pack<T>(lo).x;
+        } else {
+            // fold the row groups (lanes that hold the same columns)
 #pragma unroll
-        for (int m = LPR; m < LEOAM_WAVE; m <<= 1) {
+            for (int m = LPR; m < LEOAM_WAVE; m <<= 1) {
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-                mx[e] = fmaxf(mx[e], shfl_xor_f(mx[e], m));
-                mn[e] = fminf(mn[e], shfl_xor_f(mn[e], m));
+                for (int e = 0; e < EPL; ++e) {
+                    mx[e] = fmaxf(mx[e], shfl_xor_f(mx[e], m));
+                    mn[e] = fminf(mn[e], shfl_xor_f(mn[e], m));
+                }
             }
+            // row group 0 writes kmax, row group 1 writes kmin
+            if (rgrp == 0) store16(Abh, ((size_t)c * 2 + 0) * ROWB + col_bytes, pack<T>(mx));
+            if (rgrp == 1) store16(Abh, ((size_t)c * 2 + 1) * ROWB + col_bytes, pack<T>(mn));
         }
-        // row group 0 writes kmax, row group 1 writes kmin
-        if (rgrp == 0) store16(Abh, ((size_t)c * 2 + 0) * ROWB + col_bytes, pack<T>(mx));
-        if (rgrp == 1) store16(Abh, ((size_t)c * 2 + 1) * ROWB + col_bytes, pack<T>(mn));
     }
 }
 

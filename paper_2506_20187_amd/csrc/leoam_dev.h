@@ -195,6 +195,16 @@ __device__ __forceinline__ float rows_max4(float v) {
     permlane16_swap(u, w);      // u: rows 0,0,2,2; w: rows 1,1,3,3 (rows 0 = 2 and 1 = 3 by now)
     return fmaxf(u, w);
 }
+// Four values at once: row 0 returns the maximum (minimum) of a over lanes j, j+16, j+32,
+// j+48, row 1 that of c, row 2 that of b, row 3 that of d (three swaps for four folds).
+template <bool kMax> __device__ __forceinline__ float rows_extreme_quad(float a, float b, float c, float d) {
+    permlane32_swap(a, b);
+    float u = kMax ? fmaxf(a, b) : fminf(a, b);
+    permlane32_swap(c, d);
+    float w = kMax ? fmaxf(c, d) : fminf(c, d);
+    permlane16_swap(u, w);
+    return kMax ? fmaxf(u, w) : fminf(u, w);
+}
 // The same for doubles: both halves of a double travel through the same swaps.
 __device__ __forceinline__ void permlane32_swap_d(double& a, double& b) {
     uint64_t ua = __builtin_bit_cast(uint64_t, a), ub = __builtin_bit_cast(uint64_t, b);
