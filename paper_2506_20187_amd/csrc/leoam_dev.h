@@ -222,6 +222,35 @@ __device__ __forceinline__ void permlane16_swap_d(double& a, double& b) {
     a = __builtin_bit_cast(double, ((uint64_t)ah << 32) | al);
     b = __builtin_bit_cast(double, ((uint64_t)bh << 32) | bl);
 }
+// Sum of a 64-bit value over aligned groups of 2^log2_group lanes (wave-uniform
+// log2_group, 0..6); every lane of a group gets the total.  Butterfly steps inside a
+// row on the DPP path, the steps across rows by lane swaps: nothing goes through LDS.
+template <int kCtrl> __device__ __forceinline__ uint64_t dpp_u64(uint64_t v) {
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, kCtrl, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)(v >> 32), kCtrl, 0xf, 0xf, true);
+    return ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo;
+}
+__device__ __forceinline__ uint64_t group_sum_u64(uint64_t v, int log2_group) {
+    if (log2_group > 0) v += dpp_u64<0xB1>(v);
+    if (log2_group > 1) v += dpp_u64<0x4E>(v);
+    if (log2_group > 2) v += dpp_u64<0x141>(v);
+    if (log2_group > 3) v += dpp_u64<0x140>(v);
+    if (log2_group > 4) {
+        // rows 0+1 and 2+3: after the swap a holds rows (0,0,2,2) of v, b rows (1,1,3,3)
+        uint32_t al = (uint32_t)v, ah = (uint32_t)(v >> 32), bl = al, bh = ah;
+        asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\tv_permlane16_swap_b32 %2, %3\n\ts_nop 1"
+                     : "+v"(al), "+v"(bl), "+v"(ah), "+v"(bh));
+        v = (((uint64_t)ah << 32) | al) + (((uint64_t)bh << 32) | bl);
+    }
+    if (log2_group > 5) {
+        uint32_t al = (uint32_t)v, ah = (uint32_t)(v >> 32), bl = al, bh = ah;
+        asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\tv_permlane32_swap_b32 %2, %3\n\ts_nop 1"
+                     : "+v"(al), "+v"(bl), "+v"(ah), "+v"(bh));
+        v = (((uint64_t)ah << 32) | al) + (((uint64_t)bh << 32) | bl);
+    }
+    return v;
+}
+
 template <bool kMax> __device__ __forceinline__ double rows_extreme4_d(double v) {
     double a = v, b = v;
     permlane32_swap_d(a, b);

@@ -253,7 +253,9 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
                 }
                 // suffix over lanes: sum of lanes > this lane
                 uint64_t incl = wave_incl_scan(lane_sum);
-                const uint64_t wave_total = __shfl(incl, LEOAM_WAVE - 1, LEOAM_WAVE);
+                const uint64_t wave_total =
+                    ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(incl >> 32), LEOAM_WAVE - 1) << 32) |
+                    (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)incl, LEOAM_WAVE - 1);
                 uint64_t run = above + (wave_total - incl);        // totals of bins above this lane's bins
                 int first_bad = -1;                                // highest bin whose inclusion breaks the fit
                 uint64_t above_bad = 0, in_bad = 0;
@@ -332,7 +334,7 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
             for (int j = sub; j < n; j += (1 << tshift))
                 if (L.cand_ki[j] >= mine_ki) run += L.cand_tot[j];
         }
-        for (int m = 1; m < (1 << tshift); m <<= 1) run += __shfl_xor(run, m, LEOAM_WAVE);
+        run = group_sum_u64(run, tshift);
         if (cand < n && sub == 0) {
             run += above;
             L.cand_keep[cand] = fits((uint32_t)(run >> 32), (uint32_t)run, max_cnt, max_tok) ? 1u : 0u;
