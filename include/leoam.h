@@ -306,7 +306,9 @@ int leoam_validate_boundaries(const leoam_shape* shape, const int32_t* chunk_off
  *   total_bytes  device int64, nullable                    out  bytes used of each blob
  * blob_bytes must be at least leoam_compressed_bytes_bound() (the size with
  * every chunk 8-bit), else LEOAM_E_WORKSPACE; the bytes past *total_bytes are
- * not written.  Boundaries must tile the context (chunks that do not are skipped).
+ * not written.  Boundaries must tile the context: a chunk whose boundaries do not
+ * lie in [0, n_ctx] in ascending order takes no room and is skipped, and no chunk
+ * is written past blob_bytes whatever the boundaries hold.
  */
 int kv_chunk_compress(const leoam_shape* shape, const void* K, const void* V, const int32_t* chunk_off,
                       const int32_t* n_chunks, const uint8_t* four_bit, void* kblob, void* vblob, size_t blob_bytes,

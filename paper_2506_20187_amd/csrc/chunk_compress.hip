@@ -39,7 +39,7 @@ constexpr int kLayWaves = kLayThreads / LEOAM_WAVE;
 
 // sum of v over the workgroup (every thread gets it); `slots` holds kLayWaves values
 __device__ __forceinline__ unsigned long long layout_block_sum(unsigned long long v, unsigned long long* slots) {
-    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, LEOAM_WAVE);
+    v = group_sum_u64(v, 6);
     __syncthreads();
     if (lane_id() == 0) slots[threadIdx.x / LEOAM_WAVE] = v;
     __syncthreads();
@@ -49,48 +49,59 @@ __device__ __forceinline__ unsigned long long layout_block_sum(unsigned long lon
     return t;
 }
 
-// bytes of chunk c of a sequence in one blob, for one kv head
-__device__ __forceinline__ int chunk_bytes(const int32_t* off, const uint8_t* four, int c) {
-    return (off[c + 1] - off[c]) * (four[c] ? LEOAM_D / 2 : LEOAM_D);
+// bytes of chunk c of a sequence in one blob, for one kv head.  A chunk whose boundaries do
+// not lie in the context in ascending order stores nothing (the compression kernel skips it
+// by the same test).
+__device__ __forceinline__ int chunk_bytes(const int32_t* off, const uint8_t* four, int c, int n_ctx) {
+    const int t0 = off[c], rows = off[c + 1] - t0;
+    if (t0 < 0 || rows <= 0 || rows > n_ctx - t0) return 0;
+    return rows * (four[c] ? LEOAM_D / 2 : LEOAM_D);
 }
 
 __global__ __launch_bounds__(kLayThreads) void compress_layout_kernel(
     const int32_t* __restrict__ chunk_off, const int32_t* __restrict__ n_chunks, const uint8_t* __restrict__ four_bit,
-    QRecord* __restrict__ qmeta, long long* __restrict__ total_bytes, int c_max, int n_kv_heads, int batch) {
+    QRecord* __restrict__ qmeta, long long* __restrict__ total_bytes, int c_max, int n_kv_heads, int batch, int n_ctx) {
     __shared__ unsigned long long slots[kLayWaves];
     __shared__ unsigned long long wave_incl[kLayWaves];
     // one workgroup per (kv head, sequence): each repeats the sequence's sums and writes its head's records
     const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / LEOAM_WAVE;
 
-    // bytes of all the sequences before this one
+    // bytes of all the sequences before this one: a wave per sequence, kLayWaves of them at a time
     unsigned long long before = 0;
-    for (int bb = 0; bb < b; ++bb) {
-        const int32_t* off = chunk_off + (size_t)bb * (c_max + 1);
-        const uint8_t* four = four_bit + (size_t)bb * c_max;
-        const int n = min(max(n_chunks[bb], 0), c_max);
+    for (int b0 = 0; b0 < b; b0 += kLayWaves) {
+        const int bb = b0 + wave;
         unsigned long long part = 0;
-        for (int c = tid; c < n; c += kLayThreads) part += (unsigned long long)chunk_bytes(off, four, c);
-        before += layout_block_sum(part, slots) * (unsigned long long)n_kv_heads;
+        if (bb < b) {
+            const int32_t* off = chunk_off + (size_t)bb * (c_max + 1);
+            const uint8_t* four = four_bit + (size_t)bb * c_max;
+            const int n = min(max(n_chunks[bb], 0), c_max);
+#pragma unroll 4
+            for (int c = lane; c < n; c += LEOAM_WAVE) part += (unsigned long long)chunk_bytes(off, four, c, n_ctx);
+        }
+        part = group_sum_u64(part, 6);
+        __syncthreads();      // the previous round's totals have been read
+        if (lane == 0) slots[wave] = part;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < kLayWaves; ++w) before += slots[w];
     }
+    before *= (unsigned long long)n_kv_heads;
 
     const int32_t* off = chunk_off + (size_t)b * (c_max + 1);
     const uint8_t* four = four_bit + (size_t)b * c_max;
     const int n = min(max(n_chunks[b], 0), c_max);
     // bytes of one head of this sequence
     unsigned long long part = 0;
-    for (int c = tid; c < n; c += kLayThreads) part += (unsigned long long)chunk_bytes(off, four, c);
+    for (int c = tid; c < n; c += kLayThreads) part += (unsigned long long)chunk_bytes(off, four, c, n_ctx);
     const unsigned long long per_head = layout_block_sum(part, slots);
 
     // exclusive scan over the chunks, a tile of 1024 at a time
     unsigned long long carry = 0;
     for (int base = 0; base < c_max; base += kLayThreads) {
         const int c = base + tid;
-        const unsigned long long mine = c < n ? (unsigned long long)chunk_bytes(off, four, c) : 0ull;
-        unsigned long long incl = mine;
-        for (int d = 1; d < LEOAM_WAVE; d <<= 1) {
-            const unsigned long long up = __shfl_up(incl, d, LEOAM_WAVE);
-            if (lane >= d) incl += up;
-        }
+        // (chunks that tile a context sum to less than 2^31 bytes per head, so a wave's scan stays in 32 bits)
+        const unsigned long long mine = c < n ? (unsigned long long)chunk_bytes(off, four, c, n_ctx) : 0ull;
+        const unsigned long long incl = wave_incl_scan_u32((uint32_t)mine);
         __syncthreads();
         if (lane == LEOAM_WAVE - 1) wave_incl[wave] = incl;
         __syncthreads();
@@ -125,15 +136,6 @@ constexpr int kCmpWaves = kCmpThreads / LEOAM_WAVE;
 constexpr int kCmpGroups = kCmpThreads / 16;       // token rows per step
 constexpr int kCmpHeld = 4;                        // rows per lane group kept in registers
 constexpr int kCmpHeldRows = kCmpGroups * kCmpHeld;
-
-__device__ __forceinline__ float wave_min_f(float v) {
-    for (int m = 32; m >= 1; m >>= 1) v = fminf(v, shfl_xor_f(v, m));
-    return v;
-}
-__device__ __forceinline__ float wave_max_f(float v) {
-    for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, shfl_xor_f(v, m));
-    return v;
-}
 
 // The 8 codes of a lane's channels, as integer-valued floats: round-half-even of the
 // correctly rounded quotient (x - zero) / scale.  The quotient is first approximated by a
@@ -184,7 +186,7 @@ template <typename T>
 __global__ __launch_bounds__(kCmpThreads) void compress_kernel(
     const char* __restrict__ K, const char* __restrict__ V, const int32_t* __restrict__ chunk_off,
     const int32_t* __restrict__ n_chunks, QRecord* __restrict__ qmeta, unsigned char* __restrict__ kblob,
-    unsigned char* __restrict__ vblob, int c_max, int n_kv_heads, int n_ctx) {
+    unsigned char* __restrict__ vblob, long long blob_bytes, int c_max, int n_kv_heads, int n_ctx) {
     static_assert(T::kEpl == 8, "16-bit sources only");
     constexpr int ROWB = Row<T>::kRowBytes;
     __shared__ float red[2][kCmpWaves];
@@ -200,6 +202,8 @@ __global__ __launch_bounds__(kCmpThreads) void compress_kernel(
     QRecord* rec = qmeta + bh * c_max + c;
     const long long byte_off = rec->byte_off;
     const bool four = rec->bits == 4;
+    // (boundaries that overlap can add up to more than the blobs hold: such a chunk is not written)
+    if (byte_off < 0 || byte_off + (long long)rows * (four ? LEOAM_D / 2 : LEOAM_D) > blob_bytes) return;
     const char* src = (is_v ? V : K) + (bh * (size_t)n_ctx + t0) * ROWB + (size_t)c16 * 16;
 
     // ---- min / max of the chunk (a row past the end re-reads the last row) ------------
@@ -227,8 +231,8 @@ __global__ __launch_bounds__(kCmpThreads) void compress_kernel(
 #pragma unroll
         for (int j = 0; j < kCmpHeld; j += 2) fold2(a[j], a[j + 1]);
     }
-    lo = wave_min_f(lo);
-    hi = wave_max_f(hi);
+    lo = wave_extreme_f<false>(lo);
+    hi = wave_extreme_f<true>(hi);
     if (lane == 0) {
         red[0][wave] = lo;
         red[1][wave] = hi;
@@ -313,20 +317,20 @@ size_t compressed_bytes_bound(const leoam_shape* s) {
 
 hipError_t compress_dispatch(const leoam_shape* s, const void* K, const void* V, const int32_t* chunk_off,
                              const int32_t* n_chunks, const uint8_t* four_bit, void* kblob, void* vblob, void* qmeta,
-                             long long* total_bytes, hipStream_t stream) {
+                             size_t blob_bytes, long long* total_bytes, hipStream_t stream) {
     hipLaunchKernelGGL(compress_layout_kernel, dim3(s->n_kv_heads, s->batch), dim3(kLayThreads), 0, stream, chunk_off, n_chunks,
-                       four_bit, (QRecord*)qmeta, total_bytes, s->c_max, s->n_kv_heads, s->batch);
+                       four_bit, (QRecord*)qmeta, total_bytes, s->c_max, s->n_kv_heads, s->batch, s->n_ctx);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     dim3 grid(s->c_max, s->n_kv_heads * 2, s->batch), block(kCmpThreads);      // y: (kv head, K or V)
     if (s->kv_dtype == LEOAM_F16)
         hipLaunchKernelGGL(compress_kernel<F16>, grid, block, 0, stream, (const char*)K, (const char*)V, chunk_off,
-                           n_chunks, (QRecord*)qmeta, (unsigned char*)kblob, (unsigned char*)vblob, s->c_max,
-                           s->n_kv_heads, s->n_ctx);
+                           n_chunks, (QRecord*)qmeta, (unsigned char*)kblob, (unsigned char*)vblob,
+                           (long long)blob_bytes, s->c_max, s->n_kv_heads, s->n_ctx);
     else
         hipLaunchKernelGGL(compress_kernel<BF16>, grid, block, 0, stream, (const char*)K, (const char*)V, chunk_off,
-                           n_chunks, (QRecord*)qmeta, (unsigned char*)kblob, (unsigned char*)vblob, s->c_max,
-                           s->n_kv_heads, s->n_ctx);
+                           n_chunks, (QRecord*)qmeta, (unsigned char*)kblob, (unsigned char*)vblob,
+                           (long long)blob_bytes, s->c_max, s->n_kv_heads, s->n_ctx);
     return hipGetLastError();
 }
 

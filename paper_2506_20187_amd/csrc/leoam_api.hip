@@ -31,7 +31,7 @@ hipError_t tree_refine_dispatch(const leoam_shape*, const void*, const void*, co
 size_t compressed_bytes_bound(const leoam_shape*);
 hipError_t compression_tags_dispatch(const leoam_shape*, const int32_t*, const int32_t*, const int32_t*, uint8_t*, hipStream_t);
 hipError_t compress_dispatch(const leoam_shape*, const void*, const void*, const int32_t*, const int32_t*, const uint8_t*,
-                             void*, void*, void*, long long*, hipStream_t);
+                             void*, void*, void*, size_t, long long*, hipStream_t);
 hipError_t abstract_append_dispatch(const leoam_shape*, const void*, int32_t*, int32_t*, int, void*, int32_t*, hipStream_t);
 
 // scores of the first `sink` and the last `tail` chunks of every (b, h) row become FLT_MAX
@@ -269,7 +269,7 @@ int kv_chunk_compress(const leoam_shape* shape, const void* K, const void* V, co
     if (shape->kv_dtype != LEOAM_F16 && shape->kv_dtype != LEOAM_BF16) return LEOAM_E_UNSUPPORTED;
     if (((uintptr_t)kblob & 15u) || ((uintptr_t)vblob & 15u) || ((uintptr_t)qmeta & 15u)) return LEOAM_E_INVALID_ARG;
     if (blob_bytes < compressed_bytes_bound(shape)) return LEOAM_E_WORKSPACE;
-    return from_hip(compress_dispatch(shape, K, V, chunk_off, n_chunks, four_bit, kblob, vblob, qmeta,
+    return from_hip(compress_dispatch(shape, K, V, chunk_off, n_chunks, four_bit, kblob, vblob, qmeta, blob_bytes,
                                       (long long*)total_bytes, (hipStream_t)stream));
 }
 

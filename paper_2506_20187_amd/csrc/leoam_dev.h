@@ -186,14 +186,24 @@ __device__ __forceinline__ float rows_sum4(float a, float b, float c, float d) {
     permlane16_swap(u, w);
     return u + w;
 }
-// The maximum of v over lanes j, j+16, j+32, j+48, in all four (two swaps on the
-// vector ALU instead of two round trips through the LDS crossbar).
-__device__ __forceinline__ float rows_max4(float v) {
+// The maximum (minimum) of v over lanes j, j+16, j+32, j+48, in all four (two swaps on
+// the vector ALU instead of two round trips through the LDS crossbar).
+template <bool kMax> __device__ __forceinline__ float rows_extreme4(float v) {
     float a = v, b = v;
     permlane32_swap(a, b);      // a: lower half everywhere, b: upper half everywhere
-    float u = fmaxf(a, b), w = u;
+    float u = kMax ? fmaxf(a, b) : fminf(a, b), w = u;
     permlane16_swap(u, w);      // u: rows 0,0,2,2; w: rows 1,1,3,3 (rows 0 = 2 and 1 = 3 by now)
-    return fmaxf(u, w);
+    return kMax ? fmaxf(u, w) : fminf(u, w);
+}
+__device__ __forceinline__ float rows_max4(float v) { return rows_extreme4<true>(v); }
+// Maximum (minimum) over the 64 lanes, in every lane: butterfly inside the rows on the
+// DPP path, then across the rows.
+template <bool kMax> __device__ __forceinline__ float wave_extreme_f(float v) {
+    v = kMax ? fmaxf(v, dpp_f<0xB1>(v)) : fminf(v, dpp_f<0xB1>(v));
+    v = kMax ? fmaxf(v, dpp_f<0x4E>(v)) : fminf(v, dpp_f<0x4E>(v));
+    v = kMax ? fmaxf(v, dpp_f<0x141>(v)) : fminf(v, dpp_f<0x141>(v));
+    v = kMax ? fmaxf(v, dpp_f<0x140>(v)) : fminf(v, dpp_f<0x140>(v));
+    return rows_extreme4<kMax>(v);
 }
 // Four values at once: row 0 returns the maximum (minimum) of a over lanes j, j+16, j+32,
 // j+48, row 1 that of c, row 2 that of b, row 3 that of d (three swaps for four folds).

@@ -186,6 +186,38 @@ def test_compress_error_codes(L):
     assert not ok.any() and (qm[..., 2] == 8).all() and not qm[..., 3:].any()
 
 
+def test_compress_bad_boundaries_stay_inside_the_blobs(L, oracle):
+    """Boundaries that rise, fall and rise again: every rising step is a chunk inside the context, together
+    they hold more rows than the context.  Falling steps take no room, and a chunk that would end past
+    blob_bytes is not written."""
+    B, Hkv, N, c_max = 1, 2, 256, 5
+    g = torch.Generator().manual_seed(11)
+    K = torch.randn(B, Hkv, N, 128, generator=g).to(torch.float16)
+    V = torch.randn(B, Hkv, N, 128, generator=g).to(torch.float16)
+    off = torch.tensor([[0, 256, 0, 256, 100, 90]], dtype=torch.int32, device="cuda")
+    nc = torch.tensor([5], dtype=torch.int32, device="cuda")
+    fb = torch.zeros(B, c_max, dtype=torch.uint8, device="cuda")
+    shape = L.make_shape(B, Hkv, Hkv, 128, N, c_max, 1, torch.float16)
+    cap = L.leoam_compressed_bytes_bound(shape)
+    guard = 4096
+    kbig = torch.full((cap + guard,), 0xEE, dtype=torch.uint8, device="cuda")
+    vbig = torch.full((cap + guard,), 0xEE, dtype=torch.uint8, device="cuda")
+    qm = torch.zeros(B, Hkv, c_max, 8, dtype=torch.int32, device="cuda")
+    total = torch.zeros(1, dtype=torch.int64, device="cuda")
+    L.kv_chunk_compress(shape, K.cuda(), V.cuda(), off, nc, fb, kbig[:cap], vbig[:cap], qm, total)
+    torch.cuda.synchronize()
+    assert (kbig[cap:] == 0xEE).all() and (vbig[cap:] == 0xEE).all(), "nothing is written past blob_bytes"
+    # two whole-context chunks per head at 8 bits: twice what a head's share of the blob holds
+    assert int(total.item()) == 2 * cap
+    # head 0's two chunks fill the blob (the same codes twice), head 1's would lie past it
+    packed1 = np.array([[0, N]], dtype=np.int32)
+    wk, wv, _ = oracle.chunk_compress(K[:, :1], V[:, :1], packed1, np.array([1], dtype=np.int32), np.zeros((1, 1), dtype=bool))
+    half = N * 128
+    kb, vb = kbig[:cap].cpu().numpy(), vbig[:cap].cpu().numpy()
+    assert np.array_equal(kb[:half], wk) and np.array_equal(kb[half:], wk)
+    assert np.array_equal(vb[:half], wv) and np.array_equal(vb[half:], wv)
+
+
 def test_compression_tags_exact_and_policy_loop(L, oracle):
     """chunk_compression_tags against the oracle on ragged selections, then the whole policy loop on the GPU:
     theta from the latency condition -> token budget (1 - theta) N -> selection by score -> tags -> compressed
