@@ -660,25 +660,22 @@ __global__ __launch_bounds__(kAttThreads) void sparse_attention_qm_kernel(
 
     // ---- fold the four lane groups (same m everywhere in the wave); zero_v's share is the same for
     // every channel ---------------------------------------------------------------------------------
-    l_run += shfl_xor_f(l_run, 16);
-    l_run += shfl_xor_f(l_run, 32);
+    // (four accumulators at a time by lane swaps: afterwards lane group r holds the total of
+    // accumulator e_own of the quad, so all 64 lanes write to LDS)
+    l_run = rows_sum4(l_run, l_run, l_run, l_run);
+    const int e_own = ((grp & 1) << 1) | (grp >> 1);        // rows 0,1,2,3 own accumulators 0,2,1,3
+    static_assert(EPL == 8, "two quads of accumulators per head");
 #pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-            acc[g][e] += accz[g];
-            acc[g][e] += shfl_xor_f(acc[g][e], 16);
-            acc[g][e] += shfl_xor_f(acc[g][e], 32);
-        }
-    if (grp == 0) {
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) xw[wave][g][c16 * EPL + code_channel(e)] = acc[g][e];
-        if (c16 < G) {
-            xw[wave][c16][LEOAM_D] = m_run;
-            xw[wave][c16][LEOAM_D + 1] = l_run;
-        }
+    for (int g = 0; g < G; ++g) {
+        const float f0 = rows_sum4(acc[g][0] + accz[g], acc[g][1] + accz[g], acc[g][2] + accz[g], acc[g][3] + accz[g]);
+        const float f1 = rows_sum4(acc[g][4] + accz[g], acc[g][5] + accz[g], acc[g][6] + accz[g], acc[g][7] + accz[g]);
+        // accumulator e holds channel code_channel(e) = 2e (e < 4) or 2(e - 4) + 1
+        xw[wave][g][c16 * EPL + 2 * e_own] = f0;
+        xw[wave][g][c16 * EPL + 2 * e_own + 1] = f1;
+    }
+    if (grp == 0 && c16 < G) {
+        xw[wave][c16][LEOAM_D] = m_run;
+        xw[wave][c16][LEOAM_D + 1] = l_run;
     }
     finish_split<G>(xw, partial, b, h, split, n_splits, n_kv_heads, mg);
 }

@@ -511,24 +511,19 @@ void sparse_attention_mfma_kernel(
     }
 
     // ---- fold the four lane groups (same m everywhere in the wave) ---------------
-    l_run += shfl_xor_f(l_run, 16);
-    l_run += shfl_xor_f(l_run, 32);
+    // (four accumulators at a time by lane swaps: afterwards lane group r holds the total of
+    // accumulator e_own of the quad, so all 64 lanes write to LDS)
+    l_run = rows_sum4(l_run, l_run, l_run, l_run);
+    const int e_own = ((grp & 1) << 1) | (grp >> 1);        // rows 0,1,2,3 own accumulators 0,2,1,3
+    static_assert(EPL == 8, "two quads of accumulators per head");
 #pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-            acc[g][e] += shfl_xor_f(acc[g][e], 16);
-            acc[g][e] += shfl_xor_f(acc[g][e], 32);
-        }
-    if (grp == 0) {
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) xw[wave][g][c16 * EPL + e] = acc[g][e];
-        if (c16 < G) {
-            xw[wave][c16][LEOAM_D] = m_run;
-            xw[wave][c16][LEOAM_D + 1] = l_run;
-        }
+    for (int g = 0; g < G; ++g) {
+        xw[wave][g][c16 * EPL + e_own] = rows_sum4(acc[g][0], acc[g][1], acc[g][2], acc[g][3]);
+        xw[wave][g][c16 * EPL + 4 + e_own] = rows_sum4(acc[g][4], acc[g][5], acc[g][6], acc[g][7]);
+    }
+    if (grp == 0 && c16 < G) {
+        xw[wave][c16][LEOAM_D] = m_run;
+        xw[wave][c16][LEOAM_D + 1] = l_run;
     }
     finish_split<G>(xw, partial, b, h, split, n_splits, n_kv_heads, mg);
 }
