@@ -203,6 +203,42 @@ def test_select_exact(L, oracle, C):
                 assert np.array_equal(w, g), f"{what} differs: C={C} {name} max_chunks={max_chunks} budget={budget}"
 
 
+@pytest.mark.parametrize("m", [1, 2, 16, 17, 33, 64, 65, 128, 129, 256, 257, 512, 513, 1024, 1025])
+def test_select_cluster_at_the_threshold(L, oracle, m):
+    """m chunks with nearly equal (distinct, and a few equal) scores sit where the budget runs out, the
+    others far above and far below: after the first histogram pass exactly those m are left to be ranked,
+    which takes the pairwise step through every width of its lane groups (and past its limit of 1024)."""
+    rng = np.random.default_rng(m)
+    B, Hkv, C = 2, 2, m + 300
+    sizes = rng.integers(1, 33, size=(B, C))
+    offs = [np.concatenate([[0], np.cumsum(sizes[b])]).astype(np.int32) for b in range(B)]
+    N = int(max(o[-1] for o in offs))
+    offs = [np.concatenate([o[:-1], [N]]).astype(np.int32) for o in offs]
+    packed, counts, c_max = gen.pack_boundaries(offs, N)
+    score = np.empty((B, Hkv, c_max), dtype=np.float32)
+    for b in range(B):
+        for h in range(Hkv):
+            role = rng.permutation(C)
+            s = np.empty(C, dtype=np.float32)
+            s[role[:100]] = 1000.0 + rng.standard_normal(100) * 50              # far above
+            s[role[100:300]] = -1000.0 + rng.standard_normal(200) * 50          # far below
+            cluster = 10.0 + np.float32(2e-6) * rng.integers(0, max(2, m // 2), size=m)     # one bin wide, with ties
+            s[role[300:]] = cluster.astype(np.float32)
+            score[b, h, :C] = s
+    for frac in (0.25, 0.5, 0.9):
+        # the 100 high chunks hold about 100 * 16.5 tokens; the budget ends part of the way into the cluster
+        budget = int(100 * 16.5 + frac * m * 16.5)
+        want = oracle.topk_select(score, packed, counts, 0, budget, c_max)
+        got = gpu_select(L, score, packed, counts, 0, budget, c_max, N)
+        for w, g, what in zip(want, got, ("sel_idx", "sel_count", "sel_tokens")):
+            assert np.array_equal(w, g), f"{what} differs: m={m} budget={budget}"
+        max_chunks = 100 + int(frac * m)
+        want = oracle.topk_select(score, packed, counts, max_chunks, 0, c_max)
+        got = gpu_select(L, score, packed, counts, max_chunks, 0, c_max, N)
+        for w, g, what in zip(want, got, ("sel_idx", "sel_count", "sel_tokens")):
+            assert np.array_equal(w, g), f"{what} differs: m={m} max_chunks={max_chunks}"
+
+
 def test_select_kmax_caps_the_count(L, oracle):
     rng = np.random.default_rng(3)
     C, N = 200, 200 * 8
