@@ -52,10 +52,32 @@ __device__ __forceinline__ unsigned long long layout_block_sum(unsigned long lon
 // bytes of chunk c of a sequence in one blob, for one kv head.  A chunk whose boundaries do
 // not lie in the context in ascending order stores nothing (the compression kernel skips it
 // by the same test).
-__device__ __forceinline__ int chunk_bytes(const int32_t* off, const uint8_t* four, int c, int n_ctx) {
-    const int t0 = off[c], rows = off[c + 1] - t0;
+__device__ __forceinline__ int chunk_bytes(int t0, int t1, int four, int n_ctx) {
+    const int rows = t1 - t0;
     if (t0 < 0 || rows <= 0 || rows > n_ctx - t0) return 0;
-    return rows * (four[c] ? LEOAM_D / 2 : LEOAM_D);
+    return rows * (four ? LEOAM_D / 2 : LEOAM_D);
+}
+// Sum of chunk_bytes over chunks first, first + step, ... below n.  The loads are
+// unconditional (indices past the end are clamped, their results dropped) and kLayUnroll
+// chunks are fetched per round trip.
+constexpr int kLayUnroll = 8;
+__device__ __forceinline__ unsigned long long chunk_bytes_sum(const int32_t* off, const uint8_t* four, int first, int step,
+                                                              int n, int c_max, int n_ctx) {
+    unsigned long long part = 0;
+    for (int c = first; c < n; c += step * kLayUnroll) {
+        int t0[kLayUnroll], t1[kLayUnroll], f[kLayUnroll];
+#pragma unroll
+        for (int u = 0; u < kLayUnroll; ++u) {
+            const int cc = min(c + u * step, c_max - 1);
+            t0[u] = off[cc];
+            t1[u] = off[cc + 1];
+            f[u] = four[cc];
+        }
+#pragma unroll
+        for (int u = 0; u < kLayUnroll; ++u)
+            if (c + u * step < n) part += (unsigned long long)chunk_bytes(t0[u], t1[u], f[u], n_ctx);
+    }
+    return part;
 }
 
 __global__ __launch_bounds__(kLayThreads) void compress_layout_kernel(
@@ -75,8 +97,7 @@ __global__ __launch_bounds__(kLayThreads) void compress_layout_kernel(
             const int32_t* off = chunk_off + (size_t)bb * (c_max + 1);
             const uint8_t* four = four_bit + (size_t)bb * c_max;
             const int n = min(max(n_chunks[bb], 0), c_max);
-#pragma unroll 4
-            for (int c = lane; c < n; c += LEOAM_WAVE) part += (unsigned long long)chunk_bytes(off, four, c, n_ctx);
+            part = chunk_bytes_sum(off, four, lane, LEOAM_WAVE, n, c_max, n_ctx);
         }
         part = group_sum_u64(part, 6);
         __syncthreads();      // the previous round's totals have been read
@@ -91,16 +112,16 @@ __global__ __launch_bounds__(kLayThreads) void compress_layout_kernel(
     const uint8_t* four = four_bit + (size_t)b * c_max;
     const int n = min(max(n_chunks[b], 0), c_max);
     // bytes of one head of this sequence
-    unsigned long long part = 0;
-    for (int c = tid; c < n; c += kLayThreads) part += (unsigned long long)chunk_bytes(off, four, c, n_ctx);
-    const unsigned long long per_head = layout_block_sum(part, slots);
+    const unsigned long long per_head = layout_block_sum(chunk_bytes_sum(off, four, tid, kLayThreads, n, c_max, n_ctx), slots);
 
     // exclusive scan over the chunks, a tile of 1024 at a time
     unsigned long long carry = 0;
     for (int base = 0; base < c_max; base += kLayThreads) {
         const int c = base + tid;
         // (chunks that tile a context sum to less than 2^31 bytes per head, so a wave's scan stays in 32 bits)
-        const unsigned long long mine = c < n ? (unsigned long long)chunk_bytes(off, four, c, n_ctx) : 0ull;
+        const int cc = min(c, c_max - 1);
+        const int t0 = off[cc], t1 = off[cc + 1], f4 = four[cc];
+        const unsigned long long mine = c < n ? (unsigned long long)chunk_bytes(t0, t1, f4, n_ctx) : 0ull;
         const unsigned long long incl = wave_incl_scan_u32((uint32_t)mine);
         __syncthreads();
         if (lane == LEOAM_WAVE - 1) wave_incl[wave] = incl;
@@ -117,7 +138,7 @@ __global__ __launch_bounds__(kLayThreads) void compress_layout_kernel(
             QRecord r;
             if (c < n) {
                 r.byte_off = (long long)(before + (unsigned long long)h * per_head + within);
-                r.bits = four[c] ? 4 : 8;
+                r.bits = f4 ? 4 : 8;
             } else {
                 r.byte_off = 0;
                 r.bits = 0;
