@@ -287,7 +287,10 @@ def make_case(config: str, layer: int = 0, *, device="cpu", seed: int = BASE_SEE
         offs.append(off)
         heavy.append(hv if hv is not None else np.zeros(N, dtype=bool))
         planted = pl if pl is not None else planted
-    packed, counts, c_max = pack_boundaries(offs, N)
+    # the chunk capacity is rounded up to a multiple of 32: the abstracts of every (sequence, kv head)
+    # then start at the same offset inside 16 KiB (what the score kernel's 16 KiB groups like best)
+    most = max(len(o) - 1 for o in offs)
+    packed, counts, c_max = pack_boundaries(offs, N, c_max=(most + 31) // 32 * 32)
     smallest = min(int(np.diff(o).min()) for o in offs)
     if cfg["max_chunks"] > 0:
         k_max = cfg["max_chunks"]

@@ -90,7 +90,9 @@ typedef struct {
     int32_t n_kv_heads;     /* Hkv >= 1 */
     int32_t head_dim;       /* D, must be 128 */
     int32_t n_ctx;          /* N, tokens per sequence (same for the whole batch) */
-    int32_t c_max;          /* row stride of per-chunk arrays, 1..16384 */
+    int32_t c_max;          /* row stride of per-chunk arrays, 1..16384 (any value is correct; a multiple of 32
+                             * lets every (b,h)'s abstract start at the same offset inside 16 KiB, which is
+                             * what chunk_score streams fastest) */
     int32_t k_max;          /* row stride of sel_idx, 1..c_max; also caps the kept count */
     int32_t kv_dtype;       /* leoam_dtype of K and V */
     int32_t abstract_dtype; /* dtype of the abstract and of q: == kv_dtype, or LEOAM_F16 when kv_dtype == LEOAM_Q8Q4 */
