@@ -165,7 +165,7 @@ __device__ __forceinline__ uint32_t row0_max_u32(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_readlane((int)v, 15);
 }
 
-// ---- sums across the four 16-lane rows -----------------------------------------
+// ---- sums, maxima and minima across the four 16-lane rows ------------------------
 // v_permlane32_swap a, b exchanges a[32..63] with b[0..31]; v_permlane16_swap
 // exchanges rows 1 and 3 of a with rows 0 and 2 of b.  (Written as assembly: the
 // compiler builtins of this toolchain lose the second result.  The s_nop pairs
@@ -232,6 +232,13 @@ __device__ __forceinline__ void permlane16_swap_d(double& a, double& b) {
     a = __builtin_bit_cast(double, ((uint64_t)ah << 32) | al);
     b = __builtin_bit_cast(double, ((uint64_t)bh << 32) | bl);
 }
+template <bool kMax> __device__ __forceinline__ double rows_extreme4_d(double v) {
+    double a = v, b = v;
+    permlane32_swap_d(a, b);
+    double u = kMax ? fmax(a, b) : fmin(a, b), w = u;
+    permlane16_swap_d(u, w);
+    return kMax ? fmax(u, w) : fmin(u, w);
+}
 // Sum of a 64-bit value over aligned groups of 2^log2_group lanes (wave-uniform
 // log2_group, 0..6); every lane of a group gets the total.  Butterfly steps inside a
 // row on the DPP path, the steps across rows by lane swaps: nothing goes through LDS.
@@ -259,14 +266,6 @@ __device__ __forceinline__ uint64_t group_sum_u64(uint64_t v, int log2_group) {
         v = (((uint64_t)ah << 32) | al) + (((uint64_t)bh << 32) | bl);
     }
     return v;
-}
-
-template <bool kMax> __device__ __forceinline__ double rows_extreme4_d(double v) {
-    double a = v, b = v;
-    permlane32_swap_d(a, b);
-    double u = kMax ? fmax(a, b) : fmin(a, b), w = u;
-    permlane16_swap_d(u, w);
-    return kMax ? fmax(u, w) : fmin(u, w);
 }
 
 }  // namespace leoam
