@@ -69,11 +69,13 @@ __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
 
     const int n_sets = (C + kChunksPerSet - 1) / kChunksPerSet;
     const int stride = gridDim.x * kScoreWaves;
-    // Groups of four sets (16 KiB) are cut at 16 KiB addresses, not at the start of the (b,h)'s
-    // abstract: `lead` sets of the first group lie before it and are skipped.  With c_max not a
-    // multiple of 32 the abstracts of different (b,h) start at different offsets inside 16 KiB, and
-    // groups cut from each one's start measured 18-30 % slower on MI355X than mutually aligned ones.
-    const int lead = kSingle ? 0 : (int)(((uintptr_t)Abh >> 12) & 3);
+    // Groups of four sets (16 KiB of 16-bit rows) are cut at addresses that are multiples of their
+    // size, not at the start of the (b,h)'s abstract: `lead` sets of the first group lie before it
+    // and are skipped.  With c_max not a multiple of 32 the abstracts of different (b,h) start at
+    // different offsets inside 16 KiB, and groups cut from each one's start measured 18-30 % slower
+    // on MI355X than mutually aligned ones.
+    constexpr uintptr_t kSetBytes = (uintptr_t)kRowsPerSet * ROWB;
+    const int lead = kSingle ? 0 : (int)(((uintptr_t)Abh / kSetBytes) & 3);
 
     // Loads are unconditional (a guarded load would make the compiler wait for
     // every outstanding load and defeat the prefetch): a row past the end of the

@@ -159,6 +159,37 @@ def test_score_exact(L, oracle, dtype, G):
     assert np.array_equal(s_only.cpu().numpy(), ub)
 
 
+@pytest.mark.parametrize("dtype,G,c_max", [("bf16", 4, 301), ("f16", 2, 264), ("bf16", 1, 333), ("f32", 4, 150)])
+def test_score_exact_many_heads_odd_capacity(L, oracle, dtype, G, c_max):
+    """Enough (sequence, kv head) pairs for the launch that streams 16 KiB groups of abstract rows, with
+    capacities that let the abstracts of different pairs start at every offset inside 16 KiB (the groups
+    are cut at 16 KiB addresses, so the first one of a pair is partly skipped), and ragged chunk counts."""
+    rng = np.random.default_rng(c_max)
+    B, Hkv, D = 64, 8, 128
+    counts = rng.integers(c_max // 2, c_max + 1, size=B).astype(np.int32)
+    counts[:3] = (c_max, 0, 1)
+    # abstracts straight from random key values: kmax >= kmin element-wise
+    a = rng.standard_normal((B, Hkv, c_max, D)).astype(np.float32)
+    b = rng.standard_normal((B, Hkv, c_max, D)).astype(np.float32)
+    ab = torch.from_numpy(np.stack([np.maximum(a, b), np.minimum(a, b)], axis=3)).to(TDT[dtype])      # [B,Hkv,c_max,2,D]
+    q = torch.from_numpy(rng.standard_normal((B, Hkv * G, D)).astype(np.float32)).to(TDT[dtype])
+    ub, lb = oracle.chunk_score(q, ab.to(torch.float64).numpy(), counts, want_lower=True)
+    shape = L.make_shape(B, Hkv * G, Hkv, D, 4096, c_max, 1, TDT[dtype])
+    abd = dev(ab)
+    set_bytes = 16 * D * abd.element_size()                  # sixteen abstract rows
+    leads = {((abd.data_ptr() + i * c_max * 2 * D * abd.element_size()) // set_bytes) & 3 for i in range(B * Hkv)}
+    assert len(leads) > 1, "the capacities were chosen so that the first groups differ"
+    s_ub = torch.empty(B, Hkv, c_max, dtype=torch.float32, device="cuda")
+    s_lb = torch.empty_like(s_ub)
+    L.chunk_score(shape, dev(q), abd, dev(counts), s_ub, s_lb)
+    s_only = torch.empty_like(s_ub)
+    L.chunk_score(shape, dev(q), abd, dev(counts), s_only, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(s_ub.cpu().numpy(), ub)
+    assert np.array_equal(s_lb.cpu().numpy(), lb)
+    assert np.array_equal(s_only.cpu().numpy(), ub)
+
+
 # ---------------------------------------------------------------------------
 # a3 select
 # ---------------------------------------------------------------------------
