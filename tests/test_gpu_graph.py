@@ -39,6 +39,19 @@ def test_decode_step_replays_from_a_graph(L, cfg, kw, separate):
     case = gen.make_case(cfg, device="cuda", **kw)
     layer = L.DecodeLayer(case.K, case.V, case.chunk_off, case.n_chunks, case.hq, case.k_max, case.max_chunks,
                           case.token_budget)
+    replay_against_eager(layer, case, separate)
+
+
+@pytest.mark.parametrize("separate", [False, True], ids=["one_call", "three_calls"])
+def test_compressed_store_step_replays_from_a_graph(L, separate):
+    qc = gen.make_quant_case("c4", layer=9, n_ctx=32768 + 77, hq=8, hkv=2, token_budget=2048, device="cuda")
+    c = qc.case
+    layer = L.DecodeLayer(qc.kblob, qc.vblob, c.chunk_off, c.n_chunks, c.hq, c.k_max, c.max_chunks, c.token_budget,
+                          qmeta=qc.qmeta, n_kv_heads=c.hkv, n_ctx=c.n_ctx)
+    replay_against_eager(layer, c, separate)
+
+
+def replay_against_eager(layer, case, separate):
     layer.build_abstract()
     step = layer.step_separate if separate else layer.step
     q = case.q.clone()                      # the graph reads its query from this buffer
