@@ -147,12 +147,16 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
         const int wbase = wave * LEOAM_WAVE * kIpt;
         float rs[kIpt];
         int ro[kIpt];
+        // (the boundary after the wave's last item goes out with the others: left to the compiler the
+        // load sinks into the one-lane branch that uses it, behind the wait for the others - one more
+        // round trip; the empty asm is an opaque use that keeps it here)
+        int ro_end = off[min(wbase + LEOAM_WAVE * kIpt, c_max)];
 #pragma unroll
         for (int j = 0; j < kIpt; ++j) {
             rs[j] = srow[min(wbase + LEOAM_WAVE * j + lane, c_max - 1)];
             ro[j] = off[min(wbase + LEOAM_WAVE * j + lane, c_max)];
         }
-        const int ro_end = off[min(wbase + LEOAM_WAVE * kIpt, c_max)];
+        asm volatile("" : "+v"(ro_end));
         constexpr int kPerBlock = kStageItems / kIpt;          // lanes whose items a block holds
         uint32_t* st = L.stage[wave];
         const int my_block = lane / kPerBlock, base = (lane % kPerBlock) * kIpt;
