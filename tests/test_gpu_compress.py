@@ -62,6 +62,19 @@ def test_compress_exact_ragged_chunks(L, oracle, dtype, share):
     check_against_oracle(oracle, gpu_compress(L, K, V, packed, counts, fb), K, V, packed, counts, fb)
 
 
+def test_compress_many_sequences(L, oracle):
+    # more sequences than the layout kernel sums in one round (a wave per earlier sequence, sixteen at a time)
+    rng = np.random.default_rng(77)
+    g = torch.Generator().manual_seed(6)
+    B, Hkv, N = 37, 2, 300
+    K = torch.randn(B, Hkv, N, 128, generator=g).to(torch.bfloat16)
+    V = torch.randn(B, Hkv, N, 128, generator=g).to(torch.bfloat16)
+    offs = [gen.make_boundaries(N, rng, sizes=(1, 3, 16, 40, 70)) for _ in range(B)]
+    packed, counts, c_max = gen.pack_boundaries(offs, N)
+    fb = rng.random((B, c_max)) < 0.5
+    check_against_oracle(oracle, gpu_compress(L, K, V, packed, counts, fb), K, V, packed, counts, fb)
+
+
 def test_compress_degenerate_values(L, oracle):
     # constant chunks (scale 0), chunks on the code grid with ties, one huge outlier, negative zero
     N, B, Hkv = 256, 1, 2
