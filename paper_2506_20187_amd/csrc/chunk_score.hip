@@ -225,17 +225,17 @@ __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
 template <typename T, int G>
 static hipError_t launch_score(const leoam_shape* s, const void* q, const void* abstract, const int32_t* n_chunks,
                                float* ub, float* lb, hipStream_t stream) {
-    // About eighteen workgroups per compute unit in total, so that most waves take a
-    // single group of row sets.  The count per (b,h) is kept odd: with 8, 16 or 32
-    // workgroups per (b,h) the kernel measured 13 % slower on MI355X (the workgroups
-    // that run together then walk the abstract at a power-of-two stride).
+    // Enough workgroups that every wave takes a single group of row sets (a wave that walks on to
+    // a second group, a whole grid further, measured 3-10 % slower).  The count per (b,h) is kept
+    // odd: with 8, 16 or 32 workgroups per (b,h) the kernel measured 13 % slower on MI355X (the
+    // workgroups that run together then walk the abstract at a power-of-two stride).
     const int sets = (s->c_max + kChunksPerSet - 1) / kChunksPerSet;
     const int units = s->batch * s->n_kv_heads;
     const int groups = (sets + 3 + 3) / 4;                  // a wave works on groups of four sets (up to three lead sets)
     // small launches (groups of four would leave the chip under four waves per SIMD): one set per wave
     const bool single = (long long)groups * units <= 4096;
-    int gx = (4480 + units - 1) / units;
     const int gx_max = ((single ? sets : groups) + kScoreWaves - 1) / kScoreWaves;
+    int gx = single ? (4480 + units - 1) / units : gx_max;      // (small launches: about eighteen workgroups per CU)
     if (gx > gx_max) gx = gx_max;
     gx |= 1;
     dim3 grid(gx, s->n_kv_heads, s->batch), block(kScoreWaves * LEOAM_WAVE);
