@@ -372,6 +372,7 @@ static hipError_t launch_fused(const leoam_shape* s, const float* score, const v
     if (s->c_max <= kSelThreads) LEOAM_FUSED(1);
     else if (s->c_max <= 2 * kSelThreads) LEOAM_FUSED(2);
     else if (s->c_max <= 4 * kSelThreads) LEOAM_FUSED(4);
+    else if (s->c_max <= 6 * kSelThreads) LEOAM_FUSED(6);
     else LEOAM_FUSED(8);
 #undef LEOAM_FUSED
     return hipGetLastError();

@@ -342,7 +342,10 @@ static hipError_t launch_fused_q(const leoam_shape* s, const float* score, const
     if (s->c_max <= kSelThreads) LEOAM_FUSEDQ(1);
     else if (s->c_max <= 2 * kSelThreads) LEOAM_FUSEDQ(2);
     else if (s->c_max <= 4 * kSelThreads) LEOAM_FUSEDQ(4);
+    else if (s->c_max <= 6 * kSelThreads) LEOAM_FUSEDQ(6);
     else if (s->c_max <= 8 * kSelThreads) LEOAM_FUSEDQ(8);
+    else if (s->c_max <= 10 * kSelThreads) LEOAM_FUSEDQ(10);
+    else if (s->c_max <= 12 * kSelThreads) LEOAM_FUSEDQ(12);
     else LEOAM_FUSEDQ(16);
 #undef LEOAM_FUSEDQ
     return hipGetLastError();

@@ -80,7 +80,11 @@ __device__ __forceinline__ uint64_t block_excl_scan(uint64_t v, uint64_t* wave_s
     return base + incl - v;
 }
 
-constexpr int kStageItems = 256;                  // items a wave transposes at a time
+// A wave transposes its items through LDS a block of whole 64-item slices at a time; a block
+// must also hold whole lanes (kIpt items each): four slices when kIpt divides 256, else five
+// (kIpt = 10) or three (kIpt = 6, 12).
+constexpr int stage_slices(int ipt) { return (256 % ipt == 0) ? 4 : (ipt % 5 == 0 ? 5 : 3); }
+constexpr int kStageItems = 5 * LEOAM_WAVE;       // the largest block
 constexpr int kStageStride = kStageItems + 4;
 
 // LDS of one selection
@@ -143,7 +147,7 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
         // A lane's kIpt consecutive items are 4*kIpt bytes apart from its neighbour's: read
         // directly, every load instruction would touch 64 * kIpt * 4 / 128 cache lines.  The
         // wave reads its 64 * kIpt items with consecutive lanes on consecutive items instead
-        // and transposes them through LDS, 256 items at a time.
+        // and transposes them through LDS, a block of slices at a time.
         const int wbase = wave * LEOAM_WAVE * kIpt;
         float rs[kIpt];
         int ro[kIpt];
@@ -157,7 +161,10 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
             ro[j] = off[min(wbase + LEOAM_WAVE * j + lane, c_max)];
         }
         asm volatile("" : "+v"(ro_end));
-        constexpr int kPerBlock = kStageItems / kIpt;          // lanes whose items a block holds
+        constexpr int kSl = stage_slices(kIpt);                // slices per block
+        constexpr int kBlkItems = kSl * LEOAM_WAVE, kBlocks = kIpt / kSl;
+        static_assert(kBlkItems % kIpt == 0 && kIpt % kSl == 0 && kBlkItems <= kStageItems, "unsupported items per lane");
+        constexpr int kPerBlock = kBlkItems / kIpt;            // lanes whose items a block holds
         uint32_t* st = L.stage[wave];
         const int my_block = lane / kPerBlock, base = (lane % kPerBlock) * kIpt;
         auto wave_sync = [] {
@@ -165,9 +172,9 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
             __builtin_amdgcn_wave_barrier();
         };
 #pragma unroll
-        for (int blk = 0; blk < kIpt / 4; ++blk) {
+        for (int blk = 0; blk < kBlocks; ++blk) {
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) st[LEOAM_WAVE * jj + lane] = float_to_bits(rs[4 * blk + jj]);
+            for (int jj = 0; jj < kSl; ++jj) st[LEOAM_WAVE * jj + lane] = float_to_bits(rs[kSl * blk + jj]);
             wave_sync();
             if (my_block == blk) {
 #pragma unroll
@@ -176,15 +183,15 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
             wave_sync();
         }
 #pragma unroll
-        for (int blk = 0; blk < kIpt / 4; ++blk) {
+        for (int blk = 0; blk < kBlocks; ++blk) {
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) st[LEOAM_WAVE * jj + lane] = (uint32_t)ro[4 * blk + jj];
+            for (int jj = 0; jj < kSl; ++jj) st[LEOAM_WAVE * jj + lane] = (uint32_t)ro[kSl * blk + jj];
             // the boundary after the block's last item: the first item of the next block, or of the next wave
             int after = ro_end;
-            if constexpr (kIpt > 4) {
-                if (blk + 1 < kIpt / 4) after = ro[4 * (blk + 1 < kIpt / 4 ? blk + 1 : blk)];
+            if constexpr (kBlocks > 1) {
+                if (blk + 1 < kBlocks) after = ro[kSl * (blk + 1 < kBlocks ? blk + 1 : blk)];
             }
-            if (lane == 0) st[kStageItems] = (uint32_t)after;
+            if (lane == 0) st[kBlkItems] = (uint32_t)after;
             wave_sync();
             if (my_block == blk) {
 #pragma unroll

@@ -51,7 +51,10 @@ hipError_t topk_select_dispatch(const leoam_shape* s, const float* score, const 
     if (s->c_max <= kSelThreads) LEOAM_SEL(1);
     else if (s->c_max <= 2 * kSelThreads) LEOAM_SEL(2);
     else if (s->c_max <= 4 * kSelThreads) LEOAM_SEL(4);
+    else if (s->c_max <= 6 * kSelThreads) LEOAM_SEL(6);
     else if (s->c_max <= 8 * kSelThreads) LEOAM_SEL(8);
+    else if (s->c_max <= 10 * kSelThreads) LEOAM_SEL(10);
+    else if (s->c_max <= 12 * kSelThreads) LEOAM_SEL(12);
     else LEOAM_SEL(16);
 #undef LEOAM_SEL
     return hipGetLastError();

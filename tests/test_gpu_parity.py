@@ -204,7 +204,7 @@ def gpu_select(L, score, packed, counts, max_chunks, budget, k_max, N):
     return sel.cpu().numpy(), cnt.cpu().numpy(), tok.cpu().numpy()
 
 
-@pytest.mark.parametrize("C", [5, 130, 1024, 1500, 3000, 8192, 16384])
+@pytest.mark.parametrize("C", [5, 130, 1024, 1500, 3000, 5000, 8192, 9000, 11000, 16384])
 def test_select_exact(L, oracle, C):
     rng = np.random.default_rng(C)
     B, Hkv = 2, 3
@@ -447,10 +447,12 @@ def test_path_full_size_layer(L, oracle, cfg, layer, separate):
     check_path(L, oracle, case, separate=separate)
 
 
-def test_path_c3_full_shape_sampled(L, oracle):
-    """Batch-16 128K layer in the launch configuration bench.py times; the oracle
-    checks two of the sixteen sequences end to end."""
-    case = gen.make_case("c3", layer=30, device="cuda")
+@pytest.mark.parametrize("layer", [30, 0])
+def test_path_c3_full_shape_sampled(L, oracle, layer):
+    """Batch-16 128K layer in the launch configuration bench.py times (a deep layer with about 3K chunks
+    per sequence, the first layer with about 4.5K: four and six chunks per lane in the selection); the
+    oracle checks two of the sixteen sequences end to end."""
+    case = gen.make_case("c3", layer=layer, device="cuda")
     check_path(L, oracle, case, seqs=slice(5, 7))
 
 
@@ -483,7 +485,7 @@ def gpu_select_attend(L, dtype, score, q, K, V, packed, counts, max_chunks, budg
 
 
 @pytest.mark.parametrize("dtype,G,C", [("bf16", 4, 700), ("bf16", 4, 3000), ("f16", 1, 1500), ("f16", 2, 6000),
-                                       ("bf16", 2, 300), ("bf16", 1, 40), ("f16", 4, 2047),
+                                       ("bf16", 2, 300), ("bf16", 1, 40), ("f16", 4, 2047), ("bf16", 4, 4500), ("bf16", 4, 7000),
                                        ("f32", 2, 900), ("bf16", 8, 900)])      # last two: shapes that take two launches
 def test_select_attention_one_call(L, oracle, dtype, G, C):
     rng = np.random.default_rng(1000 + C + G)
