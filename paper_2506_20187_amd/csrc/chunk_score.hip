@@ -91,6 +91,16 @@ __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
     // the first fetch goes out before the queries are converted
     uint4 cur[NLOAD], nxt[NLOAD];
     const int g0 = blockIdx.x * kScoreWaves + wave;      // this wave's first group of four sets (or first set)
+    // A workgroup past the end of a sequence with fewer chunks than the capacity has nothing to
+    // contract: it writes its share of the row's tail and leaves before the queries are staged.
+    const int units_here = kSingle ? n_sets : (n_sets + lead + 3) >> 2;
+    if ((int)(blockIdx.x * kScoreWaves) >= units_here) {
+        for (int c = C + blockIdx.x * blockDim.x + threadIdx.x; c < c_max; c += gridDim.x * blockDim.x) {
+            score_ub[bh * c_max + c] = -INFINITY;
+            if (kLower) score_lb[bh * c_max + c] = INFINITY;
+        }
+        return;
+    }
     fetch(kSingle ? g0 : 4 * g0 - lead, cur);
 
     // A operands: clamped query values for every step, in double.  They are the same
