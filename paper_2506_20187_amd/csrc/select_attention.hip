@@ -24,7 +24,11 @@
 // Streaming: q K^T on v_mfma_f32_16x16x32 with token = row, query head = column
 // (as in sparse_attention.hip); P V in fp32 on the vector ALU.  With sixteen
 // waves per workgroup a wave has 128 registers: two K/V tiles in flight and the
-// accumulators; the queries (the matrix core's B operand) stay in LDS.
+// accumulators; the queries (the matrix core's B operand) stay in LDS.  Nothing
+// else in the tile loop goes through LDS: the running maximum over the four lane
+// groups is taken with lane swaps on the vector ALU (two ds_bpermute round trips
+// per tile in its place cost the launch 10 % on MI355X, the next tile's loads
+// queue behind the same waits).
 #include "fused_tail.h"
 
 namespace leoam {
