@@ -118,18 +118,22 @@ def test_quant_error_codes(L):
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("n_ctx,G", [(32768 + 77, 4), (32768 + 77, 1), (589824, 4)])
+@pytest.mark.parametrize("n_ctx,G", [(32768 + 77, 4), (32768 + 77, 1), (589824, 4), (327680, 2), (786432, 4)])
 def test_quant_one_call_equals_separate_calls(L, oracle, n_ctx, G):
     """The one-launch kernel of the compressed store (selection inside the launch, splits merged by the last
     workgroup) against the separate select / attention calls and the oracle; the larger context has more than
-    8192 chunks (sixteen chunks per lane in the selection).  The workspace's partials start as garbage, the
+    8192 chunks; the contexts are chosen so that the selection runs with 4, 6, 10 and 12 chunks per lane.  The workspace's partials start as garbage, the
     second call must leave the same bits as the first."""
     qc = gen.make_quant_case("c4", layer=9, n_ctx=n_ctx, hq=G, hkv=1, token_budget=4096, device="cuda")
     c = qc.case
     lay = L.DecodeLayer(qc.kblob, qc.vblob, c.chunk_off, c.n_chunks, c.hq, c.k_max, c.max_chunks, c.token_budget,
                         qmeta=qc.qmeta, n_kv_heads=c.hkv, n_ctx=c.n_ctx)
-    if n_ctx > 500000:
-        assert lay.shape.c_max > 8192
+    if n_ctx == 589824:
+        assert 8192 < lay.shape.c_max <= 10240          # ten chunks per lane in the selection
+    if n_ctx == 327680:
+        assert 4096 < lay.shape.c_max <= 6144           # six
+    if n_ctx == 786432:
+        assert 10240 < lay.shape.c_max <= 12288         # twelve
     lay.build_abstract()
     head = 256                                   # arrival counters stay zero, the partials behind them do not matter
     lay.workspace[head:].fill_(0x7f)
