@@ -486,7 +486,8 @@ def gpu_select_attend(L, dtype, score, q, K, V, packed, counts, max_chunks, budg
 
 @pytest.mark.parametrize("dtype,G,C", [("bf16", 4, 700), ("bf16", 4, 3000), ("f16", 1, 1500), ("f16", 2, 6000),
                                        ("bf16", 2, 300), ("bf16", 1, 40), ("f16", 4, 2047), ("bf16", 4, 4500), ("bf16", 4, 7000),
-                                       ("f32", 2, 900), ("bf16", 8, 900)])      # last two: shapes that take two launches
+                                       ("bf16", 8, 900), ("f16", 8, 3000), ("bf16", 8, 5000), ("f32", 2, 900)])
+                                       # (the last four: shapes that take two launches)
 def test_select_attention_one_call(L, oracle, dtype, G, C):
     rng = np.random.default_rng(1000 + C + G)
     B, Hkv, D = 2, 2, 128
