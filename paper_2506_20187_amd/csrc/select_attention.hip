@@ -328,8 +328,9 @@ static inline size_t fused_part_bytes_per_split(const leoam_shape* s) {
 
 bool select_attention_is_fused(const leoam_shape* s) {
     const int g = s->n_q_heads / s->n_kv_heads;
+    // (the kernel adds 32-bit row offsets to a per-(b,h) base: n_ctx * 256 bytes must stay below 4 GiB)
     return (s->kv_dtype == LEOAM_F16 || s->kv_dtype == LEOAM_BF16) && g <= 4 && s->k_max <= kFusedMaxSel &&
-           s->c_max <= 8 * kSelThreads;
+           s->c_max <= 8 * kSelThreads && s->n_ctx < (1 << 24);
 }
 
 static int fused_recommended_splits(const leoam_shape* s, int max_tokens) {
@@ -357,6 +358,8 @@ size_t select_attention_workspace_bytes(const leoam_shape* s, int max_tokens) {
     }
     return arrival_bytes(s) + body;
 }
+
+size_t select_attention_counter_bytes(const leoam_shape* s) { return arrival_bytes(s); }
 
 size_t select_attention_min_workspace_bytes(const leoam_shape* s) {
     return arrival_bytes(s) + ((select_attention_is_fused(s) || select_attention_q_is_fused(s)) ? 0 : attention_min_workspace_bytes(s));

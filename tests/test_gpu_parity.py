@@ -300,7 +300,8 @@ def gpu_attention(L, case_dtype, q, K, V, packed, counts, sel, cnt, k_max, max_t
     return out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
 
 
-@pytest.mark.parametrize("dtype,G", [("f32", 1), ("f32", 2), ("f16", 1), ("f16", 8), ("bf16", 4), ("bf16", 2)])
+@pytest.mark.parametrize("dtype,G", [("f32", 1), ("f32", 2), ("f32", 4), ("f32", 8), ("f16", 1), ("f16", 8), ("bf16", 4),
+                                      ("bf16", 2)])
 def test_attention_random_selection(L, oracle, dtype, G):
     rng = np.random.default_rng(40 + G)
     B, Hkv, N, D = 2, 2, 2500, 128
@@ -379,6 +380,38 @@ def run_path(L, case, separate=False):
     return layer
 
 
+def explain_score_mismatch(got, ub, ub64):
+    """Which kind of score mismatch this is: the kernel and the oracle add the same exact products in
+    different orders, so their float64 sums can differ in the last place and round to different floats
+    only when the sum lies at a rounding midpoint of float32 (expected about once in 1e9 scores); anything
+    else is an arithmetic error in the kernel."""
+    bad = np.argwhere(got != ub)
+    lines = [f"{len(bad)} scores differ"]
+    for b, h, c in bad[:8]:
+        s64, lo = float(ub64[b, h, c]), np.float32(ub64[b, h, c])
+        other = np.nextafter(lo, np.float32(np.inf) if s64 > float(lo) else np.float32(-np.inf))
+        mid = 0.5 * (float(lo) + float(other))
+        rel = abs(s64 - mid) / max(abs(s64), 1e-300)
+        kind = "float64 sum at a float32 rounding midpoint (summation order)" if rel < 1e-12 else "NOT a rounding tie: kernel error"
+        lines.append(f"  (b={b}, h={h}, chunk={c}): gpu {got[b, h, c]!r} oracle {ub[b, h, c]!r} float64 sum {s64!r}: {kind}")
+    return "\n".join(lines)
+
+
+def explain_selection_mismatch(got_sel, sel, ub, margin):
+    """On a kept-list mismatch: the oracle's margin at the cut (score of the last kept chunk minus score of the
+    first one left out) per (sequence, kv head), and whether it is a near-tie (< 1e-6 of the score)."""
+    lines = []
+    for b, h in np.argwhere((got_sel != sel).any(axis=2))[:8]:
+        kept = sel[b, h][sel[b, h] >= 0]
+        ref = float(np.abs(ub[b, h, kept]).min()) if len(kept) else 0.0
+        m = float(margin[b, h])
+        kind = "near-tie at the cut" if m < 1e-6 * ref else "clear margin: selection error"
+        only_gpu = sorted(set(got_sel[b, h][got_sel[b, h] >= 0].tolist()) - set(kept.tolist()))[:6]
+        only_orc = sorted(set(kept.tolist()) - set(got_sel[b, h][got_sel[b, h] >= 0].tolist()))[:6]
+        lines.append(f"  (b={b}, h={h}): cut margin {m:.3e} at |score| {ref:.3e}: {kind}; only gpu {only_gpu}, only oracle {only_orc}")
+    return "kept lists differ\n" + "\n".join(lines)
+
+
 def check_path(L, oracle, case, seqs=None, separate=False):
     layer = run_path(L, case, separate)
     sl = slice(None) if seqs is None else seqs
@@ -389,10 +422,12 @@ def check_path(L, oracle, case, seqs=None, separate=False):
     for b in range(ab.shape[0]):
         assert np.array_equal(got_ab[b, :, : nc[b]], ab[b, :, : nc[b]]), "abstract"
     ub, ub64 = oracle.chunk_score(q, np.nan_to_num(ab), nc, want_f64=True)
-    assert np.array_equal(layer.score[sl].cpu().numpy(), ub), "score"
+    got_ub = layer.score[sl].cpu().numpy()
+    assert np.array_equal(got_ub, ub), explain_score_mismatch(got_ub, ub, ub64)
     sel, cnt, tok, margin = oracle.topk_select(ub, off, nc, case.max_chunks, case.token_budget, case.k_max, want_margin=True)
+    got_sel = layer.sel_idx[sl].cpu().numpy()
+    assert np.array_equal(got_sel, sel), explain_selection_mismatch(got_sel, sel, ub, margin)
     assert np.array_equal(layer.sel_count[sl].cpu().numpy(), cnt), "sel_count"
-    assert np.array_equal(layer.sel_idx[sl].cpu().numpy(), sel), "sel_idx"
     assert np.array_equal(layer.sel_tokens[sl].cpu().numpy(), tok), "sel_tokens"
     out, lse = oracle.sparse_attention(q, K, V, off, sel, cnt)
     err = np.abs(host_f64(layer.out[sl]) - out).max()
@@ -486,8 +521,9 @@ def gpu_select_attend(L, dtype, score, q, K, V, packed, counts, max_chunks, budg
 
 @pytest.mark.parametrize("dtype,G,C", [("bf16", 4, 700), ("bf16", 4, 3000), ("f16", 1, 1500), ("f16", 2, 6000),
                                        ("bf16", 2, 300), ("bf16", 1, 40), ("f16", 4, 2047), ("bf16", 4, 4500), ("bf16", 4, 7000),
-                                       ("bf16", 8, 900), ("f16", 8, 3000), ("bf16", 8, 5000), ("f32", 2, 900)])
-                                       # (the last four: shapes that take two launches)
+                                       ("bf16", 8, 900), ("f16", 8, 3000), ("bf16", 8, 5000), ("f32", 2, 900),
+                                       ("f32", 4, 1300)])
+                                       # (the last five: shapes that take two launches)
 def test_select_attention_one_call(L, oracle, dtype, G, C):
     rng = np.random.default_rng(1000 + C + G)
     B, Hkv, D = 2, 2, 128

@@ -151,6 +151,13 @@ def test_quant_one_call_equals_separate_calls(L, oracle, n_ctx, G):
     assert (one[3] - lay.out).abs().max().item() <= 1e-4
     off, nc = c.chunk_off.cpu(), c.n_chunks.cpu()
     kb, vb, qm = qc.kblob.cpu(), qc.vblob.cpu(), qc.qmeta.cpu()
-    out, lse = oracle.sparse_attention_q(c.q.cpu(), kb, vb, qm, off, one[0].cpu().numpy(), one[1].cpu().numpy())
+    # the kept list of the one-launch kernel against the oracle's own abstract -> score -> selection
+    ab = oracle.abstract_build_q(kb, qm, off, nc)
+    ub = oracle.chunk_score(c.q.cpu(), np.nan_to_num(ab), nc)
+    assert np.array_equal(lay.score.cpu().numpy(), ub), "score"
+    sel, cnt, tok = oracle.topk_select(ub, off, nc, c.max_chunks, c.token_budget, c.k_max)
+    assert np.array_equal(one[0].cpu().numpy(), sel), "sel_idx"
+    assert np.array_equal(one[1].cpu().numpy(), cnt) and np.array_equal(one[2].cpu().numpy(), tok)
+    out, lse = oracle.sparse_attention_q(c.q.cpu(), kb, vb, qm, off, sel, cnt)
     assert np.abs(one[3].cpu().numpy().astype(np.float64) - out).max() <= TOL
     assert np.abs(one[4].cpu().numpy().astype(np.float64) - lse).max() <= 1e-3
