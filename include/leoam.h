@@ -274,6 +274,31 @@ int chunk_select_attention_decode(const leoam_shape* shape, const float* score_u
                                   int32_t* sel_count, int32_t* sel_tokens, float* out, float* lse, void* workspace,
                                   size_t workspace_bytes, void* stream);
 
+/*
+ * chunk_select_attention_decode for callers that cannot allocate device memory or
+ * bring a workspace: code inside a HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation.  Same arguments, outputs and preconditions,
+ * without the workspace: arrival counters and split partials live in a buffer of
+ * LEOAM_STATIC_SCRATCH_BYTES that is part of the library image (every GPU the
+ * library runs on holds its own copy until the process ends).  The call allocates
+ * nothing and frees nothing; it enqueues one small fill kernel (the counters) and
+ * the kernels of chunk_select_attention_decode.  The number of splits is what
+ * leoam_fused_workspace_bytes(shape, token_budget) would give, or fewer if that
+ * exceeds the buffer; a shape whose smallest workspace does not fit (a two-launch
+ * shape with batch * n_q_heads * 520 bytes above the limit, or more than 64 Ki
+ * (sequence, kv head) pairs' counters) returns LEOAM_E_WORKSPACE and enqueues
+ * nothing.  All calls on one GPU share the buffer: calls that may overlap on a
+ * GPU (two streams, two threads) race and must be serialised by the caller.  The
+ * buffer's address is looked up on the first call on each device (not inside a
+ * graph capture: issue one call before capturing).
+ */
+#define LEOAM_STATIC_SCRATCH_BYTES (4u << 20)
+int chunk_select_attention_decode_static(const leoam_shape* shape, const float* score_ub, const void* q, const void* K,
+                                         const void* V, const void* qmeta, const int32_t* chunk_off,
+                                         const int32_t* n_chunks, int32_t max_chunks, int32_t token_budget,
+                                         float softmax_scale, int32_t* sel_idx, int32_t* sel_count, int32_t* sel_tokens,
+                                         float* out, float* lse, void* stream);
+
 /* Bytes of workspace chunk_select_attention_decode wants when at most
  * `max_tokens` tokens are kept per (b,h) (<= 0: n_ctx).  0 on a bad shape. */
 size_t leoam_fused_workspace_bytes(const leoam_shape* shape, int32_t max_tokens);

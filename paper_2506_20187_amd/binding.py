@@ -54,6 +54,8 @@ def _load() -> ctypes.CDLL:
     lib.sparse_chunk_attention_decode.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, sz, vp]
     lib.chunk_select_attention_decode.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_float, vp, vp, vp,
                                                   vp, vp, vp, sz, vp]
+    lib.chunk_select_attention_decode_static.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_float, vp, vp,
+                                                         vp, vp, vp, vp]
     lib.kv_chunk_compress.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp]
     lib.chunk_compression_tags.argtypes = [sp, vp, vp, vp, vp, vp]
     lib.leoam_compressed_bytes_bound.argtypes = [sp]
@@ -71,7 +73,8 @@ def _load() -> ctypes.CDLL:
     lib.leoam_status_string.restype = ctypes.c_char_p
     lib.leoam_version.restype = ctypes.c_int
     for name in ("kv_chunk_abstract_build", "chunk_score", "chunk_score_pin", "chunk_topk_select", "sparse_chunk_attention_decode",
-                 "chunk_select_attention_decode", "kv_chunk_abstract_append", "chunk_tree_refine", "kv_chunk_compress", "chunk_compression_tags", "leoam_workspace_init",
+                 "chunk_select_attention_decode", "chunk_select_attention_decode_static", "kv_chunk_abstract_append", "chunk_tree_refine",
+                 "kv_chunk_compress", "chunk_compression_tags", "leoam_workspace_init",
                  "leoam_validate_boundaries", "leoam_copy_probe"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
@@ -80,7 +83,8 @@ def _load() -> ctypes.CDLL:
 _lib = _load()
 
 EXPORTS = ("kv_chunk_abstract_build", "chunk_score", "chunk_score_pin", "chunk_topk_select", "sparse_chunk_attention_decode",
-           "chunk_select_attention_decode", "leoam_fused_workspace_bytes", "leoam_workspace_init",
+           "chunk_select_attention_decode", "chunk_select_attention_decode_static", "leoam_fused_workspace_bytes",
+           "leoam_workspace_init",
            "kv_chunk_abstract_append", "leoam_tree_evaluations", "chunk_tree_refine", "leoam_tree_workspace_bytes",
            "kv_chunk_compress", "chunk_compression_tags", "leoam_compressed_bytes_bound", "leoam_compression_share",
            "leoam_workspace_bytes", "leoam_validate_boundaries", "leoam_copy_probe", "leoam_status_string",
@@ -212,6 +216,20 @@ def chunk_select_attention_decode(shape: Shape, score_ub, q, K, V, chunk_off, n_
                                               ctypes.c_float(softmax_scale), _p(sel_idx), _p(sel_count), _p(sel_tokens),
                                               _p(out), _p(lse), _p(workspace), nbytes, _stream(stream)),
            "chunk_select_attention_decode")
+
+
+STATIC_SCRATCH_BYTES = 4 << 20
+
+
+def chunk_select_attention_decode_static(shape: Shape, score_ub, q, K, V, chunk_off, n_chunks, max_chunks: int,
+                                         token_budget: int, softmax_scale, sel_idx, sel_count, sel_tokens, out, lse,
+                                         stream=None, qmeta=None) -> None:
+    """chunk_select_attention_decode with the library's own static workspace (allocates nothing)."""
+    _check(_lib.chunk_select_attention_decode_static(ctypes.byref(shape), _p(score_ub), _p(q), _p(K), _p(V), _p(qmeta),
+                                                     _p(chunk_off), _p(n_chunks), int(max_chunks), int(token_budget),
+                                                     ctypes.c_float(softmax_scale), _p(sel_idx), _p(sel_count),
+                                                     _p(sel_tokens), _p(out), _p(lse), _stream(stream)),
+           "chunk_select_attention_decode_static")
 
 
 def leoam_fused_workspace_bytes(shape: Shape, max_tokens: int) -> int:

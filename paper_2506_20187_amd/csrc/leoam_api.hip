@@ -1,6 +1,7 @@
 // C ABI of the library (include/leoam.h): argument checks, then kernel launches
 // on the caller's stream.  Nothing here allocates or synchronises, except the
 // debug helper leoam_validate_boundaries.
+#include <mutex>
 #include <vector>
 
 #include "leoam_dev.h"
@@ -24,6 +25,7 @@ hipError_t select_attention_dispatch(const leoam_shape*, const float*, const voi
                                      float*, float*, void*, size_t, hipStream_t);
 size_t select_attention_workspace_bytes(const leoam_shape*, int);
 size_t select_attention_min_workspace_bytes(const leoam_shape*);
+size_t select_attention_counter_bytes(const leoam_shape*);
 hipError_t workspace_zero_dispatch(void*, size_t, hipStream_t);
 size_t tree_workspace_bytes(const leoam_shape*, int);
 hipError_t tree_refine_dispatch(const leoam_shape*, const void*, const void*, const void*, int, int, int, int, int32_t*,
@@ -72,6 +74,29 @@ static int check_shape(const leoam_shape* s) {
 }
 
 static inline int from_hip(hipError_t e) { return e == hipSuccess ? LEOAM_OK : LEOAM_E_HIP; }
+
+// ---- workspace of chunk_select_attention_decode_static ------------------------------------------
+// Device memory that belongs to the library image: every GPU the library runs on holds its own copy
+// until the process ends.  `static_scratch` names the array in DEVICE code only; on the host the
+// name is a stand-in without a device address, so host code asks the runtime for the address once per
+// device (with that device current) and uses that pointer from then on.
+static __device__ __align__(256) unsigned char static_scratch[LEOAM_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+static void* static_scratch_ptr() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(static_scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
 }  // namespace leoam
 
 using namespace leoam;
@@ -214,6 +239,36 @@ int chunk_select_attention_decode(const leoam_shape* shape, const float* score_u
     return from_hip(select_attention_dispatch(shape, score_ub, q, K, V, qmeta, chunk_off, n_chunks, max_chunks,
                                               token_budget, softmax_scale, sel_idx, sel_count, sel_tokens, out, lse,
                                               workspace, workspace_bytes, (hipStream_t)stream));
+}
+
+int chunk_select_attention_decode_static(const leoam_shape* shape, const float* score_ub, const void* q, const void* K,
+                                         const void* V, const void* qmeta, const int32_t* chunk_off,
+                                         const int32_t* n_chunks, int32_t max_chunks, int32_t token_budget,
+                                         float softmax_scale, int32_t* sel_idx, int32_t* sel_count, int32_t* sel_tokens,
+                                         float* out, float* lse, void* stream) {
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!score_ub || !q || !K || !V || !chunk_off || !n_chunks || !sel_idx || !sel_count || !out)
+        return LEOAM_E_INVALID_ARG;
+    if (shape->k_max > attention_max_sel()) return LEOAM_E_UNSUPPORTED;
+    if (shape->kv_dtype == LEOAM_Q8Q4) {
+        if (!qmeta) return LEOAM_E_INVALID_ARG;
+        if (shape->k_max > attention_q_max_sel()) return LEOAM_E_UNSUPPORTED;
+    }
+    // the smallest workspace the call can run with must fit the static buffer
+    if (select_attention_min_workspace_bytes(shape) > (size_t)LEOAM_STATIC_SCRATCH_BYTES) return LEOAM_E_WORKSPACE;
+    void* ws = static_scratch_ptr();
+    if (!ws) return LEOAM_E_HIP;
+    size_t bytes = select_attention_workspace_bytes(shape, token_budget);
+    if (bytes > (size_t)LEOAM_STATIC_SCRATCH_BYTES) bytes = (size_t)LEOAM_STATIC_SCRATCH_BYTES;      // fewer splits
+    // The buffer keeps what the last call on this GPU left, and that call may have had another shape
+    // (its partials where this one's arrival counters lie): the counters are cleared here, by a fill
+    // kernel (a memset node is not safe to record into a HIP graph on this platform).
+    hipError_t e = workspace_zero_dispatch(ws, select_attention_counter_bytes(shape), (hipStream_t)stream);
+    if (e != hipSuccess) return LEOAM_E_HIP;
+    return from_hip(select_attention_dispatch(shape, score_ub, q, K, V, qmeta, chunk_off, n_chunks, max_chunks,
+                                              token_budget, softmax_scale, sel_idx, sel_count, sel_tokens, out, lse, ws,
+                                              bytes, (hipStream_t)stream));
 }
 
 size_t leoam_fused_workspace_bytes(const leoam_shape* shape, int32_t max_tokens) {
