@@ -371,12 +371,24 @@ int chunk_compression_tags(const leoam_shape* shape, const int32_t* n_chunks, co
 double leoam_compression_share(double n_bytes, double ratio, double bandwidth, double t_other, double t_compute,
                                double decompress_rate);
 
+const char* leoam_status_string(int status);
+int leoam_version(void);
+
+/* ------------------------------------------------------------------------
+ * Measuring aids.  Not part of the decode path: two plain streaming kernels of
+ * known size that the benchmark and the profiles compare the path's kernels
+ * with on the same GPU.
+ * ------------------------------------------------------------------------ */
+
 /* Plain device copy of `bytes` bytes (multiple of 16, 16-byte aligned): the
  * known-size kernel that hardware byte counters are scaled against. */
 int leoam_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
 
-const char* leoam_status_string(int status);
-int leoam_version(void);
+/* Reads `bytes` bytes (multiple of 16, 16-byte aligned) and keeps nothing: the
+ * read-only stream whose rate is the measured ceiling the path's HBM-bound
+ * kernels are reported against.  `sink`: 4 writable bytes (device), written
+ * only for one data pattern in 2^64. */
+int leoam_read_probe(const void* src, size_t bytes, void* sink, void* stream);
 
 #ifdef __cplusplus
 }

@@ -11,7 +11,7 @@ from .binding import (  # noqa: F401
     leoam_workspace_bytes,
     leoam_fused_workspace_bytes, leoam_workspace_init, kv_chunk_abstract_append, leoam_tree_evaluations, chunk_tree_refine,
     leoam_tree_workspace_bytes, kv_chunk_compress, chunk_compression_tags, leoam_compressed_bytes_bound, leoam_compression_share,
-    leoam_validate_boundaries, leoam_copy_probe,
+    leoam_validate_boundaries, leoam_copy_probe, leoam_read_probe,
     status_string, version, default_scale,
 )
-from .layer import DecodeLayer  # noqa: F401
+from .layer import DecodeLayer, DecodeStack  # noqa: F401

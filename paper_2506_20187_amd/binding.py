@@ -69,13 +69,14 @@ def _load() -> ctypes.CDLL:
     lib.leoam_workspace_init.argtypes = [vp, sz, vp]
     lib.leoam_validate_boundaries.argtypes = [sp, vp, vp, vp]
     lib.leoam_copy_probe.argtypes = [vp, vp, sz, vp]
+    lib.leoam_read_probe.argtypes = [vp, sz, vp, vp]
     lib.leoam_status_string.argtypes = [ctypes.c_int]
     lib.leoam_status_string.restype = ctypes.c_char_p
     lib.leoam_version.restype = ctypes.c_int
     for name in ("kv_chunk_abstract_build", "chunk_score", "chunk_score_pin", "chunk_topk_select", "sparse_chunk_attention_decode",
                  "chunk_select_attention_decode", "chunk_select_attention_decode_static", "kv_chunk_abstract_append", "chunk_tree_refine",
                  "kv_chunk_compress", "chunk_compression_tags", "leoam_workspace_init",
-                 "leoam_validate_boundaries", "leoam_copy_probe"):
+                 "leoam_validate_boundaries", "leoam_copy_probe", "leoam_read_probe"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -87,7 +88,7 @@ EXPORTS = ("kv_chunk_abstract_build", "chunk_score", "chunk_score_pin", "chunk_t
            "leoam_workspace_init",
            "kv_chunk_abstract_append", "leoam_tree_evaluations", "chunk_tree_refine", "leoam_tree_workspace_bytes",
            "kv_chunk_compress", "chunk_compression_tags", "leoam_compressed_bytes_bound", "leoam_compression_share",
-           "leoam_workspace_bytes", "leoam_validate_boundaries", "leoam_copy_probe", "leoam_status_string",
+           "leoam_workspace_bytes", "leoam_validate_boundaries", "leoam_copy_probe", "leoam_read_probe", "leoam_status_string",
            "leoam_version")
 
 
@@ -251,6 +252,10 @@ def leoam_validate_boundaries(shape: Shape, chunk_off, n_chunks, stream=None) ->
 
 def leoam_copy_probe(dst, src, nbytes: int, stream=None) -> None:
     _check(_lib.leoam_copy_probe(_p(dst), _p(src), int(nbytes), _stream(stream)), "leoam_copy_probe")
+
+
+def leoam_read_probe(src, nbytes: int, sink, stream=None) -> None:
+    _check(_lib.leoam_read_probe(_p(src), int(nbytes), _p(sink), _stream(stream)), "leoam_read_probe")
 
 
 def default_scale(head_dim: int) -> float:
