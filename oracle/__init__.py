@@ -359,6 +359,30 @@ def chunk_compress(K, V, chunk_off, n_chunks, four_bit):
     return kblob[:n].copy(), vblob[:n].copy(), qm
 
 
+def chunk_recompress(K, V, chunk_off, n_chunks, four_old, four_new, kblob, vblob, qmeta, used_bytes: int):
+    """A store built under the tags `four_old` brought to `four_new` by re-encoding only the chunks whose
+    tag changed (see leoam_oracle.c).  kblob / vblob: uint8 arrays of the full capacity (modified in place,
+    as is qmeta).  Returns (status, used_bytes, chunks re-encoded); status 1 = no room, nothing changed."""
+    ka, tag = _as_numpy(K)
+    va, tag_v = _as_numpy(V)
+    assert tag == tag_v and ka.shape == va.shape
+    B, Hkv, N, D = ka.shape
+    off, nc = _i32(chunk_off), _i32(n_chunks)
+    c_max = off.shape[1] - 1
+    _check_boundaries(off, nc, N)
+    fo = np.ascontiguousarray(np.asarray(four_old).astype(np.uint8))
+    fn = np.ascontiguousarray(np.asarray(four_new).astype(np.uint8))
+    assert fo.shape == (B, c_max) and fn.shape == (B, c_max)
+    assert kblob.dtype == np.uint8 and vblob.dtype == np.uint8 and kblob.flags.c_contiguous and vblob.flags.c_contiguous
+    assert kblob.shape == vblob.shape and qmeta.dtype == QCHUNK_DTYPE and qmeta.shape == (B, Hkv, c_max)
+    used = np.asarray([used_bytes], dtype=np.int64)
+    changed = np.zeros(1, dtype=np.int64)
+    rc = _load().orc_chunk_recompress(tag, B, Hkv, N, D, _ptr(ka), _ptr(va), _ptr(off), _ptr(nc), c_max, _ptr(fo),
+                                      _ptr(fn), _ptr(kblob), _ptr(vblob), ctypes.c_int64(kblob.size), _ptr(qmeta),
+                                      _ptr(used), _ptr(changed))
+    return int(rc), int(used[0]), int(changed[0])
+
+
 def compression_share(n_bytes: float, ratio: float, bandwidth: float, t_other: float, t_compute: float,
                       decompress_rate: float) -> float:
     """Sec. 4.4: the share theta of the transmitted bytes that is sent compressed (see leoam_oracle.c)."""

@@ -18,6 +18,7 @@
  *                        most important share of the cache).
  *   orc_sparse_attention Sec. 2.1 Eq. (1), restricted to the selected tokens.
  *   orc_chunk_compress   Sec. 4.4 / 6.1: the compressed (8-bit / 4-bit) store.
+ *   orc_chunk_recompress the same store brought to a new set of 4-bit tags, chunk by chunk.
  *   orc_compression_share Sec. 4.4: the share of the data that is sent compressed.
  *
  * All floating-point work is done in double.  Stored fp32/fp16/bf16 inputs
@@ -422,15 +423,54 @@ int orc_dequant(int B, int Hkv, int N, int D, const uint8_t *blob, const orc_qch
     return 0;
 }
 
+/* One chunk of one (b,h) into the compressed store at byte `pos` of both blobs (Sec. 4.4 / 6.1):
+ * per tensor, zero = min, scale = (max - min) / levels, code = round-half-even((x - zero) / scale)
+ * kept inside 0..levels, levels = 15 (`four`) or 255; every operation that decides a code is one
+ * float (binary32) operation.  Writes the record and rows * row bytes per blob, then zeros up to the
+ * next multiple of 16.  Returns the bytes taken per blob. */
+static int64_t orc_encode_chunk(int dtype, int N, int D, const void *K, const void *V, size_t bh, int t0, int t1,
+                                int four, uint8_t *kblob, uint8_t *vblob, int64_t pos, orc_qchunk *m) {
+    float levels = four ? 15.0f : 255.0f;
+    int64_t row = four ? D / 2 : D, rows = t1 - t0;
+    m->byte_off = pos;
+    m->bits = four ? 4 : 8;
+    for (int use_v = 0; use_v < 2; ++use_v) {
+        const void *X = use_v ? V : K;
+        uint8_t *blob = use_v ? vblob : kblob;
+        float lo = INFINITY, hi = -INFINITY;
+        for (int t = t0; t < t1; ++t)
+            for (int d = 0; d < D; ++d) {
+                float x = (float)widen(X, dtype, (bh * N + t) * D + d);
+                if (x < lo) lo = x;
+                if (x > hi) hi = x;
+            }
+        float range = hi - lo;
+        float scale = range / levels;
+        if (use_v) { m->scale_v = scale; m->zero_v = lo; } else { m->scale_k = scale; m->zero_k = lo; }
+        for (int t = t0; t < t1; ++t)
+            for (int d = 0; d < D; ++d) {
+                float x = (float)widen(X, dtype, (bh * N + t) * D + d);
+                int code = 0;
+                if (scale > 0.0f) {
+                    float diff = x - lo;
+                    float r = rintf(diff / scale);
+                    if (r < 0.0f) r = 0.0f;
+                    if (r > levels) r = levels;
+                    code = (int)r;
+                }
+                uint8_t *dst = blob + pos + (int64_t)(t - t0) * row;
+                if (!four) dst[d] = (uint8_t)code;
+                else if (d & 1) dst[d / 2] = (uint8_t)(dst[d / 2] | (code << 4));
+                else dst[d / 2] = (uint8_t)code;
+            }
+    }
+    int64_t bytes = (rows * row + 15) / 16 * 16;
+    for (int64_t i = rows * row; i < bytes; ++i) kblob[pos + i] = vblob[pos + i] = 0;
+    return bytes;
+}
+
 /* Sec. 4.4 "Dynamic KV compression" / Sec. 6.1 (KV compressed to INT4): builds the
- * compressed store from the 16-bit (or fp32) cache.  Per (b, h, chunk, tensor):
- *     zero  = min over the chunk's elements,  scale = (max - min) / levels,
- *     code  = round-half-even((x - zero) / scale), kept inside 0..levels,
- * levels = 255 (8-bit chunk) or 15 (4-bit chunk; two codes per byte, even channel
- * in the low nibble); scale == 0 (all elements equal) gives code 0 everywhere.
- * The decision that yields an integer is taken in float (binary32): max - min,
- * the division by levels, x - zero and the division by scale are single float
- * operations, each correctly rounded - the precision of the stored scale and zero.
+ * compressed store from the 16-bit (or fp32) cache, every chunk by orc_encode_chunk.
  * Layout: the chunks of a (b,h) follow each other, each padded to a multiple of
  * 16 bytes; the (b,h) pairs follow each other; K and V blobs use the same
  * offsets.  Records of chunks >= n_chunks[b] are zero.  Returns 1 if the blobs
@@ -456,49 +496,58 @@ int orc_chunk_compress(int dtype, int B, int Hkv, int N, int D, const void *K, c
         const int32_t *off = chunk_off + (size_t)b * (c_max + 1);
         for (int h = 0; h < Hkv; ++h) {
             size_t bh = (size_t)b * Hkv + h;
+            for (int c = 0; c < n_chunks[b]; ++c)
+                pos += orc_encode_chunk(dtype, N, D, K, V, bh, off[c], off[c + 1], four_bit[(size_t)b * c_max + c] != 0,
+                                        kblob, vblob, pos, qmeta + bh * c_max + c);
+        }
+    }
+    return 0;
+}
+
+/* Sec. 4.4: the compressed share changes from step to step (theta follows the measured times, and which
+ * chunks are unimportant follows the scores), so a store built under the tags `four_old` is brought to
+ * the tags `four_new` by re-encoding ONLY the chunks whose tag changed, from the uncompressed cache:
+ *   8-bit -> 4-bit  the chunk is encoded again where it lies (it takes half of its old room),
+ *   4-bit -> 8-bit  the chunk moves to fresh room at the end of the used part of the blobs; these
+ *                   chunks are placed in (b, h, chunk) order starting at *used_bytes.
+ * Every other byte of the blobs and every other record stays as it is.  *used_bytes grows by the room
+ * the moved chunks take.  If that would exceed blob_bytes nothing is changed and 1 is returned (the
+ * caller then rebuilds the store with orc_chunk_compress, which also closes the holes).
+ * n_changed (nullable): chunks re-encoded, counted per (b, h, chunk). */
+int orc_chunk_recompress(int dtype, int B, int Hkv, int N, int D, const void *K, const void *V,
+                         const int32_t *chunk_off, const int32_t *n_chunks, int c_max, const uint8_t *four_old,
+                         const uint8_t *four_new, uint8_t *kblob, uint8_t *vblob, int64_t blob_bytes,
+                         orc_qchunk *qmeta, int64_t *used_bytes, int64_t *n_changed) {
+    int64_t grow = 0, changed = 0;
+    for (int b = 0; b < B; ++b) {
+        const int32_t *off = chunk_off + (size_t)b * (c_max + 1);
+        for (int c = 0; c < n_chunks[b]; ++c) {
+            int was = four_old[(size_t)b * c_max + c] != 0, is = four_new[(size_t)b * c_max + c] != 0;
+            if (was && !is) grow += (((int64_t)(off[c + 1] - off[c]) * D + 15) / 16 * 16) * Hkv;
+        }
+    }
+    if (n_changed) *n_changed = 0;
+    if (*used_bytes + grow > blob_bytes) return 1;
+    int64_t pos = *used_bytes;
+    for (int b = 0; b < B; ++b) {
+        const int32_t *off = chunk_off + (size_t)b * (c_max + 1);
+        for (int h = 0; h < Hkv; ++h) {
+            size_t bh = (size_t)b * Hkv + h;
             for (int c = 0; c < n_chunks[b]; ++c) {
+                int was = four_old[(size_t)b * c_max + c] != 0, is = four_new[(size_t)b * c_max + c] != 0;
                 orc_qchunk *m = qmeta + bh * c_max + c;
-                int four = four_bit[(size_t)b * c_max + c] != 0;
-                float levels = four ? 15.0f : 255.0f;
-                int64_t row = four ? D / 2 : D, rows = off[c + 1] - off[c];
-                m->byte_off = pos;
-                m->bits = four ? 4 : 8;
-                for (int use_v = 0; use_v < 2; ++use_v) {
-                    const void *X = use_v ? V : K;
-                    uint8_t *blob = use_v ? vblob : kblob;
-                    float lo = INFINITY, hi = -INFINITY;
-                    for (int t = off[c]; t < off[c + 1]; ++t)
-                        for (int d = 0; d < D; ++d) {
-                            float x = (float)widen(X, dtype, (bh * N + t) * D + d);
-                            if (x < lo) lo = x;
-                            if (x > hi) hi = x;
-                        }
-                    float range = hi - lo;
-                    float scale = range / levels;
-                    if (use_v) { m->scale_v = scale; m->zero_v = lo; } else { m->scale_k = scale; m->zero_k = lo; }
-                    for (int t = off[c]; t < off[c + 1]; ++t)
-                        for (int d = 0; d < D; ++d) {
-                            float x = (float)widen(X, dtype, (bh * N + t) * D + d);
-                            int code = 0;
-                            if (scale > 0.0f) {
-                                float diff = x - lo;
-                                float r = rintf(diff / scale);
-                                if (r < 0.0f) r = 0.0f;
-                                if (r > levels) r = levels;
-                                code = (int)r;
-                            }
-                            uint8_t *dst = blob + pos + (int64_t)(t - off[c]) * row;
-                            if (!four) dst[d] = (uint8_t)code;
-                            else if (d & 1) dst[d / 2] = (uint8_t)(dst[d / 2] | (code << 4));
-                            else dst[d / 2] = (uint8_t)code;
-                        }
+                if (was == is) continue;
+                ++changed;
+                if (is) {
+                    orc_encode_chunk(dtype, N, D, K, V, bh, off[c], off[c + 1], 1, kblob, vblob, m->byte_off, m);
+                } else {
+                    pos += orc_encode_chunk(dtype, N, D, K, V, bh, off[c], off[c + 1], 0, kblob, vblob, pos, m);
                 }
-                int64_t bytes = (rows * row + 15) / 16 * 16;
-                for (int64_t i = rows * row; i < bytes; ++i) kblob[pos + i] = vblob[pos + i] = 0;
-                pos += bytes;
             }
         }
     }
+    *used_bytes = pos;
+    if (n_changed) *n_changed = changed;
     return 0;
 }
 

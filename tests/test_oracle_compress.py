@@ -236,3 +236,111 @@ def test_compression_tags_follow_the_selection():
     # entries past sel_count are ignored
     sel2[0, 0, 3] = 7
     assert np.array_equal(oracle.compression_tags(np.array([n], dtype=np.int32), sel2, np.array([[3, 2]], dtype=np.int32), c_max), t2)
+
+
+# ---------------------------------------------------------------------------
+# oracle.chunk_recompress: a store brought to new 4-bit tags chunk by chunk
+# ---------------------------------------------------------------------------
+def live_intervals(qm, packed, counts):
+    """[start, end) of every chunk's rows in a blob, from its record"""
+    out = []
+    B, Hkv, _ = qm.shape
+    for b in range(B):
+        for h in range(Hkv):
+            for c in range(counts[b]):
+                rec = qm[b, h, c]
+                rows = int(packed[b, c + 1] - packed[b, c])
+                out.append((int(rec["byte_off"]), int(rec["byte_off"]) + rows * (64 if rec["bits"] == 4 else 128), (b, h, c)))
+    return out
+
+
+def recompress_case(seed, dtype=torch.float16, share_old=0.5, share_new=0.5):
+    K, V, packed, counts, c_max, fb_old = random_case(seed, dtype, B=3, Hkv=2, N=200, share=share_old)
+    rng = np.random.default_rng(seed + 1000)
+    fb_new = rng.random(fb_old.shape) < share_new
+    kb, vb, qm = oracle.chunk_compress(K, V, packed, counts, fb_old)
+    used = kb.size
+    cap = K.shape[0] * K.shape[1] * (K.shape[2] * 128 + 16 * c_max) * 2        # room for every chunk to move once
+    kbig, vbig = np.full(cap, 0xEE, dtype=np.uint8), np.full(cap, 0xEE, dtype=np.uint8)
+    kbig[:used], vbig[:used] = kb, vb
+    return K, V, packed, counts, c_max, fb_old, fb_new, kbig, vbig, qm, used
+
+
+@pytest.mark.parametrize("seed,share_old,share_new", [(1, 0.5, 0.5), (2, 0.0, 1.0), (3, 1.0, 0.0), (4, 0.3, 0.8), (5, 0.8, 0.2)])
+def test_recompress_equals_a_full_compression_under_the_new_tags(seed, share_old, share_new):
+    K, V, packed, counts, c_max, fb_old, fb_new, kb, vb, qm, used = recompress_case(seed, share_old=share_old,
+                                                                                  share_new=share_new)
+    kb0, vb0, qm0 = kb.copy(), vb.copy(), qm.copy()
+    rc, used_new, changed = oracle.chunk_recompress(K, V, packed, counts, fb_old, fb_new, kb, vb, qm, used)
+    assert rc == 0
+    # the store now decodes to exactly what a full compression under the new tags decodes to, chunk by chunk:
+    # same format, same scale and zero, same codes (byte offsets may differ: moved chunks, holes)
+    kf, vf, qf = oracle.chunk_compress(K, V, packed, counts, fb_new)
+    N = K.shape[2]
+    for blob, full, which in ((kb, kf, "k"), (vb, vf, "v")):
+        got_val, got_codes = decode(blob, qm, packed, counts, N, which)
+        want_val, want_codes = decode(full, qf, packed, counts, N, which)
+        assert np.array_equal(got_codes, want_codes) and np.array_equal(got_val, want_val)
+    for b in range(qm.shape[0]):
+        n = counts[b]
+        for f in ("bits", "scale_k", "zero_k", "scale_v", "zero_v"):
+            assert np.array_equal(qm[b, :, :n][f], qf[b, :, :n][f]), f
+    # only chunks whose tag changed were touched: the others keep their record, and their bytes are the old bytes
+    n_diff = 0
+    for b in range(qm.shape[0]):
+        for c in range(counts[b]):
+            same = bool(fb_old[b, c]) == bool(fb_new[b, c])
+            n_diff += 0 if same else qm.shape[1]
+            for h in range(qm.shape[1]):
+                if same:
+                    assert qm[b, h, c] == qm0[b, h, c]
+                    o, rows = int(qm0[b, h, c]["byte_off"]), int(packed[b, c + 1] - packed[b, c])
+                    nbytes = rows * (64 if fb_old[b, c] else 128)
+                    assert np.array_equal(kb[o:o + nbytes], kb0[o:o + nbytes]) and np.array_equal(vb[o:o + nbytes], vb0[o:o + nbytes])
+                elif fb_new[b, c]:
+                    assert qm[b, h, c]["byte_off"] == qm0[b, h, c]["byte_off"]       # shrinks where it lies
+                else:
+                    assert qm[b, h, c]["byte_off"] >= used                            # moves to fresh room
+    assert changed == n_diff
+    # the live chunks do not overlap (brute force over all pairs), lie below the new high-water mark, and the
+    # mark grew by exactly the room of the moved chunks; nothing past it was written
+    iv = sorted(live_intervals(qm, packed, counts))
+    for (s0, e0, _), (s1, e1, _) in zip(iv, iv[1:]):
+        assert e0 <= s1
+    assert iv[-1][1] <= used_new
+    grow = sum(((int(packed[b, c + 1] - packed[b, c]) * 128 + 15) // 16 * 16) * qm.shape[1]
+               for b in range(qm.shape[0]) for c in range(counts[b]) if fb_old[b, c] and not fb_new[b, c])
+    assert used_new == used + grow
+    assert np.all(kb[used_new:] == 0xEE) and np.all(vb[used_new:] == 0xEE)
+    # moved chunks follow each other in (b, h, chunk) order from the old mark
+    moved = [(int(qm[b, h, c]["byte_off"]), (b, h, c)) for b in range(qm.shape[0]) for h in range(qm.shape[1])
+             for c in range(counts[b]) if fb_old[b, c] and not fb_new[b, c]]
+    assert [k for _, k in sorted(moved)] == [k for _, k in moved]
+    if moved:
+        assert moved[0][0] == used
+
+
+def test_recompress_with_the_same_tags_changes_nothing_and_back_and_forth_returns_the_codes():
+    K, V, packed, counts, c_max, fb_old, fb_new, kb, vb, qm, used = recompress_case(9)
+    kb0, vb0, qm0 = kb.copy(), vb.copy(), qm.copy()
+    rc, used1, changed = oracle.chunk_recompress(K, V, packed, counts, fb_old, fb_old, kb, vb, qm, used)
+    assert (rc, used1, changed) == (0, used, 0)
+    assert np.array_equal(kb, kb0) and np.array_equal(vb, vb0) and np.array_equal(qm, qm0)
+    # there and back: the codes, scales and zeros are those of the first store again
+    rc, used2, _ = oracle.chunk_recompress(K, V, packed, counts, fb_old, fb_new, kb, vb, qm, used)
+    rc2, used3, _ = oracle.chunk_recompress(K, V, packed, counts, fb_new, fb_old, kb, vb, qm, used2)
+    assert rc == 0 and rc2 == 0 and used3 >= used2 >= used
+    N = K.shape[2]
+    for blob, blob0, which in ((kb, kb0, "k"), (vb, vb0, "v")):
+        _, codes = decode(blob, qm, packed, counts, N, which)
+        _, codes0 = decode(blob0, qm0, packed, counts, N, which)
+        assert np.array_equal(codes, codes0)
+
+
+def test_recompress_without_room_changes_nothing():
+    K, V, packed, counts, c_max, fb_old, fb_new, kb, vb, qm, used = recompress_case(12, share_old=1.0, share_new=0.0)
+    tight_k, tight_v = kb[: used + 64].copy(), vb[: used + 64].copy()       # room for 64 more bytes only
+    qm0 = qm.copy()
+    rc, used1, changed = oracle.chunk_recompress(K, V, packed, counts, fb_old, fb_new, tight_k, tight_v, qm, used)
+    assert rc == 1 and used1 == used and changed == 0
+    assert np.array_equal(tight_k, kb[: used + 64]) and np.array_equal(tight_v, vb[: used + 64]) and np.array_equal(qm, qm0)
