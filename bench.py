@@ -139,7 +139,7 @@ def cpu_model():
     return "unknown"
 
 
-def compress_store(B, torch, case, four_bit, timed):
+def compress_store(B, torch, case, four_bit, timed, retag=False):
     """kv_chunk_compress of one layer (Sec. 4.4 / 6.1).  Returns the blobs cut to the used bytes, the records and,
     if `timed`, the timing record: source bytes read plus code bytes written per second."""
     import numpy as np
@@ -160,6 +160,20 @@ def compress_store(B, torch, case, four_bit, timed):
         src = 2 * case.K.numel() * case.K.element_size()
         rec = {"us_per_layer": round(ms * 1e3, 1), "source_bytes": src, "code_bytes": 2 * n, "four_bit_share_of_chunks": 0.5,
                "GBps_read_plus_written": round((src + 2 * n) / (ms * 1e-3) / 1e9, 1)}
+        if retag:
+            # the live store brought to tags that differ in a tenth of the chunks (kv_chunk_recompress):
+            # only those chunks are read and encoded again
+            flip = np.random.default_rng(1).random(four_bit.shape) < 0.1
+            new_tags = torch.from_numpy(np.ascontiguousarray(np.logical_xor(four_bit, flip)).astype(np.uint8)).cuda()
+            info = torch.zeros(3, dtype=torch.int64, device="cuda")
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            B.kv_chunk_recompress(shape, case.K, case.V, case.chunk_off, case.n_chunks, fbd, new_tags, kb, vb, qm, used, info)
+            b.record()
+            torch.cuda.synchronize()
+            rec["recompress_tenth_of_the_tags"] = {"us": round(a.elapsed_time(b) * 1e3, 1), "chunks_encoded_again": int(info[1]),
+                                                   "refused": int(info[0]), "fresh_room_bytes": int(info[2])}
     else:
         call()
         torch.cuda.synchronize()
@@ -204,8 +218,7 @@ def main():
             lay = L.DecodeLayer(kblob, vblob, case.chunk_off, case.n_chunks, case.hq, case.k_max,
                                 case.max_chunks, case.token_budget, qmeta=qmeta, n_kv_heads=case.hkv,
                                 n_ctx=case.n_ctx)
-            case.K = case.V = None          # only the compressed store stays resident
-            tags.append(fb)
+            tags.append(fb)                 # (the 16-bit cache stays resident too: the policy section below compares with it)
         else:
             case = gen.make_case(args.workload, layer=lid, device="cuda")
             lay = L.DecodeLayer(case.K, case.V, case.chunk_off, case.n_chunks, case.hq, case.k_max, case.max_chunks,
@@ -372,7 +385,7 @@ def main():
     if not quant and cfg["dtype"] in ("f16", "bf16"):
         case = cases[0]
         fb = gen.tag_four_bit(case.chunk_off.cpu().numpy(), case.n_chunks.cpu().numpy(), case.extra["heavy"], 0.5)
-        compress = compress_store(B, torch, case, fb, timed=True)[3]
+        compress = compress_store(B, torch, case, fb, timed=True, retag=True)[3]
 
     # ---- plain streams of known size: what this machine reads, and copies, per second -------------
     # (4 GiB: far beyond the last-level cache; the read-only rate is the measured ceiling the
@@ -398,6 +411,77 @@ def main():
     copy_ms = time_calls(lambda: B.leoam_copy_probe(dst, src, nbytes), 10, torch)
     copy_gbs = 2 * nbytes / (copy_ms * 1e-3) / 1e9
     del src, dst
+    # ---- dynamic compression policy (Sec. 4.4) from rates measured on this GPU, compressed workload only ----
+    # The condition T0 + D (1 - theta + theta delta) / B <= Tc + D theta / R with: D = the kept K/V of a layer-step at
+    # 16 bits; delta = 0.25 (16-bit -> 4-bit, Sec. 6.1); B = the rate at which a plain copy moves source bytes through
+    # HBM (all tiers are in HBM here, so a copy is what a "transfer" is); T0 = the measured evaluation time
+    # (chunk_score + chunk_topk_select); Tc = the measured attention over the same kept tokens at 16 bits; R from the
+    # measured difference between the compressed-store attention and what its bytes alone would cost at the 16-bit
+    # kernel's rate (no measurable difference: decompression is hidden, R is reported as null and taken as 1e15).
+    policy = None
+    if quant:
+        bw = copy_gbs / 2 * 1e9
+        policy = {"bandwidth_GBps": round(bw / 1e9, 1), "ratio": 0.25, "layers": {}}
+        for lid, lay, case, p in zip(layer_ids, layers, cases, parts):
+            dt16 = case.K.dtype
+            s16 = B.make_shape(case.batch, case.hq, case.hkv, 128, case.n_ctx, lay.shape.c_max, lay.shape.k_max, dt16)
+            q16 = case.q.to(dt16)
+            ws16 = torch.empty((B.leoam_workspace_bytes(s16, lay.token_budget) + 15) // 16 * 16, dtype=torch.uint8, device="cuda")
+            out16 = torch.empty_like(lay.out)
+            t16 = time_calls(lambda: B.sparse_chunk_attention_decode(s16, q16, case.K, case.V, lay.chunk_off, lay.n_chunks,
+                                                                     lay.sel_idx, lay.sel_count, lay.scale, out16, None, ws16),
+                             30, torch) * 1e-3
+            tq = time_calls(lambda: B.sparse_chunk_attention_decode(lay.shape, case.q, lay.K, lay.V, lay.chunk_off,
+                                                                    lay.n_chunks, lay.sel_idx, lay.sel_count, lay.scale,
+                                                                    lay.out, lay.lse, lay.att_workspace, None, lay.qmeta),
+                            30, torch) * 1e-3
+            t_eval = time_calls(lambda: (B.chunk_score(lay.shape, case.q, lay.abstract, lay.n_chunks, lay.score, None),
+                                         B.chunk_topk_select(lay.shape, lay.score, lay.chunk_off, lay.n_chunks, lay.max_chunks,
+                                                             lay.token_budget, lay.sel_idx, lay.sel_count, lay.sel_tokens)),
+                                30, torch) * 1e-3
+            d16 = p["kept_tokens"] * 2 * 128 * 2
+            extra = tq - t16 * p["kv"] / d16
+            rate = d16 / extra if extra > 0 else None
+            theta = B.leoam_compression_share(d16, 0.25, bw, t_eval, t16, rate or 1e15)
+            policy["layers"][str(lid)] = {"D_bytes_16bit": d16, "stored_bytes": p["kv"], "T0_eval_us": round(t_eval * 1e6, 2),
+                                          "Tc_attention_16bit_us": round(t16 * 1e6, 2),
+                                          "attention_compressed_us": round(tq * 1e6, 2),
+                                          "decompress_rate_GBps": None if rate is None else round(rate / 1e9, 1),
+                                          "theta": round(theta, 4)}
+            del ws16, out16
+        # the policy applied to the first layer: tags from the selection with a budget of (1 - theta) of the context
+        # (chunk_compression_tags), then the live store brought to them by kv_chunk_recompress
+        lay, case, fb0 = layers[0], cases[0], tags[0]
+        theta = policy["layers"][str(layer_ids[0])]["theta"]
+        shape16 = B.make_shape(case.batch, case.hq, case.hkv, 128, case.n_ctx, lay.shape.c_max, 1, case.K.dtype)
+        cap = 2 * B.leoam_compressed_bytes_bound(shape16)
+        kb2 = torch.empty(cap, dtype=torch.uint8, device="cuda")
+        vb2 = torch.empty(cap, dtype=torch.uint8, device="cuda")
+        qm2 = torch.empty_like(lay.qmeta)
+        used = torch.zeros(1, dtype=torch.int64, device="cuda")
+        info = torch.zeros(3, dtype=torch.int64, device="cuda")
+        fb_old = torch.from_numpy(np.ascontiguousarray(fb0).astype(np.uint8)).cuda()
+        B.kv_chunk_compress(shape16, case.K, case.V, case.chunk_off, case.n_chunks, fb_old, kb2, vb2, qm2, used)
+        sel_shape = B.make_shape(case.batch, case.hq, case.hkv, 128, case.n_ctx, lay.shape.c_max, lay.shape.c_max, L.binding.Q8Q4)
+        sel2 = torch.empty(case.batch, case.hkv, lay.shape.c_max, dtype=torch.int32, device="cuda")
+        cnt2 = torch.empty(case.batch, case.hkv, dtype=torch.int32, device="cuda")
+        B.chunk_topk_select(sel_shape, lay.score, lay.chunk_off, lay.n_chunks, 0, max(1, int((1.0 - theta) * case.n_ctx)), sel2,
+                            cnt2, None)
+        fb_new = torch.empty_like(fb_old)
+        B.chunk_compression_tags(sel_shape, lay.n_chunks, sel2, cnt2, fb_new)
+        torch.cuda.synchronize()
+        t_a, t_b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t_a.record()
+        B.kv_chunk_recompress(shape16, case.K, case.V, case.chunk_off, case.n_chunks, fb_old, fb_new, kb2, vb2, qm2, used, info)
+        t_b.record()
+        torch.cuda.synchronize()
+        nvalid = int(case.n_chunks.sum())
+        policy["retag_first_layer"] = {"theta": theta, "four_bit_share_of_chunks_before": round(float(fb_old.sum()) / nvalid, 4),
+                                       "four_bit_share_of_chunks_after": round(float(fb_new.sum()) / nvalid, 4),
+                                       "chunks_encoded_again": int(info[1]), "of_chunks": nvalid * case.hkv,
+                                       "refused": int(info[0]), "fresh_room_bytes": int(info[2]),
+                                       "kv_chunk_recompress_us": round(t_a.elapsed_time(t_b) * 1e3, 1)}
+        del kb2, vb2, qm2, sel2
     e_med, e_p10, e_p90 = percentiles(eager_ms)
     g_med, g_p10, g_p90 = percentiles(graph_ms)
 
@@ -462,6 +546,7 @@ def main():
         "abstract_append_us": None if append_us is None else round(append_us, 2),
         "tree_refine": tree,
         "compress": compress,
+        "compression_policy": policy,
         "read_probe_GBps": round(read_gbs, 1),
         "read_probe_GBps_at_launch_size": round(read_small_gbs, 1),
         "copy_probe_GBps": round(copy_gbs, 1),

@@ -344,6 +344,31 @@ int kv_chunk_compress(const leoam_shape* shape, const void* K, const void* V, co
 size_t leoam_compressed_bytes_bound(const leoam_shape* shape);
 
 /*
+ * Sec. 4.4: the compressed share is chosen dynamically (theta follows the measured
+ * times, and which chunks are unimportant follows the scores), so the tags of a
+ * store change while it is in use.  Brings a store that was written under the
+ * tags four_bit_old (by kv_chunk_compress or by earlier calls of this function)
+ * to the tags four_bit_new by encoding again, from the uncompressed cache and as
+ * kv_chunk_compress does, ONLY the chunks whose tag changed:
+ *   8-bit -> 4-bit   the chunk is encoded where it lies (half of its old room);
+ *   4-bit -> 8-bit   the chunk moves to fresh room behind the used part of the
+ *                    blobs; moved chunks are placed in (b, h, chunk) order from
+ *                    *used_bytes on, which grows by the room they take.
+ * Every other byte of the blobs and every other record stays as it is (records
+ * carry each chunk's own offset, so the kernels that read the store need no
+ * particular order; the room a moved chunk leaves stays unused until the next
+ * kv_chunk_compress).  Afterwards every chunk decodes to exactly what
+ * kv_chunk_compress under four_bit_new would store.
+ *   used_bytes  device int64, in / out: bytes in use of each blob (kv_chunk_compress's total_bytes)
+ *   info        device int64[3], out: {1 if the fresh room did not fit blob_bytes - then nothing
+ *               was changed -, chunks encoded again counted per (b, h, chunk), bytes of fresh room}
+ * shape->kv_dtype is the dtype of K and V (LEOAM_F16 or LEOAM_BF16), as for kv_chunk_compress.
+ */
+int kv_chunk_recompress(const leoam_shape* shape, const void* K, const void* V, const int32_t* chunk_off,
+                        const int32_t* n_chunks, const uint8_t* four_bit_old, const uint8_t* four_bit_new, void* kblob,
+                        void* vblob, size_t blob_bytes, void* qmeta, int64_t* used_bytes, int64_t* info, void* stream);
+
+/*
  * Sec. 4.4 (the compressed share) with Sec. 4.2 (chunks ordered by importance): the
  * paper fixes the size of the share, not which data it holds.  Here a chunk is
  * tagged 4-bit unless some kv head of its sequence keeps it in the selection

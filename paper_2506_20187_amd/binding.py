@@ -57,6 +57,7 @@ def _load() -> ctypes.CDLL:
     lib.chunk_select_attention_decode_static.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_float, vp, vp,
                                                          vp, vp, vp, vp]
     lib.kv_chunk_compress.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp]
+    lib.kv_chunk_recompress.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp]
     lib.chunk_compression_tags.argtypes = [sp, vp, vp, vp, vp, vp]
     lib.leoam_compressed_bytes_bound.argtypes = [sp]
     lib.leoam_compressed_bytes_bound.restype = sz
@@ -75,7 +76,7 @@ def _load() -> ctypes.CDLL:
     lib.leoam_version.restype = ctypes.c_int
     for name in ("kv_chunk_abstract_build", "chunk_score", "chunk_score_pin", "chunk_topk_select", "sparse_chunk_attention_decode",
                  "chunk_select_attention_decode", "chunk_select_attention_decode_static", "kv_chunk_abstract_append", "chunk_tree_refine",
-                 "kv_chunk_compress", "chunk_compression_tags", "leoam_workspace_init",
+                 "kv_chunk_compress", "kv_chunk_recompress", "chunk_compression_tags", "leoam_workspace_init",
                  "leoam_validate_boundaries", "leoam_copy_probe", "leoam_read_probe"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
@@ -87,7 +88,7 @@ EXPORTS = ("kv_chunk_abstract_build", "chunk_score", "chunk_score_pin", "chunk_t
            "chunk_select_attention_decode", "chunk_select_attention_decode_static", "leoam_fused_workspace_bytes",
            "leoam_workspace_init",
            "kv_chunk_abstract_append", "leoam_tree_evaluations", "chunk_tree_refine", "leoam_tree_workspace_bytes",
-           "kv_chunk_compress", "chunk_compression_tags", "leoam_compressed_bytes_bound", "leoam_compression_share",
+           "kv_chunk_compress", "kv_chunk_recompress", "chunk_compression_tags", "leoam_compressed_bytes_bound", "leoam_compression_share",
            "leoam_workspace_bytes", "leoam_validate_boundaries", "leoam_copy_probe", "leoam_read_probe", "leoam_status_string",
            "leoam_version")
 
@@ -158,6 +159,17 @@ def kv_chunk_compress(shape: Shape, K, V, chunk_off, n_chunks, four_bit, kblob, 
     _check(_lib.kv_chunk_compress(ctypes.byref(shape), _p(K), _p(V), _p(chunk_off), _p(n_chunks), _p(four_bit), _p(kblob),
                                   _p(vblob), kblob.numel() * kblob.element_size(), _p(qmeta), _p(total_bytes),
                                   _stream(stream)), "kv_chunk_compress")
+
+
+def kv_chunk_recompress(shape: Shape, K, V, chunk_off, n_chunks, four_bit_old, four_bit_new, kblob, vblob, qmeta,
+                        used_bytes, info, stream=None) -> None:
+    """A store written under four_bit_old brought to four_bit_new: only the chunks whose tag changed are encoded again.
+    used_bytes: int64[1] (in / out), info: int64[3] (out)."""
+    if kblob.numel() * kblob.element_size() != vblob.numel() * vblob.element_size():
+        raise ValueError("kblob and vblob must have the same size")
+    _check(_lib.kv_chunk_recompress(ctypes.byref(shape), _p(K), _p(V), _p(chunk_off), _p(n_chunks), _p(four_bit_old),
+                                    _p(four_bit_new), _p(kblob), _p(vblob), kblob.numel() * kblob.element_size(),
+                                    _p(qmeta), _p(used_bytes), _p(info), _stream(stream)), "kv_chunk_recompress")
 
 
 def chunk_compression_tags(shape: Shape, n_chunks, sel_idx, sel_count, four_bit, stream=None) -> None:

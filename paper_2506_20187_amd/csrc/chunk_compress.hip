@@ -207,12 +207,21 @@ template <typename T>
 __global__ __launch_bounds__(kCmpThreads) void compress_kernel(
     const char* __restrict__ K, const char* __restrict__ V, const int32_t* __restrict__ chunk_off,
     const int32_t* __restrict__ n_chunks, QRecord* __restrict__ qmeta, unsigned char* __restrict__ kblob,
-    unsigned char* __restrict__ vblob, long long blob_bytes, int c_max, int n_kv_heads, int n_ctx) {
+    unsigned char* __restrict__ vblob, long long blob_bytes, int c_max, int n_kv_heads, int n_ctx,
+    const uint8_t* __restrict__ tag_old, const uint8_t* __restrict__ tag_new, const long long* __restrict__ info,
+    long long* __restrict__ used_bytes) {
     static_assert(T::kEpl == 8, "16-bit sources only");
     constexpr int ROWB = Row<T>::kRowBytes;
     __shared__ float red[2][kCmpWaves];
 
     const int c = blockIdx.x, h = blockIdx.y >> 1, is_v = blockIdx.y & 1, b = blockIdx.z;
+    if (tag_old) {
+        // re-tagging a live store: only chunks whose tag changed are encoded again, and none if the
+        // layout step found no room; the first workgroup also advances the used size by the fresh room taken
+        if (info[0] != 0) return;
+        if (c == 0 && blockIdx.y == 0 && b == 0 && threadIdx.x == 0) *used_bytes += info[2];
+        if ((tag_old[(size_t)b * c_max + c] != 0) == (tag_new[(size_t)b * c_max + c] != 0)) return;
+    }
     if (c >= min(max(n_chunks[b], 0), c_max)) return;
     const size_t bh = (size_t)b * n_kv_heads + h;
     const int tid = threadIdx.x, lane = lane_id(), wave = tid / LEOAM_WAVE;
@@ -297,6 +306,125 @@ __global__ __launch_bounds__(kCmpThreads) void compress_kernel(
     }
 }
 
+// ---- re-tagging a live store ----------------------------------------------------------------
+// Sec. 4.4: the compressed share follows the measured times and the scores, so the tags of a store
+// change while it is in use.  Only chunks whose tag changed are encoded again: a chunk that becomes
+// 4-bit stays where it lies (it takes half of its old room), a chunk that becomes 8-bit moves to fresh
+// room behind the used part of the blobs, the moved chunks placed in (b, h, chunk) order.  This kernel
+// (one workgroup per kv head and sequence) assigns that room and rewrites the records' format fields;
+// the compression kernel then runs over the changed chunks only.  info[0] = 1 and nothing is changed
+// if the fresh room does not fit the blobs; info[1] = chunks to encode again, info[2] = bytes of fresh
+// room per blob.
+__device__ __forceinline__ unsigned long long grown_bytes_sum(const int32_t* off, const uint8_t* was, const uint8_t* is,
+                                                              int first, int step, int n, int c_max, int n_ctx,
+                                                              unsigned long long* changed) {
+    unsigned long long part = 0, cnt = 0;
+    for (int c = first; c < n; c += step * kLayUnroll) {
+        int t0[kLayUnroll], t1[kLayUnroll], fo[kLayUnroll], fn[kLayUnroll];
+#pragma unroll
+        for (int u = 0; u < kLayUnroll; ++u) {
+            const int cc = min(c + u * step, c_max - 1);
+            t0[u] = off[cc];
+            t1[u] = off[cc + 1];
+            fo[u] = was[cc];
+            fn[u] = is[cc];
+        }
+#pragma unroll
+        for (int u = 0; u < kLayUnroll; ++u) {
+            if (c + u * step >= n || (fo[u] != 0) == (fn[u] != 0)) continue;
+            const unsigned long long bytes = (unsigned long long)chunk_bytes(t0[u], t1[u], 0, n_ctx);
+            if (bytes == 0) continue;              // boundaries that do not tile the context: such a chunk stores nothing
+            ++cnt;
+            if (fo[u] != 0) part += bytes;         // 4-bit -> 8-bit: fresh room of the 8-bit size
+        }
+    }
+    *changed += cnt;
+    return part;
+}
+
+__global__ __launch_bounds__(kLayThreads) void recompress_layout_kernel(
+    const int32_t* __restrict__ chunk_off, const int32_t* __restrict__ n_chunks, const uint8_t* __restrict__ tag_old,
+    const uint8_t* __restrict__ tag_new, QRecord* __restrict__ qmeta, const long long* __restrict__ used_bytes,
+    long long blob_bytes, long long* __restrict__ info, int c_max, int n_kv_heads, int batch, int n_ctx) {
+    __shared__ unsigned long long slots[kLayWaves], slots_cnt[kLayWaves];
+    __shared__ unsigned long long wave_incl[kLayWaves];
+    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / LEOAM_WAVE;
+
+    // fresh room of every sequence (a wave per sequence): those before this one, and all of them
+    unsigned long long before = 0, all = 0, all_changed = 0;
+    for (int b0 = 0; b0 < batch; b0 += kLayWaves) {
+        const int bb = b0 + wave;
+        unsigned long long part = 0, cnt = 0;
+        if (bb < batch) {
+            const int n = min(max(n_chunks[bb], 0), c_max);
+            part = grown_bytes_sum(chunk_off + (size_t)bb * (c_max + 1), tag_old + (size_t)bb * c_max,
+                                   tag_new + (size_t)bb * c_max, lane, LEOAM_WAVE, n, c_max, n_ctx, &cnt);
+        }
+        part = group_sum_u64(part, 6);
+        cnt = group_sum_u64(cnt, 6);
+        __syncthreads();      // the previous round's totals have been read
+        if (lane == 0) {
+            slots[wave] = part;
+            slots_cnt[wave] = cnt;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < kLayWaves; ++w) {
+            if (b0 + w < b) before += slots[w];
+            all += slots[w];
+            all_changed += slots_cnt[w];
+        }
+    }
+    const unsigned long long heads = (unsigned long long)n_kv_heads;
+    const long long used = *used_bytes;
+    const bool fits = used >= 0 && (unsigned long long)used + all * heads <= (unsigned long long)blob_bytes;
+    if (b == 0 && h == 0 && tid == 0) {
+        info[0] = fits ? 0 : 1;
+        info[1] = fits ? (long long)(all_changed * heads) : 0;
+        info[2] = fits ? (long long)(all * heads) : 0;
+    }
+    if (!fits) return;
+
+    const int32_t* off = chunk_off + (size_t)b * (c_max + 1);
+    const uint8_t* was = tag_old + (size_t)b * c_max;
+    const uint8_t* is = tag_new + (size_t)b * c_max;
+    const int n = min(max(n_chunks[b], 0), c_max);
+    unsigned long long dummy = 0;
+    const unsigned long long per_head =
+        layout_block_sum(grown_bytes_sum(off, was, is, tid, kLayThreads, n, c_max, n_ctx, &dummy), slots);
+
+    // exclusive scan of the fresh room over the chunks, a tile of 1024 at a time
+    unsigned long long carry = 0;
+    for (int base = 0; base < n; base += kLayThreads) {
+        const int c = base + tid;
+        const int cc = min(c, c_max - 1);
+        const int t0 = off[cc], t1 = off[cc + 1], fo = was[cc], fn = is[cc];
+        const bool changes = c < n && (fo != 0) != (fn != 0) && chunk_bytes(t0, t1, 0, n_ctx) != 0;
+        const unsigned long long mine = (changes && fo != 0) ? (unsigned long long)chunk_bytes(t0, t1, 0, n_ctx) : 0ull;
+        const unsigned long long incl = wave_incl_scan_u32((uint32_t)mine);
+        __syncthreads();
+        if (lane == LEOAM_WAVE - 1) wave_incl[wave] = incl;
+        __syncthreads();
+        unsigned long long wave_before = 0, tile = 0;
+#pragma unroll
+        for (int w = 0; w < kLayWaves; ++w) {
+            if (w < wave) wave_before += wave_incl[w];
+            tile += wave_incl[w];
+        }
+        const unsigned long long within = carry + wave_before + incl - mine;
+        carry += tile;
+        if (changes) {
+            QRecord* r = qmeta + ((size_t)b * n_kv_heads + h) * c_max + c;
+            if (fo != 0) {
+                r->byte_off = used + (long long)(before * heads + (unsigned long long)h * per_head + within);
+                r->bits = 8;
+            } else {
+                r->bits = 4;
+            }
+        }
+    }
+}
+
 // ---- which chunks form the compressed share --------------------------------------------
 // Sec. 4.4 fixes how large the compressed share is, not which data it holds.  Here a chunk is
 // stored 4-bit unless some kv head of its sequence keeps it in the given selection (Sec. 4.2
@@ -347,11 +475,32 @@ hipError_t compress_dispatch(const leoam_shape* s, const void* K, const void* V,
     if (s->kv_dtype == LEOAM_F16)
         hipLaunchKernelGGL(compress_kernel<F16>, grid, block, 0, stream, (const char*)K, (const char*)V, chunk_off,
                            n_chunks, (QRecord*)qmeta, (unsigned char*)kblob, (unsigned char*)vblob,
-                           (long long)blob_bytes, s->c_max, s->n_kv_heads, s->n_ctx);
+                           (long long)blob_bytes, s->c_max, s->n_kv_heads, s->n_ctx, nullptr, nullptr, nullptr, nullptr);
     else
         hipLaunchKernelGGL(compress_kernel<BF16>, grid, block, 0, stream, (const char*)K, (const char*)V, chunk_off,
                            n_chunks, (QRecord*)qmeta, (unsigned char*)kblob, (unsigned char*)vblob,
-                           (long long)blob_bytes, s->c_max, s->n_kv_heads, s->n_ctx);
+                           (long long)blob_bytes, s->c_max, s->n_kv_heads, s->n_ctx, nullptr, nullptr, nullptr, nullptr);
+    return hipGetLastError();
+}
+
+hipError_t recompress_dispatch(const leoam_shape* s, const void* K, const void* V, const int32_t* chunk_off,
+                               const int32_t* n_chunks, const uint8_t* tag_old, const uint8_t* tag_new, void* kblob,
+                               void* vblob, void* qmeta, size_t blob_bytes, long long* used_bytes, long long* info,
+                               hipStream_t stream) {
+    hipLaunchKernelGGL(recompress_layout_kernel, dim3(s->n_kv_heads, s->batch), dim3(kLayThreads), 0, stream, chunk_off,
+                       n_chunks, tag_old, tag_new, (QRecord*)qmeta, used_bytes, (long long)blob_bytes, info, s->c_max,
+                       s->n_kv_heads, s->batch, s->n_ctx);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    dim3 grid(s->c_max, s->n_kv_heads * 2, s->batch), block(kCmpThreads);
+    if (s->kv_dtype == LEOAM_F16)
+        hipLaunchKernelGGL(compress_kernel<F16>, grid, block, 0, stream, (const char*)K, (const char*)V, chunk_off,
+                           n_chunks, (QRecord*)qmeta, (unsigned char*)kblob, (unsigned char*)vblob,
+                           (long long)blob_bytes, s->c_max, s->n_kv_heads, s->n_ctx, tag_old, tag_new, info, used_bytes);
+    else
+        hipLaunchKernelGGL(compress_kernel<BF16>, grid, block, 0, stream, (const char*)K, (const char*)V, chunk_off,
+                           n_chunks, (QRecord*)qmeta, (unsigned char*)kblob, (unsigned char*)vblob,
+                           (long long)blob_bytes, s->c_max, s->n_kv_heads, s->n_ctx, tag_old, tag_new, info, used_bytes);
     return hipGetLastError();
 }
 

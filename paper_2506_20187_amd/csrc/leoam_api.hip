@@ -34,6 +34,8 @@ size_t compressed_bytes_bound(const leoam_shape*);
 hipError_t compression_tags_dispatch(const leoam_shape*, const int32_t*, const int32_t*, const int32_t*, uint8_t*, hipStream_t);
 hipError_t compress_dispatch(const leoam_shape*, const void*, const void*, const int32_t*, const int32_t*, const uint8_t*,
                              void*, void*, void*, size_t, long long*, hipStream_t);
+hipError_t recompress_dispatch(const leoam_shape*, const void*, const void*, const int32_t*, const int32_t*, const uint8_t*,
+                               const uint8_t*, void*, void*, void*, size_t, long long*, long long*, hipStream_t);
 hipError_t abstract_append_dispatch(const leoam_shape*, const void*, int32_t*, int32_t*, int, void*, int32_t*, hipStream_t);
 
 // scores of the first `sink` and the last `tail` chunks of every (b, h) row become FLT_MAX
@@ -352,6 +354,22 @@ int kv_chunk_compress(const leoam_shape* shape, const void* K, const void* V, co
     if (blob_bytes < compressed_bytes_bound(shape)) return LEOAM_E_WORKSPACE;
     return from_hip(compress_dispatch(shape, K, V, chunk_off, n_chunks, four_bit, kblob, vblob, qmeta, blob_bytes,
                                       (long long*)total_bytes, (hipStream_t)stream));
+}
+
+int kv_chunk_recompress(const leoam_shape* shape, const void* K, const void* V, const int32_t* chunk_off,
+                        const int32_t* n_chunks, const uint8_t* four_bit_old, const uint8_t* four_bit_new, void* kblob,
+                        void* vblob, size_t blob_bytes, void* qmeta, int64_t* used_bytes, int64_t* info, void* stream) {
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!K || !V || !chunk_off || !n_chunks || !four_bit_old || !four_bit_new || !kblob || !vblob || !qmeta ||
+        !used_bytes || !info)
+        return LEOAM_E_INVALID_ARG;
+    if (shape->kv_dtype != LEOAM_F16 && shape->kv_dtype != LEOAM_BF16) return LEOAM_E_UNSUPPORTED;
+    if (((uintptr_t)kblob & 15u) || ((uintptr_t)vblob & 15u) || ((uintptr_t)qmeta & 15u) || ((uintptr_t)used_bytes & 7u) ||
+        ((uintptr_t)info & 7u))
+        return LEOAM_E_INVALID_ARG;
+    return from_hip(recompress_dispatch(shape, K, V, chunk_off, n_chunks, four_bit_old, four_bit_new, kblob, vblob, qmeta,
+                                        blob_bytes, (long long*)used_bytes, (long long*)info, (hipStream_t)stream));
 }
 
 int chunk_compression_tags(const leoam_shape* shape, const int32_t* n_chunks, const int32_t* sel_idx,

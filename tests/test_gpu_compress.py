@@ -277,3 +277,126 @@ def test_compression_tags_exact_and_policy_loop(L, oracle):
         four_tokens = int((sizes[b, :counts[b]] * got[b, :counts[b]]).sum())
         assert four_tokens >= N - Hkv * budget
     check_against_oracle(oracle, gpu_compress(L, K, V, packed, counts, got.astype(bool)), K, V, packed, counts, got.astype(bool))
+
+
+# ---------------------------------------------------------------------------
+# kv_chunk_recompress: a live store brought to new tags, only the changed chunks encoded again
+# ---------------------------------------------------------------------------
+def gpu_store(L, K, V, packed, counts, fb, cap):
+    """kv_chunk_compress into blobs of `cap` bytes (poisoned), everything left on the GPU"""
+    B, Hkv, N, _ = K.shape
+    c_max = packed.shape[1] - 1
+    shape = L.make_shape(B, Hkv, Hkv, 128, N, c_max, 1, K.dtype)
+    st = dict(shape=shape, K=K.cuda(), V=V.cuda(), off=torch.from_numpy(packed).cuda(), nc=torch.from_numpy(counts).cuda(),
+              kb=torch.full((cap,), 0xA5, dtype=torch.uint8, device="cuda"),
+              vb=torch.full((cap,), 0x5A, dtype=torch.uint8, device="cuda"),
+              qm=torch.full((B, Hkv, c_max, 8), -7, dtype=torch.int32, device="cuda"),
+              used=torch.zeros(1, dtype=torch.int64, device="cuda"), info=torch.full((3,), -7, dtype=torch.int64, device="cuda"))
+    L.kv_chunk_compress(shape, st["K"], st["V"], st["off"], st["nc"], tags_dev(fb), st["kb"], st["vb"], st["qm"], st["used"])
+    torch.cuda.synchronize()
+    return st
+
+
+def tags_dev(fb):
+    return torch.from_numpy(np.ascontiguousarray(fb).astype(np.uint8)).cuda()
+
+
+def oracle_store(oracle, K, V, packed, counts, fb, cap):
+    wk, wv, wq = oracle.chunk_compress(K, V, packed, counts, fb)
+    kb, vb = np.full(cap, 0xA5, dtype=np.uint8), np.full(cap, 0x5A, dtype=np.uint8)
+    kb[: wk.size], vb[: wv.size] = wk, wv
+    return kb, vb, wq, wk.size
+
+
+def assert_same_store(oracle, st, want):
+    kb, vb, wq, used = want
+    rec = st["qm"].cpu().numpy().view(oracle.QCHUNK_DTYPE).reshape(wq.shape)
+    for f in ("byte_off", "bits", "scale_k", "zero_k", "scale_v", "zero_v"):
+        assert np.array_equal(rec[f], wq[f]), f
+    assert int(st["used"].item()) == used
+    assert np.array_equal(st["kb"].cpu().numpy(), kb), "K blob (codes, holes and untouched bytes)"
+    assert np.array_equal(st["vb"].cpu().numpy(), vb), "V blob"
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+def test_recompress_exact_chain_of_retags(L, oracle, dtype):
+    rng = np.random.default_rng(41 + (dtype == torch.float16))
+    g = torch.Generator().manual_seed(6)
+    B, Hkv, N = 3, 2, 2500
+    K = (torch.randn(B, Hkv, N, 128, generator=g) * 1.9).to(dtype)
+    V = torch.randn(B, Hkv, N, 128, generator=g).to(dtype)
+    offs = [gen.make_boundaries(N, rng, sizes=(1, 2, 15, 16, 63, 64, 65, 130)) for _ in range(B)]
+    packed, counts, c_max = gen.pack_boundaries(offs, N)
+    cap = 3 * B * Hkv * N * 128
+    tags = [rng.random((B, c_max)) < s for s in (0.5, 0.5, 0.9, 0.1, 0.1)]        # the last step changes nothing
+    st = gpu_store(L, K, V, packed, counts, tags[0], cap)
+    kb, vb, wq, used = oracle_store(oracle, K, V, packed, counts, tags[0], cap)
+    assert_same_store(oracle, st, (kb, vb, wq, used))
+    for old, new in zip(tags, tags[1:]):
+        rc, used_new, changed = oracle.chunk_recompress(K, V, packed, counts, old, new, kb, vb, wq, used)
+        assert rc == 0
+        L.kv_chunk_recompress(st["shape"], st["K"], st["V"], st["off"], st["nc"], tags_dev(old), tags_dev(new), st["kb"],
+                              st["vb"], st["qm"], st["used"], st["info"])
+        torch.cuda.synchronize()
+        assert st["info"].cpu().tolist() == [0, changed, used_new - used]
+        used = used_new
+        assert_same_store(oracle, st, (kb, vb, wq, used))
+    # the kernels that read the store follow the records: attention over the re-tagged store (moved chunks, holes)
+    G = 4
+    q = (torch.randn(B, Hkv * G, 128, generator=g) * 1.3).to(torch.float16)
+    sel = np.full((B, Hkv, c_max), -1, dtype=np.int32)
+    cnt = np.zeros((B, Hkv), dtype=np.int32)
+    for b in range(B):
+        for h in range(Hkv):
+            n = int(rng.integers(1, counts[b]))
+            sel[b, h, :n] = np.sort(rng.choice(counts[b], size=n, replace=False))
+            cnt[b, h] = n
+    want, _ = oracle.sparse_attention_q(q, kb, vb, wq, packed, sel, cnt)
+    qshape = L.make_shape(B, Hkv * G, Hkv, 128, N, c_max, c_max, L.binding.Q8Q4)
+    out = torch.full((B, Hkv * G, 128), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(L.leoam_workspace_bytes(qshape, 0), dtype=torch.uint8, device="cuda")
+    L.sparse_chunk_attention_decode(qshape, q.cuda(), st["kb"], st["vb"], st["off"], st["nc"], torch.from_numpy(sel).cuda(),
+                                    torch.from_numpy(cnt).cuda(), L.default_scale(128), out, None, ws, qmeta=st["qm"])
+    torch.cuda.synchronize()
+    assert np.abs(out.cpu().numpy().astype(np.float64) - want).max() <= 2e-3
+    ab = torch.empty(B, Hkv, c_max, 2, 128, dtype=torch.float16, device="cuda")
+    L.kv_chunk_abstract_build(qshape, st["kb"], st["off"], st["nc"], ab, qmeta=st["qm"])
+    torch.cuda.synchronize()
+    want_ab = oracle.abstract_build_q(kb, wq, packed, counts)
+    got_ab = ab.cpu().to(torch.float64).numpy()
+    for b in range(B):
+        assert np.array_equal(got_ab[b, :, : counts[b]], want_ab[b, :, : counts[b]])
+
+
+def test_recompress_without_room_changes_nothing(L, oracle):
+    rng = np.random.default_rng(43)
+    g = torch.Generator().manual_seed(7)
+    B, Hkv, N = 2, 2, 900
+    K = torch.randn(B, Hkv, N, 128, generator=g).to(torch.bfloat16)
+    V = torch.randn(B, Hkv, N, 128, generator=g).to(torch.bfloat16)
+    offs = [gen.make_boundaries(N, rng, sizes=(4, 16, 33)) for _ in range(B)]
+    packed, counts, c_max = gen.pack_boundaries(offs, N)
+    cap = B * Hkv * N * 128                      # the bound: a store of 4-bit chunks fills half of it
+    old, new = np.ones((B, c_max), dtype=bool), np.zeros((B, c_max), dtype=bool)
+    st = gpu_store(L, K, V, packed, counts, old, cap)
+    before = [st[k].clone() for k in ("kb", "vb", "qm", "used")]
+    new[0, 0] = True                              # every chunk but one would move: twice the room that is left
+    L.kv_chunk_recompress(st["shape"], st["K"], st["V"], st["off"], st["nc"], tags_dev(old), tags_dev(new), st["kb"],
+                          st["vb"], st["qm"], st["used"], st["info"])
+    torch.cuda.synchronize()
+    assert st["info"].cpu().tolist() == [1, 0, 0]
+    for a, k in zip(before, ("kb", "vb", "qm", "used")):
+        assert torch.equal(a, st[k]), k
+    # a third of the chunks fits
+    new2 = old.copy()
+    want = oracle_store(oracle, K, V, packed, counts, old, cap)
+    kb, vb, wq, used = want
+    for b in range(B):
+        new2[b, : counts[b] // 3] = False
+    rc, used_new, changed = oracle.chunk_recompress(K, V, packed, counts, old, new2, kb, vb, wq, used)
+    assert rc == 0
+    L.kv_chunk_recompress(st["shape"], st["K"], st["V"], st["off"], st["nc"], tags_dev(old), tags_dev(new2), st["kb"],
+                          st["vb"], st["qm"], st["used"], st["info"])
+    torch.cuda.synchronize()
+    assert st["info"].cpu().tolist() == [0, changed, used_new - used]
+    assert_same_store(oracle, st, (kb, vb, wq, used_new))
