@@ -17,8 +17,10 @@
 // that falls back to a scan in index order.  All integer work, exact, no
 // ordering ambiguity.
 //
-// One workgroup of 1024 lanes per (sequence, kv head); every lane keeps kIpt
-// consecutive chunks in registers, so "ascending chunk index" is "lane order".
+// One workgroup per (sequence, kv head) - 1024 lanes in the selection kernels,
+// 256 in the one-launch decode step, whose workgroups also score and stream;
+// every lane keeps kIpt consecutive chunks in registers, so "ascending chunk
+// index" is "lane order".
 #pragma once
 #include "leoam_dev.h"
 
@@ -49,28 +51,30 @@ __device__ __forceinline__ uint64_t wave_incl_scan(uint64_t v) {
     return ((uint64_t)hi << 32) | lo;
 }
 
-// sum of the 16 per-wave totals in wave_sums (every lane gets it)
+// sum of the kWaves (a power of two, at most 16) per-wave totals in wave_sums (every lane gets it)
+template <int kWaves = kSelWaves>
 __device__ __forceinline__ uint64_t wave_sums_total(const uint64_t* wave_sums) {
-    const uint64_t s = wave_sums[lane_id() & (kSelWaves - 1)];
+    const uint64_t s = wave_sums[lane_id() & (kWaves - 1)];
     const uint32_t lo = row16_incl_scan_u32((uint32_t)s), hi = row16_incl_scan_u32((uint32_t)(s >> 32));
-    return ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)hi, kSelWaves - 1) << 32) |
-           (uint32_t)__builtin_amdgcn_readlane((int)lo, kSelWaves - 1);
+    return ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)hi, kWaves - 1) << 32) |
+           (uint32_t)__builtin_amdgcn_readlane((int)lo, kWaves - 1);
 }
 
-// exclusive scan over the whole workgroup in lane order; *total gets the sum.  kGuard: a
-// barrier first, for callers that cannot rule out a lane still reading wave_sums.
-template <bool kGuard = true>
+// exclusive scan over the whole workgroup (kWaves waves) in lane order; *total gets the sum.
+// kGuard: a barrier first, for callers that cannot rule out a lane still reading wave_sums.
+template <bool kGuard = true, int kWaves = kSelWaves>
 __device__ __forceinline__ uint64_t block_excl_scan(uint64_t v, uint64_t* wave_sums, uint64_t* total) {
+    static_assert(kWaves <= 16 && (kWaves & (kWaves - 1)) == 0, "the second scan level is one 16-lane row");
     const int lane = lane_id(), wave = threadIdx.x / LEOAM_WAVE;
     const uint64_t incl = wave_incl_scan(v);
     if (kGuard) __syncthreads();           // wave_sums may still be read from a previous call
     if (lane == LEOAM_WAVE - 1) wave_sums[wave] = incl;
     __syncthreads();
     // second level: lane w of a row holds wave w's sum, a row scan gives the prefixes
-    const uint64_t s = wave_sums[lane & (kSelWaves - 1)];
+    const uint64_t s = wave_sums[lane & (kWaves - 1)];
     const uint32_t lo = row16_incl_scan_u32((uint32_t)s), hi = row16_incl_scan_u32((uint32_t)(s >> 32));
-    const uint32_t all_lo = (uint32_t)__builtin_amdgcn_readlane((int)lo, kSelWaves - 1);
-    const uint32_t all_hi = (uint32_t)__builtin_amdgcn_readlane((int)hi, kSelWaves - 1);
+    const uint32_t all_lo = (uint32_t)__builtin_amdgcn_readlane((int)lo, kWaves - 1);
+    const uint32_t all_hi = (uint32_t)__builtin_amdgcn_readlane((int)hi, kWaves - 1);
     const uint32_t upto_lo = (uint32_t)__builtin_amdgcn_readlane((int)lo, wave);
     const uint32_t upto_hi = (uint32_t)__builtin_amdgcn_readlane((int)hi, wave);
     const uint32_t own_lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)s, wave);
@@ -113,12 +117,22 @@ template <int kIpt> struct SelectResult {
     uint64_t kept_total;      // the same over the whole (sequence, kv head)
 };
 
-// Every lane of the 1024-lane workgroup must call this (it contains barriers).
+// A score as the selection reads it.  kCoherent: the row was written earlier in the SAME launch by
+// workgroups on other XCDs (agent-scope write-through stores), so it is read with agent-scope loads.
+template <bool kCoherent> __device__ __forceinline__ float load_score(const float* p) {
+    if constexpr (kCoherent) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else return *p;
+}
+
+// Every lane of the kThreads-lane workgroup (256 or 1024) must call this (it contains barriers).
 // srow: the (b,h) row of scores, off: the sequence's boundary row (c_max + 1 entries).
-template <int kIpt>
+// kIpt * kThreads >= c_max.
+template <int kIpt, int kThreads = kSelThreads, bool kCoherent = false>
 __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restrict__ srow,
                                             const int32_t* __restrict__ off, int C, int c_max, int k_max, int n_ctx,
                                             int max_chunks, int token_budget, SelectResult<kIpt>& R) {
+    constexpr int kWaves = kThreads / LEOAM_WAVE;
+    static_assert(kThreads >= kBins && kWaves <= kSelWaves, "the histogram is cleared by one lane per bin");
     const int tid = threadIdx.x, lane = lane_id(), wave = tid / LEOAM_WAVE;
     uint32_t max_cnt = (uint32_t)k_max;
     if (max_chunks > 0 && (uint32_t)max_chunks < max_cnt) max_cnt = (uint32_t)max_chunks;
@@ -142,7 +156,7 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
 #pragma unroll
         for (int i = 0; i <= kIpt; ++i) offv[i] = off[min(c0 + i, c_max)];
 #pragma unroll
-        for (int i = 0; i < kIpt; ++i) sc[i] = srow[min(c0 + i, c_max - 1)];
+        for (int i = 0; i < kIpt; ++i) sc[i] = load_score<kCoherent>(srow + min(c0 + i, c_max - 1));
     } else {
         // A lane's kIpt consecutive items are 4*kIpt bytes apart from its neighbour's: read
         // directly, every load instruction would touch 64 * kIpt * 4 / 128 cache lines.  The
@@ -157,7 +171,7 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
         int ro_end = off[min(wbase + LEOAM_WAVE * kIpt, c_max)];
 #pragma unroll
         for (int j = 0; j < kIpt; ++j) {
-            rs[j] = srow[min(wbase + LEOAM_WAVE * j + lane, c_max - 1)];
+            rs[j] = load_score<kCoherent>(srow + min(wbase + LEOAM_WAVE * j + lane, c_max - 1));
             ro[j] = off[min(wbase + LEOAM_WAVE * j + lane, c_max)];
         }
         asm volatile("" : "+v"(ro_end));
@@ -231,9 +245,9 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
         L.red_max[wave] = kmaxv;
     }
     __syncthreads();
-    const uint64_t grand = wave_sums_total(L.wave_sums);
-    uint32_t lo = row0_min_u32(L.red_min[lane & (kSelWaves - 1)]);
-    uint32_t hi = row0_max_u32(L.red_max[lane & (kSelWaves - 1)]);
+    const uint64_t grand = wave_sums_total<kWaves>(L.wave_sums);
+    uint32_t lo = row0_min_u32(L.red_min[lane & (kWaves - 1)]);
+    uint32_t hi = row0_max_u32(L.red_max[lane & (kWaves - 1)]);
 
     uint64_t above = 0;
     bool use_cand = false;
@@ -337,18 +351,21 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
         __syncthreads();
         const int n = (int)min(L.sh_ncand, (uint32_t)kMaxCand);
         int tshift = 0;                                   // 2^tshift lanes share one chunk
-        while (tshift < 6 && (n << (tshift + 1)) <= kSelThreads) ++tshift;
-        const int cand = tid >> tshift, sub = tid & ((1 << tshift) - 1);
-        uint64_t run = 0;
-        if (cand < n) {
-            const uint64_t mine_ki = L.cand_ki[cand];
-            for (int j = sub; j < n; j += (1 << tshift))
-                if (L.cand_ki[j] >= mine_ki) run += L.cand_tot[j];
-        }
-        run = group_sum_u64(run, tshift);
-        if (cand < n && sub == 0) {
-            run += above;
-            L.cand_keep[cand] = fits((uint32_t)(run >> 32), (uint32_t)run, max_cnt, max_tok) ? 1u : 0u;
+        while (tshift < 6 && (n << (tshift + 1)) <= kThreads) ++tshift;
+        const int sub = tid & ((1 << tshift) - 1);
+        // (one round unless the workgroup has fewer lanes than there are candidates)
+        for (int cand = tid >> tshift; cand - (tid >> tshift) < n; cand += kThreads >> tshift) {
+            uint64_t run = 0;
+            if (cand < n) {
+                const uint64_t mine_ki = L.cand_ki[cand];
+                for (int j = sub; j < n; j += (1 << tshift))
+                    if (L.cand_ki[j] >= mine_ki) run += L.cand_tot[j];
+            }
+            run = group_sum_u64(run, tshift);
+            if (cand < n && sub == 0) {
+                run += above;
+                L.cand_keep[cand] = fits((uint32_t)(run >> 32), (uint32_t)run, max_cnt, max_tok) ? 1u : 0u;
+            }
         }
         __syncthreads();
 #pragma unroll
@@ -362,7 +379,7 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
         for (int i = 0; i < kIpt; ++i)
             if (valid[i] && key[i] == thr) tie_mine += pack_tot(1, R.size[i]);
         uint64_t tie_total;
-        uint64_t run = above + block_excl_scan(tie_mine, L.wave_sums, &tie_total);
+        uint64_t run = above + block_excl_scan<true, kWaves>(tie_mine, L.wave_sums, &tie_total);
 #pragma unroll
         for (int i = 0; i < kIpt; ++i) {
             if (valid[i] && key[i] == thr) {
@@ -377,7 +394,7 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
 #pragma unroll
     for (int i = 0; i < kIpt; ++i)
         if (R.keep[i]) kept_mine += pack_tot(1, R.size[i]);
-    R.kept_before = block_excl_scan<false>(kept_mine, L.wave_sums2, &R.kept_total);      // (nothing has read these slots yet)
+    R.kept_before = block_excl_scan<false, kWaves>(kept_mine, L.wave_sums2, &R.kept_total);      // (nothing has read these slots yet)
 }
 
 }  // namespace leoam
