@@ -11,16 +11,15 @@
 // a pass histograms (count, tokens) of the chunks still in range into 256 equal
 // sub-ranges of the live key range (LDS, one packed 64-bit atomic per chunk),
 // one wave walks the histogram from the top and picks the sub-range in which the
-// running totals stop fitting.  As soon as that sub-range holds at most 1024
+// running totals stop fitting.  As soon as that sub-range holds at most 256
 // chunks (normally after the first pass) they are ranked pairwise, the n*n
 // comparisons spread over the workgroup; a single key shared by more chunks than
 // that falls back to a scan in index order.  All integer work, exact, no
 // ordering ambiguity.
 //
-// One workgroup per (sequence, kv head) - 1024 lanes in the selection kernels,
-// 256 in the one-launch decode step, whose workgroups also score and stream;
-// every lane keeps kIpt consecutive chunks in registers, so "ascending chunk
-// index" is "lane order".
+// One workgroup per (sequence, kv head), 1024 lanes in the library's kernels (the
+// code is written for any multiple of 256 up to that); every lane keeps kIpt
+// consecutive chunks in registers, so "ascending chunk index" is "lane order".
 #pragma once
 #include "leoam_dev.h"
 
@@ -30,7 +29,14 @@ constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / LEOAM_WAVE;
 static_assert(kSelWaves == 16, "the second scan level keeps one wave total per lane of a 16-lane row");
 constexpr int kBins = 256;
-constexpr int kMaxCand = 1024;   // chunks of the cut sub-range that are ranked pairwise
+// Chunks of the cut sub-range that are ranked pairwise.  A pass of the descent costs about a
+// microsecond whatever it narrows; the pairwise step costs n / (lanes per chunk) dependent LDS
+// reads per lane, so it only pays for a few hundred chunks.  Scores that straddle zero put
+// hundreds of chunks into one sub-range of the first pass (sub-ranges are equal in the bit
+// pattern, i.e. two binades wide there): with a limit of 1024 the selection of 3.5K such chunks
+// took 100 us on MI355X, with 256 it takes 10 (one more pass), and rows whose first pass
+// already isolates a few dozen chunks are not affected.
+constexpr int kMaxCand = 256;
 
 // float -> uint32 whose unsigned order is the float order (-0 == +0)
 __device__ __forceinline__ uint32_t order_key(float s) {
@@ -133,6 +139,8 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
                                             int max_chunks, int token_budget, SelectResult<kIpt>& R) {
     constexpr int kWaves = kThreads / LEOAM_WAVE;
     static_assert(kThreads >= kBins && kWaves <= kSelWaves, "the histogram is cleared by one lane per bin");
+    // (no more candidates than lanes: a smaller workgroup takes another pass instead)
+    constexpr int kCandLimit = kThreads < kMaxCand ? kThreads : kMaxCand;
     const int tid = threadIdx.x, lane = lane_id(), wave = tid / LEOAM_WAVE;
     uint32_t max_cnt = (uint32_t)k_max;
     if (max_chunks > 0 && (uint32_t)max_chunks < max_cnt) max_cnt = (uint32_t)max_chunks;
@@ -317,7 +325,7 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
             const uint32_t nbin = L.sh_nbin;
             // (no barrier: wave 0 writes these again only after the next pass's barrier, which every
             // lane reaches after these reads)
-            if (nbin <= (uint32_t)kMaxCand) {
+            if (nbin <= (uint32_t)kCandLimit) {
                 use_cand = true;
                 break;
             }
@@ -340,7 +348,7 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
             mypos[i] = 0xffffffffu;
             if (valid[i] && key[i] >= lo && key[i] <= hi) {
                 const uint32_t pos = atomicAdd(&L.sh_ncand, 1u);
-                if (pos < (uint32_t)kMaxCand) {
+                if (pos < (uint32_t)kCandLimit) {
                     mypos[i] = pos;
                     // "j comes no later than i" <=> (key_j, -idx_j) >= (key_i, -idx_i)
                     L.cand_ki[pos] = ((uint64_t)key[i] << 32) | (uint32_t)(0x7fffffff - (c0 + i));
@@ -349,7 +357,7 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
             }
         }
         __syncthreads();
-        const int n = (int)min(L.sh_ncand, (uint32_t)kMaxCand);
+        const int n = (int)min(L.sh_ncand, (uint32_t)kCandLimit);
         int tshift = 0;                                   // 2^tshift lanes share one chunk
         while (tshift < 6 && (n << (tshift + 1)) <= kThreads) ++tshift;
         const int sub = tid & ((1 << tshift) - 1);

@@ -221,6 +221,10 @@ def test_select_exact(L, oracle, C):
         "ties": rng.integers(-3, 4, size=(B, Hkv, c_max)).astype(np.float32),
         "wide": (rng.standard_normal((B, Hkv, c_max)) * 10.0 ** rng.integers(-20, 20, size=(B, Hkv, c_max))).astype(np.float32),
         "flat": np.full((B, Hkv, c_max), -0.0, dtype=np.float32),
+        # scores on both sides of zero: the first pass of the descent (sub-ranges equal in the bit pattern)
+        # leaves hundreds of chunks in the cut sub-range, which takes further passes
+        "around_zero": rng.standard_normal((B, Hkv, c_max)).astype(np.float32) * 20,
+        "uniform_around_zero": ((rng.random((B, Hkv, c_max)) - 0.5) * 100).astype(np.float32),
     }
     flavours["flat"][:, :, ::2] = 0.0
     total = N
@@ -238,7 +242,8 @@ def test_select_exact(L, oracle, C):
 def test_select_cluster_at_the_threshold(L, oracle, m):
     """m chunks with nearly equal (distinct, and a few equal) scores sit where the budget runs out, the
     others far above and far below: after the first histogram pass exactly those m are left to be ranked,
-    which takes the pairwise step through every width of its lane groups (and past its limit of 1024)."""
+    which takes the pairwise step through every width of its lane groups and, past its limit of 256, through
+    further passes of the descent and the scan over equal keys."""
     rng = np.random.default_rng(m)
     B, Hkv, C = 2, 2, m + 300
     sizes = rng.integers(1, 33, size=(B, C))
