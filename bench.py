@@ -50,6 +50,10 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="use only the first n resident layers (0 = all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-reps", type=int, default=5, help="passes of the per-kernel timing loops")
+    ap.add_argument("--layer-ahead", choices=["auto", "on", "off"], default="auto",
+                    help="time the layer-ahead schedules of DecodeStack as well (auto: for the batch-1 workloads c1 and "
+                         "c2, where they pay; their two-stream and all-layers launches would otherwise mix into the "
+                         "profiler's per-kernel averages of the default c3 run)")
     return ap.parse_args()
 
 
@@ -313,7 +317,8 @@ def main():
     # previous step's, or a speculated one); the benchmark's queries are fixed, so every schedule
     # computes the same step.  us per layer-step, median of per-step HIP-event times.
     layer_ahead = None
-    if not quant:
+    want_ahead = args.layer_ahead == "on" or (args.layer_ahead == "auto" and args.workload in ("c1", "c2"))
+    if not quant and want_ahead:
         stack = L.DecodeStack([c.K for c in cases], [c.V for c in cases], [c.chunk_off for c in cases],
                               [c.n_chunks for c in cases], cases[0].hq, max(c.k_max for c in cases),
                               cases[0].max_chunks, cases[0].token_budget)
@@ -530,8 +535,9 @@ def main():
             "unit": "GB/s",
             "frac": round(attn_gbs / HBM_PEAK_GBS, 4),
             "traffic": measured_traffic(args.workload, "select_attention"),
-            "traffic_source": f"profiles/pmc_{args.workload}_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
-                              "benchmark, scaled by the copy probe; counters cannot be read from inside the timed process)",
+            "traffic_source": None if measured_traffic(args.workload, "select_attention") is None else
+            f"profiles/pmc_{args.workload}_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
+            "benchmark, scaled by the copy probe; counters cannot be read from inside the timed process)",
             "bytes_per_launch": int(kv_bytes),
             "us_per_launch": round(fused_us, 2),
             "frac_of_measured_read": round(attn_gbs / read_gbs, 4),

@@ -2,7 +2,7 @@
 
 Per (sequence, kv head, chunk, tensor) asymmetric affine quantisation with one
 scale and one zero point: code = round((x - zero) / scale), zero = min over the
-chunk, scale = (max - min) / (levels - 1).  8-bit chunks keep one byte per
+chunk, scale = (max - min) / levels with levels = 255 (8-bit codes 0..255) or 15 (4-bit codes 0..15).  8-bit chunks keep one byte per
 element; 4-bit chunks pack two codes per byte (even channel in the low nibble).
 K and V blobs share the per-chunk byte offsets.  Which chunks are 4-bit is
 given by `four_bit[b, c]` (the paper chooses a share from a latency model,
