@@ -51,8 +51,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-reps", type=int, default=5, help="passes of the per-kernel timing loops")
     ap.add_argument("--layer-ahead", choices=["auto", "on", "off"], default="auto",
-                    help="time the layer-ahead schedules of DecodeStack as well (auto: for the batch-1 workloads c1 and "
-                         "c2, where they pay; their two-stream and all-layers launches would otherwise mix into the "
+                    help="time the layer-ahead schedules of DecodeStack as well (auto: for the batch-1 workloads c1, c2 "
+                         "and c4, where they pay; their two-stream and all-layers launches would otherwise mix into the "
                          "profiler's per-kernel averages of the default c3 run)")
     return ap.parse_args()
 
@@ -317,11 +317,17 @@ def main():
     # previous step's, or a speculated one); the benchmark's queries are fixed, so every schedule
     # computes the same step.  us per layer-step, median of per-step HIP-event times.
     layer_ahead = None
-    want_ahead = args.layer_ahead == "on" or (args.layer_ahead == "auto" and args.workload in ("c1", "c2"))
-    if not quant and want_ahead:
-        stack = L.DecodeStack([c.K for c in cases], [c.V for c in cases], [c.chunk_off for c in cases],
-                              [c.n_chunks for c in cases], cases[0].hq, max(c.k_max for c in cases),
-                              cases[0].max_chunks, cases[0].token_budget)
+    want_ahead = args.layer_ahead == "on" or (args.layer_ahead == "auto" and args.workload in ("c1", "c2", "c4"))
+    if want_ahead:
+        if quant:
+            stack = L.DecodeStack([lay.K for lay in layers], [lay.V for lay in layers], [c.chunk_off for c in cases],
+                                  [c.n_chunks for c in cases], cases[0].hq, max(c.k_max for c in cases),
+                                  cases[0].max_chunks, cases[0].token_budget, qmetas=[lay.qmeta for lay in layers],
+                                  n_kv_heads=cases[0].hkv, n_ctx=cases[0].n_ctx)
+        else:
+            stack = L.DecodeStack([c.K for c in cases], [c.V for c in cases], [c.chunk_off for c in cases],
+                                  [c.n_chunks for c in cases], cases[0].hq, max(c.k_max for c in cases),
+                                  cases[0].max_chunks, cases[0].token_budget)
         stack.build_abstract()
         q_all = torch.stack([c.q for c in cases]).contiguous()
         layer_ahead = {"what": "us per layer-step (median, p10, p90 of per-step HIP-event times)"}

@@ -100,33 +100,52 @@ class DecodeStack:
     q_eval == q every schedule returns exactly what step_sequential returns.
     """
 
-    def __init__(self, Ks, Vs, chunk_offs, n_chunks, n_q_heads: int, k_max: int, max_chunks: int, token_budget: int):
+    def __init__(self, Ks, Vs, chunk_offs, n_chunks, n_q_heads: int, k_max: int, max_chunks: int, token_budget: int,
+                 qmetas=None, n_kv_heads: int = None, n_ctx: int = None, head_dim: int = 128):
+        """Dense stores: Ks, Vs are per-layer [B,Hkv,N,D] tensors.  Compressed stores: Ks, Vs are the per-layer byte
+        blobs, `qmetas` the per-layer [B,Hkv,c_max_l,8] int32 chunk records, and n_kv_heads / n_ctx must be given
+        (the records are copied into rows of the common capacity; queries and abstracts are fp16)."""
         self.n_layers = len(Ks)
-        batch, hkv, n_ctx, d = Ks[0].shape
-        dev, dtype = Ks[0].device, Ks[0].dtype
+        quant = qmetas is not None
+        if quant:
+            batch, hkv, d = int(chunk_offs[0].shape[0]), int(n_kv_heads), int(head_dim)
+            dev, dtype, adtype = Ks[0].device, B.Q8Q4, torch.float16
+        else:
+            batch, hkv, n_ctx, d = Ks[0].shape
+            dev, dtype, adtype = Ks[0].device, Ks[0].dtype, Ks[0].dtype
         self.batch = batch
         c_max = max(int(co.shape[1]) - 1 for co in chunk_offs)
         rows = self.n_layers * batch
         # boundary rows padded to the common capacity (entries past n_chunks are ignored by the library)
-        self.chunk_off = torch.full((rows, c_max + 1), n_ctx, dtype=torch.int32, device=dev)
+        self.chunk_off = torch.full((rows, c_max + 1), int(n_ctx), dtype=torch.int32, device=dev)
         for l, co in enumerate(chunk_offs):
             self.chunk_off[l * batch:(l + 1) * batch, : co.shape[1]] = co
         self.n_chunks = torch.cat([nc.reshape(batch) for nc in n_chunks]).to(torch.int32).contiguous()
-        self.abstract = torch.empty(rows, hkv, c_max, 2, d, dtype=dtype, device=dev)
+        self.abstract = torch.empty(rows, hkv, c_max, 2, d, dtype=adtype, device=dev)
         self.score = torch.empty(rows, hkv, c_max, dtype=torch.float32, device=dev)
         self.sel_idx = torch.empty(rows, hkv, k_max, dtype=torch.int32, device=dev)
         self.sel_count = torch.empty(rows, hkv, dtype=torch.int32, device=dev)
         self.sel_tokens = torch.empty(rows, hkv, dtype=torch.int32, device=dev)
         self.out = torch.empty(rows, n_q_heads, d, dtype=torch.float32, device=dev)
         self.lse = torch.empty(rows, n_q_heads, dtype=torch.float32, device=dev)
-        self.shape_all = B.make_shape(rows, n_q_heads, hkv, d, n_ctx, c_max, k_max, dtype)
+        self.shape_all = B.make_shape(rows, n_q_heads, hkv, d, int(n_ctx), c_max, k_max, dtype)
         self.max_chunks, self.token_budget = int(max_chunks), int(token_budget)
+        self.qmeta = None
+        if quant:
+            self.qmeta = torch.zeros(rows, hkv, c_max, 8, dtype=torch.int32, device=dev)
+            for l, qm in enumerate(qmetas):
+                self.qmeta[l * batch:(l + 1) * batch, :, : qm.shape[2]] = qm
         self.layers = []
         for l in range(self.n_layers):
             sl = slice(l * batch, (l + 1) * batch)
             bufs = {n: getattr(self, n)[sl] for n in ("abstract", "score", "sel_idx", "sel_count", "sel_tokens", "out", "lse")}
-            self.layers.append(DecodeLayer(Ks[l], Vs[l], self.chunk_off[sl], self.n_chunks[sl], n_q_heads, k_max,
-                                           max_chunks, token_budget, buffers=bufs))
+            if quant:
+                self.layers.append(DecodeLayer(Ks[l], Vs[l], self.chunk_off[sl], self.n_chunks[sl], n_q_heads, k_max,
+                                               max_chunks, token_budget, qmeta=self.qmeta[sl], n_kv_heads=hkv,
+                                               n_ctx=int(n_ctx), head_dim=d, buffers=bufs))
+            else:
+                self.layers.append(DecodeLayer(Ks[l], Vs[l], self.chunk_off[sl], self.n_chunks[sl], n_q_heads, k_max,
+                                               max_chunks, token_budget, buffers=bufs))
         self.side = torch.cuda.Stream(device=dev)          # default priority, as the main stream
         self.scored = [torch.cuda.Event() for _ in range(self.n_layers)]
 
@@ -151,7 +170,7 @@ class DecodeStack:
             B.chunk_score(s, q_eval[l], lay.abstract, lay.n_chunks, lay.score, None)
             B.chunk_select_attention_decode(s, lay.score, q[l], lay.K, lay.V, lay.chunk_off, lay.n_chunks, lay.max_chunks,
                                             lay.token_budget, lay.scale, lay.sel_idx, lay.sel_count, lay.sel_tokens,
-                                            lay.out, lay.lse, lay.workspace)
+                                            lay.out, lay.lse, lay.workspace, None, lay.qmeta)
         return self.out
 
     def step_layer_ahead(self, q: torch.Tensor, q_eval: torch.Tensor = None) -> torch.Tensor:
@@ -165,7 +184,7 @@ class DecodeStack:
             main.wait_event(self.scored[l])
             B.chunk_select_attention_decode(lay.shape, lay.score, q[l], lay.K, lay.V, lay.chunk_off, lay.n_chunks,
                                             lay.max_chunks, lay.token_budget, lay.scale, lay.sel_idx, lay.sel_count,
-                                            lay.sel_tokens, lay.out, lay.lse, lay.workspace, main)
+                                            lay.sel_tokens, lay.out, lay.lse, lay.workspace, main, lay.qmeta)
         return self.out
 
     def step_scores_ahead(self, q: torch.Tensor, q_eval: torch.Tensor = None) -> torch.Tensor:
@@ -173,7 +192,7 @@ class DecodeStack:
         for l, lay in enumerate(self.layers):
             B.chunk_select_attention_decode(lay.shape, lay.score, q[l], lay.K, lay.V, lay.chunk_off, lay.n_chunks,
                                             lay.max_chunks, lay.token_budget, lay.scale, lay.sel_idx, lay.sel_count,
-                                            lay.sel_tokens, lay.out, lay.lse, lay.workspace)
+                                            lay.sel_tokens, lay.out, lay.lse, lay.workspace, None, lay.qmeta)
         return self.out
 
     def step_select_ahead(self, q: torch.Tensor, q_eval: torch.Tensor = None) -> torch.Tensor:
@@ -181,6 +200,6 @@ class DecodeStack:
         self.select_all()
         for l, lay in enumerate(self.layers):
             B.sparse_chunk_attention_decode(lay.shape, q[l], lay.K, lay.V, lay.chunk_off, lay.n_chunks, lay.sel_idx,
-                                            lay.sel_count, lay.scale, lay.out, lay.lse, lay.att_workspace)
+                                            lay.sel_count, lay.scale, lay.out, lay.lse, lay.att_workspace, None, lay.qmeta)
         return self.out
 

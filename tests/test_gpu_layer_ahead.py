@@ -123,3 +123,46 @@ def test_evaluation_with_an_earlier_query(L, oracle):
         sl = slice(l * stack.batch, (l + 1) * stack.batch)
         differs |= not np.array_equal(stack.sel_idx[sl].cpu().numpy()[:, :, : sel.shape[2]], sel)
     assert differs, "the evaluation queries were meant to change some kept list"
+
+
+def test_schedules_on_the_compressed_store(L, oracle):
+    """The 8-bit / 4-bit store: every schedule returns what the sequential order returns bit for bit (kept lists,
+    scores) and the oracle's attention on the stored codes within 2e-3."""
+    qcs = [gen.make_quant_case("c4", layer=l, n_ctx=16384 + 64, hq=8, hkv=2, token_budget=2048) for l in (0, 17, 31)]
+    cases = [qc.case for qc in qcs]
+    c = cases[0]
+    dev = lambda t: t.cuda().contiguous()
+    k_max = max(x.k_max for x in cases)
+    stack = L.DecodeStack([dev(qc.kblob) for qc in qcs], [dev(qc.vblob) for qc in qcs], [dev(x.chunk_off) for x in cases],
+                          [dev(x.n_chunks) for x in cases], c.hq, k_max, c.max_chunks, c.token_budget,
+                          qmetas=[dev(qc.qmeta) for qc in qcs], n_kv_heads=c.hkv, n_ctx=c.n_ctx)
+    stack.build_abstract()
+    q = torch.stack([dev(x.q) for x in cases]).contiguous()
+    poison(stack)
+    stack.step_sequential(q)
+    torch.cuda.synchronize()
+    want = snapshot(stack)
+    for l, qc in enumerate(qcs):
+        x = qc.case
+        off, nc = x.chunk_off.cpu(), x.n_chunks.cpu()
+        ab = oracle.abstract_build_q(qc.kblob, qc.qmeta, off, nc)
+        ub = oracle.chunk_score(x.q.cpu(), np.nan_to_num(ab), nc)
+        sel, cnt, tok = oracle.topk_select(ub, off, nc, x.max_chunks, x.token_budget, x.k_max)
+        out, _ = oracle.sparse_attention_q(x.q.cpu(), qc.kblob, qc.vblob, qc.qmeta, off, sel, cnt)
+        sl = slice(l * stack.batch, (l + 1) * stack.batch)
+        got = stack.sel_idx[sl].cpu().numpy()
+        assert np.array_equal(got[:, :, : sel.shape[2]], sel) and np.all(got[:, :, sel.shape[2]:] == -1), f"kept list of layer {l}"
+        assert np.abs(stack.out[sl].cpu().numpy().astype(np.float64) - out).max() <= 2e-3
+    for name in ("step_layer_ahead", "step_scores_ahead"):
+        poison(stack)
+        getattr(stack, name)(q)
+        torch.cuda.synchronize()
+        for what, a, b in zip(("score", "sel_idx", "sel_count", "sel_tokens", "out", "lse"), snapshot(stack), want):
+            assert torch.equal(a, b), f"{name}: {what} differs"
+    poison(stack)
+    stack.step_select_ahead(q)
+    torch.cuda.synchronize()
+    got = snapshot(stack)
+    for what, a, b in zip(("score", "sel_idx", "sel_count", "sel_tokens"), got, want):
+        assert torch.equal(a, b), f"step_select_ahead: {what} differs"
+    assert float((got[4] - want[4]).abs().max()) <= 1e-4      # (the separate attention call splits the kept tokens differently)
