@@ -261,6 +261,13 @@ int sparse_chunk_attention_decode(const leoam_shape* shape, const void* q, const
  * do not depend on scheduling.  Other shapes run the two kernels of the separate
  * calls back to back.  sel_idx / sel_count / sel_tokens are written as by
  * chunk_topk_select.
+ * score_ub == NULL: the selection was made earlier (for instance by one
+ * chunk_topk_select call over all layers of a step, Sec. 4.4: the evaluation runs
+ * ahead of the computation); sel_idx / sel_count are then INPUTS, as for
+ * sparse_chunk_attention_decode (ids outside [0, n_chunks) contribute no tokens,
+ * counts are clamped to [0, k_max]), max_chunks / token_budget / sel_tokens are
+ * not used, and the call only attends - in the same single kernel, with the
+ * in-launch merge, where the separate call needs a second kernel.
  * Workspace: leoam_fused_workspace_bytes() bytes, 16-byte aligned.  Its first
  * 4 * batch * n_kv_heads bytes (rounded up to 256) are arrival counters: they
  * must be ZERO when the call is issued and are zero again when it completes, so

@@ -255,8 +255,8 @@ int chunk_select_attention_decode(const leoam_shape* shape, const float* score_u
                                   size_t workspace_bytes, void* stream) {
     int rc = check_shape(shape);
     if (rc) return rc;
-    if (!score_ub || !q || !K || !V || !chunk_off || !n_chunks || !sel_idx || !sel_count || !out)
-        return LEOAM_E_INVALID_ARG;
+    // (score_ub == NULL: the kept lists are inputs and the call only attends)
+    if (!q || !K || !V || !chunk_off || !n_chunks || !sel_idx || !sel_count || !out) return LEOAM_E_INVALID_ARG;
     if (shape->k_max > attention_max_sel()) return LEOAM_E_UNSUPPORTED;
     if (shape->kv_dtype == LEOAM_Q8Q4) {
         if (!qmeta) return LEOAM_E_INVALID_ARG;
@@ -276,8 +276,8 @@ int chunk_select_attention_decode_static(const leoam_shape* shape, const float* 
                                          float* out, float* lse, void* stream) {
     int rc = check_shape(shape);
     if (rc) return rc;
-    if (!score_ub || !q || !K || !V || !chunk_off || !n_chunks || !sel_idx || !sel_count || !out)
-        return LEOAM_E_INVALID_ARG;
+    // (score_ub == NULL: the kept lists are inputs and the call only attends)
+    if (!q || !K || !V || !chunk_off || !n_chunks || !sel_idx || !sel_count || !out) return LEOAM_E_INVALID_ARG;
     if (shape->k_max > attention_max_sel()) return LEOAM_E_UNSUPPORTED;
     if (shape->kv_dtype == LEOAM_Q8Q4) {
         if (!qmeta) return LEOAM_E_INVALID_ARG;

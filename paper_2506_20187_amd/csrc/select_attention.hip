@@ -46,7 +46,10 @@ struct FusedKvTile {
     uint4 v[4];
 };
 
-template <typename T, int G, int kIpt>
+// kGiven: the kept lists (sel_idx, sel_count) are inputs - a selection made earlier, for instance by
+// one chunk_topk_select call over all layers of a step - and the workgroup only builds its tables
+// from them (two list positions per lane; kIpt is not used).
+template <typename T, int G, int kIpt, bool kGiven = false>
 __global__ __launch_bounds__(kSelThreads) void select_attention_kernel(
     const float* __restrict__ score, const int32_t* __restrict__ chunk_off, const int32_t* __restrict__ n_chunks,
     int max_chunks, int token_budget, int32_t* __restrict__ sel_idx, int32_t* __restrict__ sel_count,
@@ -86,40 +89,79 @@ __global__ __launch_bounds__(kSelThreads) void select_attention_kernel(
         }
     }
 
-    // ---- selection --------------------------------------------------------------
-    SelectResult<kIpt> R;
-    select_keep<kIpt>(ph.sel, score + bh * (size_t)c_max, off, C, c_max, k_max, n_ctx, max_chunks, token_budget, R);
-    const int cnt = (int)min((uint32_t)(R.kept_total >> 32), (uint32_t)k_max);
-    const int total = (int)(uint32_t)R.kept_total;
-    {
-        // kept chunks in ascending order: first token and number of kept tokens before it
-        int32_t* ids = sel_idx + bh * (size_t)k_max;
-        const int c0 = tid * kIpt;
-        uint32_t pos = (uint32_t)(R.kept_before >> 32), before = (uint32_t)R.kept_before;
-        int tok = R.first_tok;
+    int cnt, total;
+    if constexpr (kGiven) {
+        // ---- the kept list is given: first token and size of every listed chunk, then a scan --------
+        static_assert(kFusedMaxSel == 2 * kSelThreads, "two list positions per lane");
+        const int32_t* ids = sel_idx + bh * (size_t)k_max;
+        const int listed = min(max(sel_count[bh], 0), k_max);
+        int st[2];
+        uint32_t sz[2];
 #pragma unroll
-        for (int i = 0; i < kIpt; ++i) {
-            if (R.keep[i]) {
-                if (pos < (uint32_t)k_max) {
-                    start[pos] = tok;
-                    prefix[pos] = (int32_t)before;
-                    if (split == 0) ids[pos] = c0 + i;
-                }
-                ++pos;
-                before += R.size[i];
-            }
-            tok += (int)R.size[i];
+        for (int j = 0; j < 2; ++j) {
+            // (unconditional, clamped loads; an id outside [0, n_chunks) contributes no tokens)
+            const int p = 2 * tid + j;
+            const int id = ids[min(p, k_max - 1)];
+            const bool ok = p < listed && id >= 0 && id < C;
+            const int c = ok ? id : 0;
+            const int a = min(max(off[c], 0), n_ctx), e = min(max(off[c + 1], a), n_ctx);
+            st[j] = a;
+            sz[j] = ok ? (uint32_t)(e - a) : 0u;
         }
+        uint64_t tot;
+        uint32_t before = (uint32_t)block_excl_scan<false>(pack_tot(0, sz[0] + sz[1]), ph.sel.wave_sums2, &tot);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int p = 2 * tid + j;
+            if (p < listed) {
+                start[p] = st[j];
+                prefix[p] = (int32_t)before;
+            }
+            before += sz[j];
+        }
+        cnt = listed;
+        total = (int)(uint32_t)tot;
         if (tid == 0) prefix[cnt] = total;
         if (wave == 0) {
 #pragma unroll
             for (int s = 0; s < 4; ++s) qs[s][lane] = (c16 < G) ? qb[s] : make_uint4(0, 0, 0, 0);
         }
-        if (split == 0) {
-            for (int i = cnt + tid; i < k_max; i += kSelThreads) ids[i] = -1;
-            if (tid == 0) {
-                sel_count[bh] = cnt;
-                if (sel_tokens) sel_tokens[bh] = total;
+    } else {
+        // ---- selection --------------------------------------------------------------
+        SelectResult<kIpt> R;
+        select_keep<kIpt>(ph.sel, score + bh * (size_t)c_max, off, C, c_max, k_max, n_ctx, max_chunks, token_budget, R);
+        cnt = (int)min((uint32_t)(R.kept_total >> 32), (uint32_t)k_max);
+        total = (int)(uint32_t)R.kept_total;
+        {
+            // kept chunks in ascending order: first token and number of kept tokens before it
+            int32_t* ids = sel_idx + bh * (size_t)k_max;
+            const int c0 = tid * kIpt;
+            uint32_t pos = (uint32_t)(R.kept_before >> 32), before = (uint32_t)R.kept_before;
+            int tok = R.first_tok;
+#pragma unroll
+            for (int i = 0; i < kIpt; ++i) {
+                if (R.keep[i]) {
+                    if (pos < (uint32_t)k_max) {
+                        start[pos] = tok;
+                        prefix[pos] = (int32_t)before;
+                        if (split == 0) ids[pos] = c0 + i;
+                    }
+                    ++pos;
+                    before += R.size[i];
+                }
+                tok += (int)R.size[i];
+            }
+            if (tid == 0) prefix[cnt] = total;
+            if (wave == 0) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) qs[s][lane] = (c16 < G) ? qb[s] : make_uint4(0, 0, 0, 0);
+            }
+            if (split == 0) {
+                for (int i = cnt + tid; i < k_max; i += kSelThreads) ids[i] = -1;
+                if (tid == 0) {
+                    sel_count[bh] = cnt;
+                    if (sel_tokens) sel_tokens[bh] = total;
+                }
             }
         }
     }
@@ -376,7 +418,12 @@ static hipError_t launch_fused(const leoam_shape* s, const float* score, const v
                        max_chunks, token_budget, sel_idx, sel_count, sel_tokens, (const char*)q, (const char*)K,       \
                        (const char*)V, scale * kLog2e, out, lse, partial, arrivals, n_splits, s->c_max, s->k_max,      \
                        s->n_kv_heads, s->n_ctx)
-    if (s->c_max <= kSelThreads) LEOAM_FUSED(1);
+    if (!score)      // the kept lists are given
+        hipLaunchKernelGGL((select_attention_kernel<T, G, 1, true>), grid, block, 0, stream, score, chunk_off, n_chunks,
+                           max_chunks, token_budget, sel_idx, sel_count, sel_tokens, (const char*)q, (const char*)K,
+                           (const char*)V, scale * kLog2e, out, lse, partial, arrivals, n_splits, s->c_max, s->k_max,
+                           s->n_kv_heads, s->n_ctx);
+    else if (s->c_max <= kSelThreads) LEOAM_FUSED(1);
     else if (s->c_max <= 2 * kSelThreads) LEOAM_FUSED(2);
     else if (s->c_max <= 4 * kSelThreads) LEOAM_FUSED(4);
     else if (s->c_max <= 6 * kSelThreads) LEOAM_FUSED(6);
@@ -420,8 +467,9 @@ hipError_t select_attention_dispatch(const leoam_shape* s, const float* score, c
                                            (int)n, stream);
     }
     if (!select_attention_is_fused(s)) {
-        hipError_t e = topk_select_dispatch(s, score, chunk_off, n_chunks, max_chunks, token_budget, sel_idx, sel_count,
-                                            sel_tokens, stream);
+        hipError_t e = score ? topk_select_dispatch(s, score, chunk_off, n_chunks, max_chunks, token_budget, sel_idx,
+                                                    sel_count, sel_tokens, stream)
+                             : hipSuccess;
         if (e != hipSuccess) return e;
         // the attention kernel merges its splits in the same launch, with the arrival counters of this workspace
         return attention_dispatch(s, q, K, V, qmeta, chunk_off, n_chunks, sel_idx, sel_count, scale, out, lse, body,

@@ -26,7 +26,9 @@ constexpr int kFusedQMaxSel = 1024;                    // kept chunks per (b,h) 
 constexpr int kFusedQMaxSplits = 64;
 constexpr int kFusedQTargetWgs = 256;                  // one workgroup per compute unit
 
-template <int G, int kIpt>
+// kGiven: the kept lists (sel_idx, sel_count) are inputs and the workgroup only builds its tables from
+// them (one list position per lane; kIpt is not used).
+template <int G, int kIpt, bool kGiven = false>
 __global__ __launch_bounds__(kSelThreads) void select_attention_q_kernel(
     const float* __restrict__ score, const int32_t* __restrict__ chunk_off, const int32_t* __restrict__ n_chunks,
     int max_chunks, int token_budget, int32_t* __restrict__ sel_idx, int32_t* __restrict__ sel_count,
@@ -71,51 +73,75 @@ __global__ __launch_bounds__(kSelThreads) void select_attention_q_kernel(
         }
     }
 
-    // ---- selection --------------------------------------------------------------
-    SelectResult<kIpt> R;
-    select_keep<kIpt>(ph.sel, score + bh * (size_t)c_max, off, C, c_max, k_max, n_ctx, max_chunks, token_budget, R);
-    const int cnt = (int)min((uint32_t)(R.kept_total >> 32), (uint32_t)k_max);
-    const int total = (int)(uint32_t)R.kept_total;
-    {
-        // kept chunks in ascending order: their records and the number of kept tokens before them
-        int32_t* ids = sel_idx + bh * (size_t)k_max;
-        const int c0 = tid * kIpt;
-        uint32_t pos = (uint32_t)(R.kept_before >> 32), before = (uint32_t)R.kept_before;
+    auto stage_queries = [&] {
+        float sum = 0.f;
 #pragma unroll
-        for (int i = 0; i < kIpt; ++i) {
-            if (R.keep[i]) {
-                if (pos < (uint32_t)k_max) {
-                    const QChunk m = qmeta[bh * c_max + c0 + i];
-                    ch_off[pos] = m.byte_off;
-                    ch_bits[pos] = m.bits;
-                    ch_par[pos] = make_float4(m.scale_k, m.zero_k, m.scale_v, m.zero_v);
-                    prefix[pos] = (int32_t)before;
-                    if (split == 0) ids[pos] = c0 + i;
+        for (int s = 0; s < 4; ++s) {
+            qs[s][lane] = (c16 < G) ? query_operand(qraw[s]) : make_uint4(0, 0, 0, 0);
+            float x[EPL];
+            unpack<F16>(qraw[s], x);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) sum += x[e];
+        }
+        sum += shfl_xor_f(sum, 16);
+        sum += shfl_xor_f(sum, 32);
+        if (grp == 0) qsums[c16] = (c16 < G) ? sum : 0.f;
+    };
+    int cnt;
+    if constexpr (kGiven) {
+        // ---- the kept list is given: record and size of every listed chunk, then a scan ------------
+        static_assert(kFusedQMaxSel == kSelThreads, "one list position per lane");
+        const int listed = min(max(sel_count[bh], 0), k_max);
+        const int id = sel_idx[bh * (size_t)k_max + min(tid, k_max - 1)];
+        const bool ok = tid < listed && id >= 0 && id < C;
+        const int c = ok ? id : 0;
+        const int a = min(max(off[c], 0), n_ctx), e = min(max(off[c + 1], a), n_ctx);
+        const QChunk m = qmeta[bh * c_max + c];
+        uint64_t tot;
+        const uint32_t before = (uint32_t)block_excl_scan<false>(pack_tot(0, ok ? (uint32_t)(e - a) : 0u), ph.sel.wave_sums2, &tot);
+        if (tid < listed) {
+            ch_off[tid] = m.byte_off;
+            ch_bits[tid] = m.bits;
+            ch_par[tid] = make_float4(m.scale_k, m.zero_k, m.scale_v, m.zero_v);
+            prefix[tid] = (int32_t)before;
+        }
+        cnt = listed;
+        if (tid == 0) prefix[cnt] = (int32_t)(uint32_t)tot;
+        if (wave == 0) stage_queries();
+    } else {
+        // ---- selection --------------------------------------------------------------
+        SelectResult<kIpt> R;
+        select_keep<kIpt>(ph.sel, score + bh * (size_t)c_max, off, C, c_max, k_max, n_ctx, max_chunks, token_budget, R);
+        cnt = (int)min((uint32_t)(R.kept_total >> 32), (uint32_t)k_max);
+        const int total = (int)(uint32_t)R.kept_total;
+        {
+            // kept chunks in ascending order: their records and the number of kept tokens before them
+            int32_t* ids = sel_idx + bh * (size_t)k_max;
+            const int c0 = tid * kIpt;
+            uint32_t pos = (uint32_t)(R.kept_before >> 32), before = (uint32_t)R.kept_before;
+#pragma unroll
+            for (int i = 0; i < kIpt; ++i) {
+                if (R.keep[i]) {
+                    if (pos < (uint32_t)k_max) {
+                        const QChunk m = qmeta[bh * c_max + c0 + i];
+                        ch_off[pos] = m.byte_off;
+                        ch_bits[pos] = m.bits;
+                        ch_par[pos] = make_float4(m.scale_k, m.zero_k, m.scale_v, m.zero_v);
+                        prefix[pos] = (int32_t)before;
+                        if (split == 0) ids[pos] = c0 + i;
+                    }
+                    ++pos;
+                    before += R.size[i];
                 }
-                ++pos;
-                before += R.size[i];
             }
-        }
-        if (tid == 0) prefix[cnt] = total;
-        if (wave == 0) {
-            float sum = 0.f;
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                qs[s][lane] = (c16 < G) ? query_operand(qraw[s]) : make_uint4(0, 0, 0, 0);
-                float x[EPL];
-                unpack<F16>(qraw[s], x);
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) sum += x[e];
-            }
-            sum += shfl_xor_f(sum, 16);
-            sum += shfl_xor_f(sum, 32);
-            if (grp == 0) qsums[c16] = (c16 < G) ? sum : 0.f;
-        }
-        if (split == 0) {
-            for (int i = cnt + tid; i < k_max; i += kSelThreads) ids[i] = -1;
-            if (tid == 0) {
-                sel_count[bh] = cnt;
-                if (sel_tokens) sel_tokens[bh] = total;
+            if (tid == 0) prefix[cnt] = total;
+            if (wave == 0) stage_queries();
+            if (split == 0) {
+                for (int i = cnt + tid; i < k_max; i += kSelThreads) ids[i] = -1;
+                if (tid == 0) {
+                    sel_count[bh] = cnt;
+                    if (sel_tokens) sel_tokens[bh] = total;
+                }
             }
         }
     }
@@ -339,7 +365,12 @@ static hipError_t launch_fused_q(const leoam_shape* s, const float* score, const
                        max_chunks, token_budget, sel_idx, sel_count, sel_tokens, (const char*)q,                       \
                        (const unsigned char*)K, (const unsigned char*)V, (const QChunk*)qmeta, scale * kLog2e, out,    \
                        lse, partial, arrivals, n_splits, s->c_max, s->k_max, s->n_kv_heads, s->n_ctx)
-    if (s->c_max <= kSelThreads) LEOAM_FUSEDQ(1);
+    if (!score)      // the kept lists are given
+        hipLaunchKernelGGL((select_attention_q_kernel<G, 1, true>), grid, block, 0, stream, score, chunk_off, n_chunks,
+                           max_chunks, token_budget, sel_idx, sel_count, sel_tokens, (const char*)q,
+                           (const unsigned char*)K, (const unsigned char*)V, (const QChunk*)qmeta, scale * kLog2e, out,
+                           lse, partial, arrivals, n_splits, s->c_max, s->k_max, s->n_kv_heads, s->n_ctx);
+    else if (s->c_max <= kSelThreads) LEOAM_FUSEDQ(1);
     else if (s->c_max <= 2 * kSelThreads) LEOAM_FUSEDQ(2);
     else if (s->c_max <= 4 * kSelThreads) LEOAM_FUSEDQ(4);
     else if (s->c_max <= 6 * kSelThreads) LEOAM_FUSEDQ(6);

@@ -67,6 +67,13 @@ class DecodeLayer:
                                         self.out, self.lse, self.workspace, stream, self.qmeta)
         return self.out
 
+    def attend_given(self, q: torch.Tensor, stream=None) -> torch.Tensor:
+        """Attention over kept lists that are already in sel_idx / sel_count (one kernel, in-launch merge)."""
+        B.chunk_select_attention_decode(self.shape, None, q, self.K, self.V, self.chunk_off, self.n_chunks, self.max_chunks,
+                                        self.token_budget, self.scale, self.sel_idx, self.sel_count, self.sel_tokens,
+                                        self.out, self.lse, self.workspace, stream, self.qmeta)
+        return self.out
+
     def step_separate(self, q: torch.Tensor, stream=None) -> torch.Tensor:
         """The same step through the three separate entry points."""
         s = self.shape
@@ -95,7 +102,8 @@ class DecodeStack:
                            (same priority) while layer l selects and attends
       step_scores_ahead    one chunk_score over all layers, then per layer chunk_select_attention_decode
       step_select_ahead    one chunk_score and one chunk_topk_select over all layers, then per layer
-                           sparse_chunk_attention_decode
+                           chunk_select_attention_decode with the kept lists given (it only attends, in
+                           one kernel)
     `q_eval` [layers, B, Hq, D] are the queries the evaluation uses, `q` the ones attention uses; with
     q_eval == q every schedule returns exactly what step_sequential returns.
     """
@@ -199,7 +207,8 @@ class DecodeStack:
         self.score_all(q if q_eval is None else q_eval)
         self.select_all()
         for l, lay in enumerate(self.layers):
-            B.sparse_chunk_attention_decode(lay.shape, q[l], lay.K, lay.V, lay.chunk_off, lay.n_chunks, lay.sel_idx,
-                                            lay.sel_count, lay.scale, lay.out, lay.lse, lay.att_workspace, None, lay.qmeta)
+            B.chunk_select_attention_decode(lay.shape, None, q[l], lay.K, lay.V, lay.chunk_off, lay.n_chunks,
+                                            lay.max_chunks, lay.token_budget, lay.scale, lay.sel_idx, lay.sel_count,
+                                            lay.sel_tokens, lay.out, lay.lse, lay.workspace, None, lay.qmeta)
         return self.out
 

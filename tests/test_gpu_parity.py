@@ -579,6 +579,82 @@ def test_select_attention_one_call(L, oracle, dtype, G, C):
     assert int(ws[:head].to(torch.int32).sum()) == 0           # counters are back at zero
 
 
+@pytest.mark.parametrize("dtype,G,C", [("bf16", 4, 700), ("bf16", 4, 3000), ("f16", 1, 1500), ("f16", 2, 2047), ("bf16", 2, 40),
+                                       ("bf16", 8, 900), ("f32", 2, 900)])
+                                       # (the last two: shapes that take the separate attention kernels)
+def test_one_call_with_a_given_selection(L, oracle, dtype, G, C):
+    """chunk_select_attention_decode with score_ub = NULL: the kept lists are inputs (unsorted, with ids out of
+    range and an empty list among them) and the call only attends; against the oracle, for every number of
+    splits, and bit-identical from call to call on one workspace."""
+    rng = np.random.default_rng(2000 + C + G)
+    B, Hkv, D = 2, 2, 128
+    offs = []
+    for b in range(B):
+        n = C if b == 0 else max(2, C - int(rng.integers(0, C // 3 + 1)))
+        sizes = rng.integers(1, 9, size=n)
+        offs.append(np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32))
+    N = int(max(o[-1] for o in offs))
+    offs = [np.concatenate([o[:-1], [N]]).astype(np.int32) for o in offs]
+    packed, counts, c_max = gen.pack_boundaries(offs, N)
+    K = torch.from_numpy(rng.standard_normal((B, Hkv, N, D)).astype(np.float32)).to(TDT[dtype])
+    V = torch.from_numpy(rng.standard_normal((B, Hkv, N, D)).astype(np.float32)).to(TDT[dtype])
+    q = torch.from_numpy(rng.standard_normal((B, Hkv * G, D)).astype(np.float32) * 1.5).to(TDT[dtype])
+    k_max = min(c_max, 2048)
+    sel = np.full((B, Hkv, k_max), -1, dtype=np.int32)
+    cnt = np.zeros((B, Hkv), dtype=np.int32)
+    for b in range(B):
+        for h in range(Hkv):
+            n = int(rng.integers(1, min(counts[b], k_max)))
+            sel[b, h, :n] = rng.permutation(counts[b])[:n]           # any order
+            cnt[b, h] = n
+    cnt[1, 1] = 0                                     # one head keeps nothing
+    clean_sel = sel.copy()
+    sel[0, 0, 3] = counts[0] + 5                      # ids outside [0, n_chunks) contribute no tokens
+    sel[0, 1, 0] = -4
+    for bad in ((0, 0, 3), (0, 1, 0)):
+        clean_sel[bad] = -1
+    # the oracle takes the list without the bad ids (kept order, shorter count)
+    osel = np.full_like(sel, -1)
+    ocnt = cnt.copy()
+    for b in range(B):
+        for h in range(Hkv):
+            ids = [i for i in clean_sel[b, h, : cnt[b, h]] if i >= 0]
+            osel[b, h, : len(ids)] = ids
+            ocnt[b, h] = len(ids)
+    want, want_lse = oracle.sparse_attention(q, K, V, packed, osel, ocnt)
+    shape = L.make_shape(B, Hkv * G, Hkv, D, N, c_max, k_max, TDT[dtype])
+    dq, dK, dV, doff, dnc = dev(q), dev(K), dev(V), dev(packed), dev(counts)
+    dsel, dcnt = dev(sel), dev(cnt)
+    tok = torch.full((B, Hkv), -7, dtype=torch.int32, device="cuda")
+    head = (B * Hkv * 4 + 255) // 256 * 256
+    for n_splits in (None, 1, 2, 5):
+        nbytes = L.leoam_fused_workspace_bytes(shape, 0)
+        if n_splits is not None:
+            nbytes = max(head + n_splits * B * Hkv * G * (D + 2) * 4, head + 16)
+            if dtype == "f32" or G == 8:
+                nbytes = max(nbytes, L.leoam_fused_workspace_bytes(shape, 1))
+        ws = torch.empty((nbytes + 15) // 16 * 16, dtype=torch.uint8, device="cuda")
+        L.leoam_workspace_init(ws)
+        ws[head:] = 0xFF
+        first = None
+        for _ in range(3):
+            out = torch.full((B, Hkv * G, D), float("nan"), dtype=torch.float32, device="cuda")
+            lse = torch.full((B, Hkv * G), float("nan"), dtype=torch.float32, device="cuda")
+            L.chunk_select_attention_decode(shape, None, dq, dK, dV, doff, dnc, 0, 0, L.default_scale(D), dsel, dcnt, tok,
+                                            out, lse, ws)
+            torch.cuda.synchronize()
+            got, got_lse = out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
+            assert np.abs(got - want).max() <= TOL[dtype], f"splits={n_splits}"
+            fin = np.isfinite(want_lse)
+            assert np.array_equal(np.isneginf(got_lse), np.isneginf(want_lse))
+            assert np.abs(got_lse[fin] - want_lse[fin]).max() <= 1e-4
+            assert np.all(got[1, G:2 * G] == 0)
+            first = (got, got_lse) if first is None else first
+            assert np.array_equal(got, first[0]) and np.array_equal(got_lse, first[1])
+        assert int(ws[:head].to(torch.int32).sum()) == 0           # counters are back at zero
+    assert torch.equal(dsel, dev(sel)) and torch.equal(dcnt, dev(cnt)) and int(tok.min()) == -7      # inputs untouched
+
+
 # ---------------------------------------------------------------------------
 # tree-structured chunk refinement (Sec. 4.2)
 # ---------------------------------------------------------------------------
