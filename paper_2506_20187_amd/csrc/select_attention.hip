@@ -29,6 +29,8 @@
 // groups is taken with lane swaps on the vector ALU (two ds_bpermute round trips
 // per tile in its place cost the launch 10 % on MI355X, the next tile's loads
 // queue behind the same waits).
+#include <cstdlib>
+
 #include "fused_tail.h"
 
 namespace leoam {
@@ -359,6 +361,17 @@ hipError_t select_attention_q_dispatch(const leoam_shape*, const float*, const v
                                        const int32_t*, const int32_t*, int, int, float, int32_t*, int32_t*, int32_t*,
                                        float*, float*, float*, int32_t*, int, hipStream_t);
 
+// LEOAM_STREAM_ORDERED_MERGE=1 in the environment (read once per process) makes the one-call entry points run
+// the selection kernel, the attention kernel and the merge kernel back to back instead of the one-launch
+// kernels, whose in-launch merge relies on the memory system's behaviour rather than on the memory model.
+static bool stream_ordered_merge_wanted() {
+    static const bool wanted = [] {
+        const char* v = getenv("LEOAM_STREAM_ORDERED_MERGE");
+        return v && v[0] && v[0] != '0';
+    }();
+    return wanted;
+}
+
 static inline size_t arrival_bytes(const leoam_shape* s) {
     const size_t n = (size_t)s->batch * s->n_kv_heads * sizeof(int32_t);
     return (n + kArrivalAlign - 1) / kArrivalAlign * kArrivalAlign;
@@ -404,7 +417,8 @@ size_t select_attention_workspace_bytes(const leoam_shape* s, int max_tokens) {
 size_t select_attention_counter_bytes(const leoam_shape* s) { return arrival_bytes(s); }
 
 size_t select_attention_min_workspace_bytes(const leoam_shape* s) {
-    return arrival_bytes(s) + ((select_attention_is_fused(s) || select_attention_q_is_fused(s)) ? 0 : attention_min_workspace_bytes(s));
+    const bool one_launch = (select_attention_is_fused(s) || select_attention_q_is_fused(s)) && !stream_ordered_merge_wanted();
+    return arrival_bytes(s) + (one_launch ? 0 : attention_min_workspace_bytes(s));
 }
 
 template <typename T, int G>
@@ -456,6 +470,17 @@ hipError_t select_attention_dispatch(const leoam_shape* s, const float* score, c
     const size_t head = arrival_bytes(s);
     char* body = (char*)workspace + head;
     const size_t body_bytes = workspace_bytes - head;
+    if (stream_ordered_merge_wanted()) {
+        // the kernels of the separate calls, splits combined by a kernel of their own: every hand-over
+        // between workgroups is then ordered by the stream
+        if (body_bytes < attention_min_workspace_bytes(s)) return hipErrorInvalidValue;
+        hipError_t e = score ? topk_select_dispatch(s, score, chunk_off, n_chunks, max_chunks, token_budget, sel_idx,
+                                                    sel_count, sel_tokens, stream)
+                             : hipSuccess;
+        if (e != hipSuccess) return e;
+        return attention_dispatch(s, q, K, V, qmeta, chunk_off, n_chunks, sel_idx, sel_count, scale, out, lse, body,
+                                  body_bytes, nullptr, stream);
+    }
     if (select_attention_q_is_fused(s)) {
         // the compressed store's one-launch kernel (select_attention_q.hip)
         size_t n = body_bytes / fused_part_bytes_per_split(s);

@@ -655,6 +655,38 @@ def test_one_call_with_a_given_selection(L, oracle, dtype, G, C):
     assert torch.equal(dsel, dev(sel)) and torch.equal(dcnt, dev(cnt)) and int(tok.min()) == -7      # inputs untouched
 
 
+def test_stream_ordered_merge_switch(L, tmp_path):
+    """LEOAM_STREAM_ORDERED_MERGE=1 (read once per process, so a child process) makes the one-call entry point run
+    the selection, attention and merge kernels back to back: same kept lists bit for bit, outputs within float
+    rounding of a different split of the kept tokens."""
+    import os
+    import subprocess
+    import sys
+    code = r"""
+import sys, numpy as np, torch
+sys.path.insert(0, sys.argv[1])
+import gen, paper_2506_20187_amd as L
+case = gen.make_case("c3", layer=9, batch=3, n_ctx=8192 + 100, hq=8, hkv=2, token_budget=1024, device="cuda")
+lay = L.DecodeLayer(case.K, case.V, case.chunk_off, case.n_chunks, case.hq, case.k_max, case.max_chunks, case.token_budget)
+lay.build_abstract()
+lay.step(case.q)
+torch.cuda.synchronize()
+np.savez(sys.argv[2], sel=lay.sel_idx.cpu().numpy(), cnt=lay.sel_count.cpu().numpy(), tok=lay.sel_tokens.cpu().numpy(),
+         out=lay.out.cpu().numpy(), lse=lay.lse.cpu().numpy())
+"""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = {}
+    for tag, val in (("in_launch", "0"), ("stream_ordered", "1")):
+        path = str(tmp_path / f"{tag}.npz")
+        env = dict(os.environ, LEOAM_STREAM_ORDERED_MERGE=val)
+        subprocess.run([sys.executable, "-c", code, root, path], check=True, env=env, timeout=300)
+        res[tag] = np.load(path)
+    a, b = res["in_launch"], res["stream_ordered"]
+    for k in ("sel", "cnt", "tok"):
+        assert np.array_equal(a[k], b[k]), k
+    assert np.abs(a["out"] - b["out"]).max() <= 1e-4 and np.abs(a["lse"] - b["lse"]).max() <= 1e-4
+
+
 # ---------------------------------------------------------------------------
 # tree-structured chunk refinement (Sec. 4.2)
 # ---------------------------------------------------------------------------
