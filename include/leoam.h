@@ -275,11 +275,13 @@ int sparse_chunk_attention_decode(const leoam_shape* shape, const void* q, const
  * not used, and the call only attends - in the same single kernel, with the
  * in-launch merge, where the separate call needs a second kernel.
  * Workspace: leoam_fused_workspace_bytes() bytes, 16-byte aligned.  Its first
- * 4 * batch * n_kv_heads bytes (rounded up to 256) are arrival counters: they
- * must be ZERO when the call is issued and are zero again when it completes, so
- * a workspace is cleared once (leoam_workspace_init) and then reused; the rest
- * needs no initialisation.  A smaller workspace gives fewer splits.  Calls that
- * share a workspace must not overlap.
+ * leoam_fused_control_bytes() bytes are control words (arrival counters of the
+ * (b,h) pairs and, for batch sizes that give two splits per (b,h), one 64-bit
+ * exchange word per (b, q head, channel)): they must be ZERO when the call is
+ * issued and are zero again when it completes, so a workspace is cleared once
+ * (leoam_workspace_init) and then reused; the rest needs no initialisation.  A
+ * smaller workspace gives fewer splits.  Calls that share a workspace must not
+ * overlap.
  */
 int chunk_select_attention_decode(const leoam_shape* shape, const float* score_ub, const void* q, const void* K,
                                   const void* V, const void* qmeta, const int32_t* chunk_off, const int32_t* n_chunks,
@@ -315,6 +317,10 @@ int chunk_select_attention_decode_static(const leoam_shape* shape, const float* 
 /* Bytes of workspace chunk_select_attention_decode wants when at most
  * `max_tokens` tokens are kept per (b,h) (<= 0: n_ctx).  0 on a bad shape. */
 size_t leoam_fused_workspace_bytes(const leoam_shape* shape, int32_t max_tokens);
+
+/* Leading bytes of that workspace that must be zero when chunk_select_attention_decode
+ * is issued (and are zero again when it completes).  0 on a bad shape. */
+size_t leoam_fused_control_bytes(const leoam_shape* shape);
 
 /* Zero-fills a workspace (size a multiple of 16, 16-byte aligned) on `stream`. */
 int leoam_workspace_init(void* workspace, size_t workspace_bytes, void* stream);

@@ -67,6 +67,8 @@ def _load() -> ctypes.CDLL:
     lib.leoam_workspace_bytes.restype = sz
     lib.leoam_fused_workspace_bytes.argtypes = [sp, i32]
     lib.leoam_fused_workspace_bytes.restype = sz
+    lib.leoam_fused_control_bytes.argtypes = [sp]
+    lib.leoam_fused_control_bytes.restype = sz
     lib.leoam_workspace_init.argtypes = [vp, sz, vp]
     lib.leoam_validate_boundaries.argtypes = [sp, vp, vp, vp]
     lib.leoam_copy_probe.argtypes = [vp, vp, sz, vp]
@@ -86,6 +88,7 @@ _lib = _load()
 
 EXPORTS = ("kv_chunk_abstract_build", "chunk_score", "chunk_score_pin", "chunk_topk_select", "sparse_chunk_attention_decode",
            "chunk_select_attention_decode", "chunk_select_attention_decode_static", "leoam_fused_workspace_bytes",
+           "leoam_fused_control_bytes",
            "leoam_workspace_init",
            "kv_chunk_abstract_append", "leoam_tree_evaluations", "chunk_tree_refine", "leoam_tree_workspace_bytes",
            "kv_chunk_compress", "kv_chunk_recompress", "chunk_compression_tags", "leoam_compressed_bytes_bound", "leoam_compression_share",
@@ -247,6 +250,10 @@ def chunk_select_attention_decode_static(shape: Shape, score_ub, q, K, V, chunk_
 
 def leoam_fused_workspace_bytes(shape: Shape, max_tokens: int) -> int:
     return int(_lib.leoam_fused_workspace_bytes(ctypes.byref(shape), int(max_tokens)))
+
+
+def leoam_fused_control_bytes(shape: Shape) -> int:
+    return int(_lib.leoam_fused_control_bytes(ctypes.byref(shape)))
 
 
 def leoam_workspace_init(workspace, stream=None) -> None:

@@ -12,10 +12,17 @@ namespace leoam {
 constexpr int kFusedWaves = kSelWaves;                 // 16
 constexpr int kFusedMergeBatch = 16;
 
+// `exchange` (two splits only, else nullptr): one 64-bit word per (b, q head, channel), zero between calls.
+// The two workgroups of a (sequence, kv head) then combine without a ticket and without waiting for
+// store acknowledgements: every lane swaps its normalised result (o / l, m + log2 l) into the word
+// with ONE atomic exchange; the lane that finds the other split's pair there combines the two, in
+// split order, writes the output and puts the word back to zero.  The value travels inside the atomic
+// itself, so nothing depends on the order of separate memory operations.
 template <int G>
 __device__ __forceinline__ void fused_tail(float (*xw)[G][kPartStride], int32_t& sh_last, float* partial,
                                            int32_t* arrivals, float* __restrict__ out, float* __restrict__ lse,
-                                           size_t bh, int split, int n_splits) {
+                                           size_t bh, int split, int n_splits,
+                                           unsigned long long* exchange = nullptr) {
     const int tid = threadIdx.x;
     // ---- fold the waves: lane (g, d) gets the split's (m, l, o[d]) ----------------
     const int g = tid >> 7, d = tid & (LEOAM_D - 1);
@@ -32,6 +39,30 @@ __device__ __forceinline__ void fused_tail(float (*xw)[G][kPartStride], int32_t&
         }
     }
     const size_t bj = bh * G + g;
+    if (n_splits == 2 && exchange != nullptr) {
+        if (!owner) return;
+        // w = log2 of this split's softmax denominator, on = its normalised output; the high word of a
+        // published pair is never zero (+0 travels as -0), which is what marks the word as taken
+        const float w = (l > 0.f) ? m + log2f(l) : -INFINITY;
+        const float on = (l > 0.f) ? o / l : 0.f;
+        uint32_t wb = float_to_bits(w);
+        if (wb == 0u) wb = 0x80000000u;
+        const unsigned long long mine = ((unsigned long long)wb << 32) | float_to_bits(on);
+        unsigned long long* slot = exchange + bj * LEOAM_D + d;
+        const unsigned long long other = __hip_atomic_exchange(slot, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((uint32_t)(other >> 32) == 0u) return;          // first to arrive: the other split's lane combines
+        __hip_atomic_store(slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float w_o = bits_to_float((uint32_t)(other >> 32)), on_o = bits_to_float((uint32_t)other);
+        // operands in split order, so that the result does not depend on which split arrived last
+        const float w0 = split == 0 ? w : w_o, w1 = split == 0 ? w_o : w;
+        const float o0 = split == 0 ? on : on_o, o1 = split == 0 ? on_o : on;
+        const float wm = fmaxf(w0, w1);
+        const float e0 = exp2_or_zero(w0, wm), e1 = exp2_or_zero(w1, wm);
+        const float den = e0 + e1;
+        out[bj * LEOAM_D + d] = (den > 0.f) ? (o0 * e0 + o1 * e1) / den : 0.f;
+        if (lse && d == 0) lse[bj] = (den > 0.f) ? (wm + log2f(den)) * kLn2 : -INFINITY;
+        return;
+    }
     if (n_splits > 1) {
         // publish the partial, take a ticket; the last workgroup to arrive merges
         float* mine = partial + (bj * (size_t)n_splits + split) * kPartStride;

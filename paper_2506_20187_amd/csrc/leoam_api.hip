@@ -22,10 +22,10 @@ size_t attention_min_workspace_bytes(const leoam_shape*);
 int attention_max_sel();
 hipError_t select_attention_dispatch(const leoam_shape*, const float*, const void*, const void*, const void*, const void*,
                                      const int32_t*, const int32_t*, int, int, float, int32_t*, int32_t*, int32_t*,
-                                     float*, float*, void*, size_t, hipStream_t);
-size_t select_attention_workspace_bytes(const leoam_shape*, int);
-size_t select_attention_min_workspace_bytes(const leoam_shape*);
-size_t select_attention_counter_bytes(const leoam_shape*);
+                                     float*, float*, void*, size_t, hipStream_t, bool with_exchange = true);
+size_t select_attention_workspace_bytes(const leoam_shape*, int, bool with_exchange = true);
+size_t select_attention_min_workspace_bytes(const leoam_shape*, bool with_exchange = true);
+size_t select_attention_counter_bytes(const leoam_shape*, bool with_exchange = true);
 hipError_t workspace_zero_dispatch(void*, size_t, hipStream_t);
 size_t tree_workspace_bytes(const leoam_shape*, int);
 hipError_t tree_refine_dispatch(const leoam_shape*, const void*, const void*, const void*, int, int, int, int, int32_t*,
@@ -284,24 +284,29 @@ int chunk_select_attention_decode_static(const leoam_shape* shape, const float* 
         if (shape->k_max > attention_q_max_sel()) return LEOAM_E_UNSUPPORTED;
     }
     // the smallest workspace the call can run with must fit the static buffer
-    if (select_attention_min_workspace_bytes(shape) > (size_t)LEOAM_STATIC_SCRATCH_BYTES) return LEOAM_E_WORKSPACE;
+    if (select_attention_min_workspace_bytes(shape, false) > (size_t)LEOAM_STATIC_SCRATCH_BYTES) return LEOAM_E_WORKSPACE;
     void* ws = static_scratch_ptr();
     if (!ws) return LEOAM_E_HIP;
-    size_t bytes = select_attention_workspace_bytes(shape, token_budget);
+    size_t bytes = select_attention_workspace_bytes(shape, token_budget, false);
     if (bytes > (size_t)LEOAM_STATIC_SCRATCH_BYTES) bytes = (size_t)LEOAM_STATIC_SCRATCH_BYTES;      // fewer splits
     // The buffer keeps what the last call on this GPU left, and that call may have had another shape
     // (its partials where this one's arrival counters lie): the counters are cleared here, by a fill
     // kernel (a memset node is not safe to record into a HIP graph on this platform).
-    hipError_t e = workspace_zero_dispatch(ws, select_attention_counter_bytes(shape), (hipStream_t)stream);
+    hipError_t e = workspace_zero_dispatch(ws, select_attention_counter_bytes(shape, false), (hipStream_t)stream);
     if (e != hipSuccess) return LEOAM_E_HIP;
     return from_hip(select_attention_dispatch(shape, score_ub, q, K, V, qmeta, chunk_off, n_chunks, max_chunks,
                                               token_budget, softmax_scale, sel_idx, sel_count, sel_tokens, out, lse, ws,
-                                              bytes, (hipStream_t)stream));
+                                              bytes, (hipStream_t)stream, false));
 }
 
 size_t leoam_fused_workspace_bytes(const leoam_shape* shape, int32_t max_tokens) {
     if (check_shape(shape)) return 0;
     return select_attention_workspace_bytes(shape, max_tokens);
+}
+
+size_t leoam_fused_control_bytes(const leoam_shape* shape) {
+    if (check_shape(shape)) return 0;
+    return select_attention_counter_bytes(shape);
 }
 
 int leoam_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {

@@ -57,7 +57,7 @@ __global__ __launch_bounds__(kSelThreads) void select_attention_kernel(
     int max_chunks, int token_budget, int32_t* __restrict__ sel_idx, int32_t* __restrict__ sel_count,
     int32_t* __restrict__ sel_tokens, const char* __restrict__ q, const char* __restrict__ K,
     const char* __restrict__ V, float scale_log2, float* __restrict__ out, float* __restrict__ lse, float* partial,
-    int32_t* arrivals, int n_splits, int c_max, int k_max, int n_kv_heads, int n_ctx) {
+    int32_t* arrivals, int n_splits, int c_max, int k_max, int n_kv_heads, int n_ctx, unsigned long long* exchange) {
     constexpr int ROWB = LEOAM_D * 2;
     constexpr int EPL = 8;
     static_assert(G <= 4, "the fused kernel keeps 8 accumulators per head per lane");
@@ -329,7 +329,7 @@ __global__ __launch_bounds__(kSelThreads) void select_attention_kernel(
     }
     __syncthreads();
 
-    fused_tail<G>(ph.xw, sh_last, partial, arrivals, out, lse, bh, split, n_splits);
+    fused_tail<G>(ph.xw, sh_last, partial, arrivals, out, lse, bh, split, n_splits, exchange);
 }
 
 // zero fill (arrival counters of a fresh workspace)
@@ -399,9 +399,23 @@ static int fused_recommended_splits(const leoam_shape* s, int max_tokens) {
     return want;
 }
 
-// arrival counters, then whichever is larger: the fused kernel's partials or the
+// Exchange words of the two-split merge (fused_tail.h): one 64-bit word per (b, q head, channel), zero
+// between calls like the arrival counters.  Reserved for the batch sizes that give two splits per
+// (b, h), i.e. between half a workgroup and one workgroup per compute unit.
+static inline size_t exchange_bytes(const leoam_shape* s) {
+    const long long units = (long long)s->batch * s->n_kv_heads;
+    if (!select_attention_is_fused(s) || (kFusedTargetWgs + units - 1) / units != 2) return 0;
+    return (size_t)s->batch * s->n_q_heads * LEOAM_D * sizeof(unsigned long long);
+}
+
+// the leading bytes of the workspace that are zero between calls
+static inline size_t control_bytes(const leoam_shape* s, bool with_exchange) {
+    return arrival_bytes(s) + (with_exchange ? exchange_bytes(s) : 0);
+}
+
+// control words, then whichever is larger: the fused kernel's partials or the
 // workspace of the two-launch path that shapes outside the fused kernel take
-size_t select_attention_workspace_bytes(const leoam_shape* s, int max_tokens) {
+size_t select_attention_workspace_bytes(const leoam_shape* s, int max_tokens, bool with_exchange) {
     size_t body = attention_workspace_bytes(s, max_tokens);
     if (select_attention_is_fused(s)) {
         const size_t f = fused_part_bytes_per_split(s) * (size_t)fused_recommended_splits(s, max_tokens);
@@ -411,32 +425,33 @@ size_t select_attention_workspace_bytes(const leoam_shape* s, int max_tokens) {
         const size_t f = fused_part_bytes_per_split(s) * (size_t)fused_q_recommended_splits(s, max_tokens);
         if (f > body) body = f;
     }
-    return arrival_bytes(s) + body;
+    return control_bytes(s, with_exchange) + body;
 }
 
-size_t select_attention_counter_bytes(const leoam_shape* s) { return arrival_bytes(s); }
+size_t select_attention_counter_bytes(const leoam_shape* s, bool with_exchange) { return control_bytes(s, with_exchange); }
 
-size_t select_attention_min_workspace_bytes(const leoam_shape* s) {
+size_t select_attention_min_workspace_bytes(const leoam_shape* s, bool with_exchange) {
     const bool one_launch = (select_attention_is_fused(s) || select_attention_q_is_fused(s)) && !stream_ordered_merge_wanted();
-    return arrival_bytes(s) + (one_launch ? 0 : attention_min_workspace_bytes(s));
+    return control_bytes(s, with_exchange) + (one_launch ? 0 : attention_min_workspace_bytes(s));
 }
 
 template <typename T, int G>
 static hipError_t launch_fused(const leoam_shape* s, const float* score, const void* q, const void* K, const void* V,
                                const int32_t* chunk_off, const int32_t* n_chunks, int max_chunks, int token_budget,
                                float scale, int32_t* sel_idx, int32_t* sel_count, int32_t* sel_tokens, float* out,
-                               float* lse, float* partial, int32_t* arrivals, int n_splits, hipStream_t stream) {
+                               float* lse, float* partial, int32_t* arrivals, int n_splits, unsigned long long* exchange,
+                               hipStream_t stream) {
     dim3 grid(n_splits, s->n_kv_heads, s->batch), block(kSelThreads);
 #define LEOAM_FUSED(IPT)                                                                                              \
     hipLaunchKernelGGL((select_attention_kernel<T, G, IPT>), grid, block, 0, stream, score, chunk_off, n_chunks,       \
                        max_chunks, token_budget, sel_idx, sel_count, sel_tokens, (const char*)q, (const char*)K,       \
                        (const char*)V, scale * kLog2e, out, lse, partial, arrivals, n_splits, s->c_max, s->k_max,      \
-                       s->n_kv_heads, s->n_ctx)
+                       s->n_kv_heads, s->n_ctx, exchange)
     if (!score)      // the kept lists are given
         hipLaunchKernelGGL((select_attention_kernel<T, G, 1, true>), grid, block, 0, stream, score, chunk_off, n_chunks,
                            max_chunks, token_budget, sel_idx, sel_count, sel_tokens, (const char*)q, (const char*)K,
                            (const char*)V, scale * kLog2e, out, lse, partial, arrivals, n_splits, s->c_max, s->k_max,
-                           s->n_kv_heads, s->n_ctx);
+                           s->n_kv_heads, s->n_ctx, exchange);
     else if (s->c_max <= kSelThreads) LEOAM_FUSED(1);
     else if (s->c_max <= 2 * kSelThreads) LEOAM_FUSED(2);
     else if (s->c_max <= 4 * kSelThreads) LEOAM_FUSED(4);
@@ -450,10 +465,11 @@ template <typename T>
 static hipError_t fused_by_group(const leoam_shape* s, const float* score, const void* q, const void* K, const void* V,
                                  const int32_t* chunk_off, const int32_t* n_chunks, int max_chunks, int token_budget,
                                  float scale, int32_t* sel_idx, int32_t* sel_count, int32_t* sel_tokens, float* out,
-                                 float* lse, float* partial, int32_t* arrivals, int n_splits, hipStream_t stream) {
+                                 float* lse, float* partial, int32_t* arrivals, int n_splits,
+                                 unsigned long long* exchange, hipStream_t stream) {
 #define LEOAM_FG(GG)                                                                                                   \
     launch_fused<T, GG>(s, score, q, K, V, chunk_off, n_chunks, max_chunks, token_budget, scale, sel_idx, sel_count,   \
-                        sel_tokens, out, lse, partial, arrivals, n_splits, stream)
+                        sel_tokens, out, lse, partial, arrivals, n_splits, exchange, stream)
     switch (s->n_q_heads / s->n_kv_heads) {
     case 1: return LEOAM_FG(1);
     case 2: return LEOAM_FG(2);
@@ -466,10 +482,13 @@ hipError_t select_attention_dispatch(const leoam_shape* s, const float* score, c
                                      const void* V, const void* qmeta, const int32_t* chunk_off,
                                      const int32_t* n_chunks, int max_chunks, int token_budget, float scale,
                                      int32_t* sel_idx, int32_t* sel_count, int32_t* sel_tokens, float* out, float* lse,
-                                     void* workspace, size_t workspace_bytes, hipStream_t stream) {
-    const size_t head = arrival_bytes(s);
+                                     void* workspace, size_t workspace_bytes, hipStream_t stream, bool with_exchange) {
+    const size_t head = control_bytes(s, with_exchange);
     char* body = (char*)workspace + head;
     const size_t body_bytes = workspace_bytes - head;
+    unsigned long long* exchange = (with_exchange && exchange_bytes(s) > 0)
+                                       ? (unsigned long long*)((char*)workspace + arrival_bytes(s))
+                                       : nullptr;
     if (stream_ordered_merge_wanted()) {
         // the kernels of the separate calls, splits combined by a kernel of their own: every hand-over
         // between workgroups is then ordered by the stream
@@ -507,9 +526,10 @@ hipError_t select_attention_dispatch(const leoam_shape* s, const float* score, c
     const int n_splits = (int)n;
     if (s->kv_dtype == LEOAM_F16)
         return fused_by_group<F16>(s, score, q, K, V, chunk_off, n_chunks, max_chunks, token_budget, scale, sel_idx,
-                                   sel_count, sel_tokens, out, lse, (float*)body, (int32_t*)workspace, n_splits, stream);
+                                   sel_count, sel_tokens, out, lse, (float*)body, (int32_t*)workspace, n_splits, exchange,
+                                   stream);
     return fused_by_group<BF16>(s, score, q, K, V, chunk_off, n_chunks, max_chunks, token_budget, scale, sel_idx,
-                                sel_count, sel_tokens, out, lse, (float*)body, (int32_t*)workspace, n_splits, stream);
+                                sel_count, sel_tokens, out, lse, (float*)body, (int32_t*)workspace, n_splits, exchange, stream);
 }
 
 }  // namespace leoam

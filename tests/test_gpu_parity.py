@@ -471,6 +471,17 @@ def test_path_c3_reduced_batch(L, oracle, separate):
     check_path(L, oracle, case, separate=separate)
 
 
+def test_path_two_splits_per_head(L, oracle):
+    """16 sequences x 8 kv heads: two workgroups per (sequence, kv head), combined through the exchange words of the
+    workspace (one atomic exchange per output element); ragged context, small budget."""
+    case = gen.make_case("c3", layer=20, batch=16, n_ctx=4096 + 37, hq=32, hkv=8, token_budget=768)
+    check_path(L, oracle, case)
+    case = gen.make_case("c3", layer=2, batch=16, n_ctx=2048 + 5, hq=16, hkv=8, token_budget=8)      # nothing fits
+    layer = run_path(L, case)
+    assert int(layer.sel_count.abs().sum()) == 0 and torch.all(layer.out == 0) and torch.all(torch.isneginf(layer.lse))
+    assert not layer.workspace[: L.leoam_fused_control_bytes(layer.shape)].any()
+
+
 @SEPARATE
 def test_path_empty_selection(L, oracle, separate):
     case = gen.make_case("c2", layer=3, n_ctx=4096, hq=4, hkv=1, token_budget=8)     # every chunk has >= 16 tokens
@@ -511,11 +522,11 @@ def gpu_select_attend(L, dtype, score, q, K, V, packed, counts, max_chunks, budg
     lse = torch.full((B, Hq), float("nan"), dtype=torch.float32, device="cuda")
     if ws is None:
         nbytes = L.leoam_fused_workspace_bytes(shape, budget)
-        if n_splits is not None:      # counters + room for exactly n_splits partials
-            nbytes = (B * Hkv * 4 + 255) // 256 * 256 + n_splits * B * Hq * (D + 2) * 4
+        head = L.leoam_fused_control_bytes(shape)
+        if n_splits is not None:      # control words + room for exactly n_splits partials
+            nbytes = head + n_splits * B * Hq * (D + 2) * 4
         ws = torch.empty((nbytes + 15) // 16 * 16, dtype=torch.uint8, device="cuda")
         L.leoam_workspace_init(ws)
-        head = (B * Hkv * 4 + 255) // 256 * 256
         ws[head:] = 0xFF               # the partials area needs no initialisation: poison it (NaN patterns)
     L.chunk_select_attention_decode(shape, dev(score), dev(q), dev(K), dev(V), dev(packed), dev(counts), max_chunks,
                                     budget, L.default_scale(D), sel, cnt, tok, out, lse, ws)
@@ -575,8 +586,8 @@ def test_select_attention_one_call(L, oracle, dtype, G, C):
         assert np.array_equal(sel, want_sel) and np.abs(out - want_out).max() <= TOL[dtype]
         first = (out, lse) if first is None else first
         assert np.array_equal(out, first[0]) and np.array_equal(lse, first[1])
-    head = (B * Hkv * 4 + 255) // 256 * 256
-    assert int(ws[:head].to(torch.int32).sum()) == 0           # counters are back at zero
+    head = L.leoam_fused_control_bytes(L.make_shape(B, Hkv * G, Hkv, D, N, c_max, k_max, TDT[dtype]))
+    assert int(ws[:head].to(torch.int32).sum()) == 0           # control words are back at zero
 
 
 @pytest.mark.parametrize("dtype,G,C", [("bf16", 4, 700), ("bf16", 4, 3000), ("f16", 1, 1500), ("f16", 2, 2047), ("bf16", 2, 40),
@@ -626,7 +637,7 @@ def test_one_call_with_a_given_selection(L, oracle, dtype, G, C):
     dq, dK, dV, doff, dnc = dev(q), dev(K), dev(V), dev(packed), dev(counts)
     dsel, dcnt = dev(sel), dev(cnt)
     tok = torch.full((B, Hkv), -7, dtype=torch.int32, device="cuda")
-    head = (B * Hkv * 4 + 255) // 256 * 256
+    head = L.leoam_fused_control_bytes(shape)
     for n_splits in (None, 1, 2, 5):
         nbytes = L.leoam_fused_workspace_bytes(shape, 0)
         if n_splits is not None:

@@ -135,7 +135,7 @@ def test_quant_one_call_equals_separate_calls(L, oracle, n_ctx, G):
     if n_ctx == 786432:
         assert 10240 < lay.shape.c_max <= 12288         # twelve
     lay.build_abstract()
-    head = 256                                   # arrival counters stay zero, the partials behind them do not matter
+    head = L.leoam_fused_control_bytes(lay.shape)        # control words stay zero, the partials behind them do not matter
     lay.workspace[head:].fill_(0x7f)
     lay.step(c.q)
     torch.cuda.synchronize()

@@ -7,7 +7,9 @@ exchange has no release / acquire fence (on this multi-XCD part a fence is an L2
 it rests on the hardware's ordering of acknowledged write-through stores, not on the HIP memory model.  A stale
 partial would be a silently wrong output, so every configuration is launched many times with the partial area
 re-poisoned with a changing pattern before every launch, and every result is compared bit for bit with the
-first one (which is checked against the oracle).  The loop stops at the first mismatch."""
+first one (which is checked against the oracle).  The loop stops at the first mismatch.
+(Two splits per (sequence, kv head) at batch sizes that reserve exchange words are combined differently - one
+atomic exchange per output element carries the value itself - and are soaked the same way.)"""
 import numpy as np
 import pytest
 import torch
@@ -25,13 +27,9 @@ def L():
     return lib
 
 
-def counter_bytes(batch, hkv):
-    return (batch * hkv * 4 + 255) // 256 * 256
-
-
 def soak(L, lay, q, n_splits, launches, want_out):
     s = lay.shape
-    head = counter_bytes(s.batch, s.n_kv_heads)
+    head = L.leoam_fused_control_bytes(s)           # arrival counters (+ exchange words): zero between calls
     nbytes = head + n_splits * s.batch * s.n_q_heads * 130 * 4
     ws = torch.zeros((nbytes + 15) // 16 * 16, dtype=torch.uint8, device="cuda")
 
@@ -51,7 +49,7 @@ def soak(L, lay, q, n_splits, launches, want_out):
         launch()
         ok = torch.equal(lay.out, first_out) and torch.equal(lay.lse, first_lse)     # (synchronises)
         assert ok, f"launch {i} with {n_splits} splits differs from the first launch"
-        assert not ws[:head].any(), f"launch {i}: arrival counters not back at zero"
+        assert not ws[:head].any(), f"launch {i}: control words not back at zero"
 
 
 def dense_layer(L, oracle, hq, hkv, dtype_cfg="c2"):
@@ -92,3 +90,19 @@ def test_one_launch_kernel_compressed_store(L, oracle, n_splits):
     want, _ = oracle.sparse_attention_q(c.q.cpu(), qc.kblob.cpu(), qc.vblob.cpu(), qc.qmeta.cpu(), c.chunk_off.cpu(),
                                         lay.sel_idx.cpu().numpy(), lay.sel_count.cpu().numpy())
     soak(L, lay, c.q, n_splits, LAUNCHES, want)
+
+
+def test_two_splits_combined_through_exchange_words(L, oracle):
+    """Batch sizes between half a workgroup and one workgroup per compute unit (here 16 sequences x 8 kv heads)
+    give two splits per (sequence, kv head), which are combined by one atomic exchange per output element
+    instead of the ticket: the same soak (the partial area behind the control words is unused, and poisoned)."""
+    case = gen.make_case("c3", layer=13, batch=16, n_ctx=4096 + 37, hq=32, hkv=8, token_budget=1024, device="cuda")
+    lay = L.DecodeLayer(case.K, case.V, case.chunk_off, case.n_chunks, case.hq, case.k_max, case.max_chunks,
+                        case.token_budget)
+    lay.build_abstract()
+    lay.step(case.q)
+    torch.cuda.synchronize()
+    assert L.leoam_fused_control_bytes(lay.shape) > 16 * 8 * 4 + 256, "this shape was meant to have exchange words"
+    sel, cnt = lay.sel_idx.cpu().numpy(), lay.sel_count.cpu().numpy()
+    want, _ = oracle.sparse_attention(case.q.cpu(), case.K.cpu(), case.V.cpu(), case.chunk_off.cpu(), sel, cnt)
+    soak(L, lay, case.q, 2, LAUNCHES, want)
