@@ -28,31 +28,41 @@
 
 namespace leoam {
 
-template <typename T, int G, bool kLower, bool kSingle>
+template <typename T, int G, bool kLower, bool kSingle, int kUnit = 1>
 __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
     const char* __restrict__ q, const char* __restrict__ abstract, const int32_t* __restrict__ n_chunks,
     float* __restrict__ score_ub, float* __restrict__ score_lb, int c_max, int n_kv_heads) {
     __shared__ ScoreLds<T, G, kLower> lds;
-    score_unit<T, G, kLower, kSingle>(lds, q, abstract, n_chunks, score_ub, score_lb, c_max, n_kv_heads, blockIdx.z,
+    score_unit<T, G, kLower, kSingle, false, kUnit>(lds, q, abstract, n_chunks, score_ub, score_lb, c_max, n_kv_heads, blockIdx.z,
                                       blockIdx.y, blockIdx.x, gridDim.x);
 }
 
 template <typename T, int G>
 static hipError_t launch_score(const leoam_shape* s, const void* q, const void* abstract, const int32_t* n_chunks,
                                float* ub, float* lb, hipStream_t stream) {
-    const ScoreGeometry geo = score_geometry(s);
+    // Pairs of row sets, all fetched up front, streamed 1-6 % faster than pipelined groups of four on
+    // MI355X when a set is cheap to contract (upper bound only, one pass of up to four heads); with the
+    // lower bound or eight heads per group the contraction is twice as long and the pipelined groups,
+    // which hide it behind the next fetch, were 8-14 % faster; with one head per group, 2 % faster.
+    const bool with_pairs = lb == nullptr && G > 1 && G <= 4;
+    const ScoreGeometry geo = score_geometry(s, with_pairs);
     const int gx = geo.gx;
     const bool single = geo.single;
     dim3 grid(gx, s->n_kv_heads, s->batch), block(kScoreWaves * LEOAM_WAVE);
-    // Large launches ask for unused dynamic LDS up to 40 KiB per workgroup, which holds a compute
-    // unit to four workgroups: with the seven that registers allow, the requests of more waves
-    // interleave in the memory system and the kernel measured 4 % slower on MI355X (three: 15 % slower).
+    // Large launches ask for unused dynamic LDS, which caps the workgroups of a compute unit below the
+    // seven that registers allow: with more, the requests of more waves interleave in the memory system.
+    // Groups of four: 40 KiB per workgroup (four per unit; seven measured 4 % slower on MI355X, three 15 %);
+    // pairs: 24 KiB (six per unit; seven measured 3 % slower, five 9 %).
     const size_t a_bytes = (size_t)((G + 3) / 4) * 32 * LEOAM_WAVE * sizeof(double) * (lb ? 2 : 1);
     const size_t lds_pad = (!single && a_bytes < kScoreLdsPerWg) ? kScoreLdsPerWg - a_bytes : 0;
 #define LEOAM_SCORE(LOWER, SINGLE)                                                                              \
     hipLaunchKernelGGL((chunk_score_kernel<T, G, LOWER, SINGLE>), grid, block, lds_pad, stream, (const char*)q,  \
                        (const char*)abstract, n_chunks, ub, lb, s->c_max, s->n_kv_heads)
-    if (lb) {
+    if (geo.unit == 2) {
+        const size_t pad = a_bytes < kScorePairLdsPerWg ? kScorePairLdsPerWg - a_bytes : 0;
+        hipLaunchKernelGGL((chunk_score_kernel<T, G, false, true, 2>), grid, block, pad, stream, (const char*)q,
+                           (const char*)abstract, n_chunks, ub, lb, s->c_max, s->n_kv_heads);
+    } else if (lb) {
         if (single) LEOAM_SCORE(true, true); else LEOAM_SCORE(true, false);
     } else {
         if (single) LEOAM_SCORE(false, true); else LEOAM_SCORE(false, false);

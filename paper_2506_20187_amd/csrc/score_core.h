@@ -9,7 +9,8 @@ namespace leoam {
 constexpr int kScoreWaves = 4;
 constexpr int kRowsPerSet = 16;    // abstract rows per MFMA = 8 chunks
 constexpr int kChunksPerSet = 8;
-constexpr size_t kScoreLdsPerWg = 40 * 1024;    // static + dynamic LDS of a workgroup in large launches
+constexpr size_t kScoreLdsPerWg = 40 * 1024;    // static + dynamic LDS of a workgroup that takes groups of four sets
+constexpr size_t kScorePairLdsPerWg = 24 * 1024;    // ... of one that takes pairs of sets (six workgroups per compute unit)
 
 __device__ __forceinline__ double dpp_ror8_d(double v) {
     // value of the lane 8 places away inside the 16-lane row (rotation by 8 is its own inverse)
@@ -39,7 +40,11 @@ template <typename T, int G, bool kLower> struct ScoreLds {
 // kHeadSets = ceil(G / 4); heads beyond G contribute nothing.
 // kSingle: a wave takes single row sets instead of groups of four (launches too small to
 // fill the chip: what is waited for then is a wave's own chain of round trips).
-template <typename T, int G, bool kLower, bool kSingle, bool kCoherent = false>
+// kUnit (with kSingle): row sets a wave takes at a time, all fetched before anything else is done.
+// Two at a time is the shape of large launches: a wave then has 8 KiB (16-bit rows) in flight from
+// its first instruction on and a workgroup reads 32 KiB; on MI355X this streamed 6-7 % faster than
+// groups of four sets fetched two at a time.
+template <typename T, int G, bool kLower, bool kSingle, bool kCoherent = false, int kUnit = 1>
 __device__ __forceinline__ void score_unit(ScoreLds<T, G, kLower>& lds, const char* __restrict__ q,
                                            const char* __restrict__ abstract, const int32_t* __restrict__ n_chunks,
                                            float* __restrict__ score_ub, float* __restrict__ score_lb, int c_max,
@@ -73,7 +78,7 @@ __device__ __forceinline__ void score_unit(ScoreLds<T, G, kLower>& lds, const ch
     // different offsets inside 16 KiB, and groups cut from each one's start measured 18-30 % slower
     // on MI355X than mutually aligned ones.
     constexpr uintptr_t kSetBytes = (uintptr_t)kRowsPerSet * ROWB;
-    const int lead = kSingle ? 0 : (int)(((uintptr_t)Abh / kSetBytes) & 3);
+    const int lead = kSingle ? (kUnit == 2 ? (int)(((uintptr_t)Abh / kSetBytes) & 1) : 0) : (int)(((uintptr_t)Abh / kSetBytes) & 3);
 
     // Loads are unconditional (a guarded load would make the compiler wait for
     // every outstanding load and defeat the prefetch): a row past the end of the
@@ -91,7 +96,9 @@ __device__ __forceinline__ void score_unit(ScoreLds<T, G, kLower>& lds, const ch
     const int g0 = bx * kScoreWaves + wave;      // this wave's first group of four sets (or first set)
     // A workgroup past the end of a sequence with fewer chunks than the capacity has nothing to
     // contract: it writes its share of the row's tail and leaves before the queries are staged.
-    const int units_here = kSingle ? n_sets : (n_sets + lead + 3) >> 2;
+    static_assert(kUnit == 1 || kUnit == 2, "one or two row sets at a time");
+    const int n_units = (n_sets + lead + kUnit - 1) / kUnit;
+    const int units_here = kSingle ? n_units : (n_sets + lead + 3) >> 2;
     if (bx * kScoreWaves >= units_here) {
         for (int c = C + bx * kThreads + (int)threadIdx.x; c < c_max; c += gx * kThreads) {
             store_score<kCoherent>(&score_ub[bh * c_max + c], -INFINITY);
@@ -99,7 +106,8 @@ __device__ __forceinline__ void score_unit(ScoreLds<T, G, kLower>& lds, const ch
         }
         return;
     }
-    fetch(kSingle ? g0 : 4 * g0 - lead, cur);
+    fetch(kSingle ? kUnit * g0 - lead : 4 * g0 - lead, cur);
+    if constexpr (kSingle && kUnit == 2) fetch(2 * g0 + 1 - lead, nxt);
 
     // A operands: clamped query values for every step, in double.  They are the same
     // for the four waves and would take 64 registers per lane, so they live in LDS
@@ -171,7 +179,7 @@ __device__ __forceinline__ void score_unit(ScoreLds<T, G, kLower>& lds, const ch
         // every lane holds the score of chunk (lane & 7) of this set
         if constexpr (kSingle) {
             const int c = set * kChunksPerSet + lane;
-            if (lane < kChunksPerSet && c < C) {
+            if (lane < kChunksPerSet && c >= 0 && c < C) {
                 store_score<kCoherent>(&score_ub[bh * c_max + c], (float)ub + 0.0f);
                 if (kLower) store_score<kCoherent>(&score_lb[bh * c_max + c], (float)lb + 0.0f);
             }
@@ -195,9 +203,13 @@ __device__ __forceinline__ void score_unit(ScoreLds<T, G, kLower>& lds, const ch
     // waves of the (b,h).  No loads under a condition inside the loop; sets past
     // the end are computed from clamped rows and store nothing.
     if constexpr (kSingle) {
-        for (int set = g0; set < n_sets; set += stride) {
-            if (set != g0) fetch(set, cur);          // wave-uniform; normally a wave has one set
-            consume(0, set, cur);
+        for (int u = g0; u < n_units; u += stride) {
+            if (u != g0) {          // wave-uniform; normally a wave has one unit
+                fetch(kUnit * u - lead, cur);
+                if constexpr (kUnit == 2) fetch(2 * u + 1 - lead, nxt);
+            }
+            consume(0, kUnit * u - lead, cur);
+            if constexpr (kUnit == 2) consume(0, 2 * u + 1 - lead, nxt);
         }
     }
     const int n_groups = kSingle ? 0 : (n_sets + lead + 3) >> 2;
@@ -232,8 +244,10 @@ __device__ __forceinline__ void score_unit(ScoreLds<T, G, kLower>& lds, const ch
 struct ScoreGeometry {
     int gx;
     bool single;
+    int unit;      // row sets per wave at a time (single only)
 };
-inline ScoreGeometry score_geometry(const leoam_shape* s) {
+// `with_pairs`: large launches may take pairs of row sets (see launch_score for when that pays).
+inline ScoreGeometry score_geometry(const leoam_shape* s, bool with_pairs) {
     // Enough workgroups that every wave takes a single group of row sets (a wave that walks on to
     // a second group, a whole grid further, measured 3-10 % slower).  The count per (b,h) is kept
     // odd: with 8, 16 or 32 workgroups per (b,h) the kernel measured 13 % slower on MI355X (the
@@ -247,7 +261,12 @@ inline ScoreGeometry score_geometry(const leoam_shape* s) {
     int gx = single ? (4480 + units - 1) / units : gx_max;      // (small launches: about eighteen workgroups per CU)
     if (gx > gx_max) gx = gx_max;
     gx |= 1;
-    return {gx, single};
+    if (!single && with_pairs) {
+        // large launches: a wave takes one pair of row sets (up to one lead set)
+        const int pairs = (sets + 1 + 1) / 2;
+        return {((pairs + kScoreWaves - 1) / kScoreWaves) | 1, true, 2};
+    }
+    return {gx, single, 1};
 }
 
 

@@ -161,9 +161,11 @@ def test_score_exact(L, oracle, dtype, G):
 
 @pytest.mark.parametrize("dtype,G,c_max", [("bf16", 4, 301), ("f16", 2, 264), ("bf16", 1, 333), ("f32", 4, 300)])
 def test_score_exact_many_heads_odd_capacity(L, oracle, dtype, G, c_max):
-    """Enough (sequence, kv head) pairs for the launch that streams 16 KiB groups of abstract rows, with
-    capacities that let the abstracts of different pairs start at every offset inside 16 KiB (the groups
-    are cut at 16 KiB addresses, so the first one of a pair is partly skipped), and ragged chunk counts."""
+    """Enough (sequence, kv head) pairs for the large-launch shapes (pairs of row sets when only the upper
+    bound of two to four heads is asked for, else pipelined groups of four sets), with capacities that let
+    the abstracts of different pairs start at every offset inside 16 KiB (pairs and groups are cut at
+    multiples of their size, so the first one of a (sequence, kv head) is partly skipped), and ragged
+    chunk counts."""
     rng = np.random.default_rng(c_max)
     B, Hkv, D = 64, 8, 128
     counts = rng.integers(c_max // 2, c_max + 1, size=B).astype(np.int32)
