@@ -2,6 +2,8 @@
 // each chunk from its abstract), shared by the chunk_score kernel and the one-launch decode step.
 // See chunk_score.hip for the arithmetic and the matrix-core layout.
 #pragma once
+#include <type_traits>
+
 #include "leoam_dev.h"
 
 namespace leoam {
@@ -92,7 +94,9 @@ __device__ __forceinline__ void score_unit(ScoreLds<T, G, kLower>& lds, const ch
 
     // software pipeline: the next row set is in flight while this one is contracted;
     // the first fetch goes out before the queries are converted
-    uint4 cur[NLOAD], nxt[NLOAD];
+    uint4 buf[2 * NLOAD];
+    uint4* const cur = buf;
+    uint4* const nxt = buf + NLOAD;
     const int g0 = bx * kScoreWaves + wave;      // this wave's first group of four sets (or first set)
     // A workgroup past the end of a sequence with fewer chunks than the capacity has nothing to
     // contract: it writes its share of the row's tail and leaves before the queries are staged.
@@ -136,30 +140,8 @@ __device__ __forceinline__ void score_unit(ScoreLds<T, G, kLower>& lds, const ch
     // per lane and written as a single 128-byte line: a store after every set would
     // sit in the same in-order memory counter as the prefetched loads.
     float pend_ub = 0.f, pend_lb = 0.f;
-    auto consume = [&](int it, int set, const uint4* v) {
-        asm volatile("" : "+v"(q_lane));      // keeps the LDS reads of the A operands inside this call
-        // two interleaved accumulator chains per head pass (even / odd steps)
-        double ua[HS][2], la[kLower ? HS : 1][2];
-#pragma unroll
-        for (int s = 0; s < HS; ++s) {
-            ua[s][0] = ua[s][1] = 0.0;
-            if (kLower) la[s][0] = la[s][1] = 0.0;
-        }
-#pragma unroll
-        for (int i = 0; i < NLOAD; ++i) {
-            float x[EPL];
-            unpack<T>(v[i], x);
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-                const double xd = (double)x[e];
-#pragma unroll
-                for (int s = 0; s < HS; ++s) {
-                    ua[s][e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(qa_lds[s][i * EPL + e][q_lane], xd, ua[s][e & 1], 0, 0, 0);
-                    if (kLower)
-                        la[s][e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(qb_lds[s][i * EPL + e][q_lane], xd, la[s][e & 1], 0, 0, 0);
-                }
-            }
-        }
+    // the sums of one row set -> its chunks' scores, stored or collected
+    auto finish = [&](int it, int set, const double (*ua)[2], const double (*la)[2]) {
         // result lane = 16*head + row; rows r and r+8 are the kmax and kmin halves of chunk r&7
         double ub = -INFINITY, lb = INFINITY;
 #pragma unroll
@@ -198,6 +180,47 @@ __device__ __forceinline__ void score_unit(ScoreLds<T, G, kLower>& lds, const ch
             }
         }
     };
+    // kSets row sets (v[0..NLOAD) the first, v[NLOAD..) the second) are contracted together: an A
+    // operand read from LDS serves all of them, and their accumulator chains interleave.  Every
+    // set's sums are formed in the same order whatever kSets is.
+    auto consume = [&](int it, int set, const uint4* v, auto n_sets_tag) {
+        constexpr int kSets = decltype(n_sets_tag)::value;
+        asm volatile("" : "+v"(q_lane));      // keeps the LDS reads of the A operands inside this call
+        // two interleaved accumulator chains per set and head pass (even / odd steps)
+        double ua[kSets][HS][2], la[kSets][kLower ? HS : 1][2];
+#pragma unroll
+        for (int k = 0; k < kSets; ++k)
+#pragma unroll
+            for (int s = 0; s < HS; ++s) {
+                ua[k][s][0] = ua[k][s][1] = 0.0;
+                if (kLower) la[k][s][0] = la[k][s][1] = 0.0;
+            }
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) {
+            float x[kSets][EPL];
+#pragma unroll
+            for (int k = 0; k < kSets; ++k) unpack<T>(v[k * NLOAD + i], x[k]);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+#pragma unroll
+                for (int s = 0; s < HS; ++s) {
+                    const double qa = qa_lds[s][i * EPL + e][q_lane];
+                    double qb = 0.0;
+                    if (kLower) qb = qb_lds[s][i * EPL + e][q_lane];
+#pragma unroll
+                    for (int k = 0; k < kSets; ++k) {
+                        const double xd = (double)x[k][e];
+                        ua[k][s][e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(qa, xd, ua[k][s][e & 1], 0, 0, 0);
+                        if (kLower) la[k][s][e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(qb, xd, la[k][s][e & 1], 0, 0, 0);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < kSets; ++k) finish(it + k, set + k, ua[k], la[k]);
+    };
+    constexpr std::integral_constant<int, 1> kOneSet{};
+    constexpr std::integral_constant<int, kUnit> kUnitSets{};
 
     // A wave takes groups of four consecutive sets, groups round-robin over the
     // waves of the (b,h).  No loads under a condition inside the loop; sets past
@@ -208,8 +231,7 @@ __device__ __forceinline__ void score_unit(ScoreLds<T, G, kLower>& lds, const ch
                 fetch(kUnit * u - lead, cur);
                 if constexpr (kUnit == 2) fetch(2 * u + 1 - lead, nxt);
             }
-            consume(0, kUnit * u - lead, cur);
-            if constexpr (kUnit == 2) consume(0, 2 * u + 1 - lead, nxt);
+            consume(0, kUnit * u - lead, buf, kUnitSets);
         }
     }
     const int n_groups = kSingle ? 0 : (n_sets + lead + 3) >> 2;
@@ -222,16 +244,16 @@ __device__ __forceinline__ void score_unit(ScoreLds<T, G, kLower>& lds, const ch
     for (; it + 2 < n_it; it += 2) {
         fetch(set_of(it + 1), nxt);
         __builtin_amdgcn_sched_barrier(0);       // keep the loads ahead of the contraction
-        consume(it, set_of(it), cur);
+        consume(it, set_of(it), cur, kOneSet);
         fetch(set_of(it + 2), cur);
         __builtin_amdgcn_sched_barrier(0);
-        consume(it + 1, set_of(it + 1), nxt);
+        consume(it + 1, set_of(it + 1), nxt, kOneSet);
     }
     if (n_it > 0) {
         fetch(set_of(it + 1), nxt);
         __builtin_amdgcn_sched_barrier(0);
-        consume(it, set_of(it), cur);
-        consume(it + 1, set_of(it + 1), nxt);
+        consume(it, set_of(it), cur, kOneSet);
+        consume(it + 1, set_of(it + 1), nxt, kOneSet);
     }
     // tail of the row: chunks that do not exist
     for (int c = C + bx * kThreads + (int)threadIdx.x; c < c_max; c += gx * kThreads) {
