@@ -39,6 +39,10 @@
  *       score      [batch, n_kv_heads, c_max] float
  *       sel_idx    [batch, n_kv_heads, k_max] int32
  *       out        [batch, n_q_heads, head_dim] float
+ *     K, V, q, abstract (and the blobs and chunk records of the compressed
+ *     store) are read with 16-byte loads: their addresses must be multiples of
+ *     16 (LEOAM_E_INVALID_ARG otherwise).  The other arrays need the natural
+ *     alignment of their element type.
  *     Chunk boundaries belong to a (sequence, layer) and are shared by its
  *     heads; abstracts, scores and selections are per (sequence, kv head).
  *     Query head j belongs to kv head j / (n_q_heads / n_kv_heads).
@@ -56,7 +60,7 @@ extern "C" {
 
 typedef enum {
     LEOAM_OK = 0,
-    LEOAM_E_INVALID_ARG = -1,    /* null pointer, non-positive size, Hq % Hkv != 0 */
+    LEOAM_E_INVALID_ARG = -1,    /* null pointer, misaligned pointer, non-positive size, Hq % Hkv != 0 */
     LEOAM_E_BAD_BOUNDARIES = -2, /* only from leoam_validate_boundaries */
     LEOAM_E_UNSUPPORTED = -3,    /* head_dim != 128, group size not in {1,2,4,8}, dtype combination, c_max > 16384 */
     LEOAM_E_WORKSPACE = -4,      /* workspace missing or too small */

@@ -103,6 +103,9 @@ static int check_shape(const leoam_shape* s) {
 
 static inline int from_hip(hipError_t e) { return e == hipSuccess ? LEOAM_OK : LEOAM_E_HIP; }
 
+// K, V, q, the abstract and the blobs are read with 16-byte loads
+template <typename... P> static inline bool misaligned16(P... p) { return ((... | (uintptr_t)p) & 15u) != 0; }
+
 // ---- workspace of chunk_select_attention_decode_static ------------------------------------------
 // Device memory that belongs to the library image: every GPU the library runs on holds its own copy
 // until the process ends.  `static_scratch` names the array in DEVICE code only; on the host the
@@ -136,6 +139,7 @@ int kv_chunk_abstract_build(const leoam_shape* shape, const void* K, const void*
     int rc = check_shape(shape);
     if (rc) return rc;
     if (!K || !chunk_off || !n_chunks || !abstract) return LEOAM_E_INVALID_ARG;
+    if (misaligned16(K, abstract, qmeta)) return LEOAM_E_INVALID_ARG;
     if (shape->kv_dtype == LEOAM_Q8Q4) {
         if (!qmeta) return LEOAM_E_INVALID_ARG;
         return from_hip(abstract_build_q_dispatch(shape, K, qmeta, chunk_off, n_chunks, abstract, (hipStream_t)stream));
@@ -148,6 +152,7 @@ int kv_chunk_abstract_append(const leoam_shape* shape, const void* K, int32_t* c
     int rc = check_shape(shape);
     if (rc) return rc;
     if (!K || !chunk_off || !n_chunks || !abstract || chunk_size < 1) return LEOAM_E_INVALID_ARG;
+    if (misaligned16(K, abstract)) return LEOAM_E_INVALID_ARG;
     if (shape->kv_dtype == LEOAM_Q8Q4) return LEOAM_E_UNSUPPORTED;
     return from_hip(abstract_append_dispatch(shape, K, chunk_off, n_chunks, chunk_size, abstract, status,
                                              (hipStream_t)stream));
@@ -178,6 +183,7 @@ int chunk_tree_refine(const leoam_shape* shape, const void* q, const void* K, co
     if (rc) return rc;
     if (!q || !K || !abstract || !ref_off || !ref_score || !ref_count || !ref_evals || !ref_status)
         return LEOAM_E_INVALID_ARG;
+    if (misaligned16(q, K, abstract)) return LEOAM_E_INVALID_ARG;
     if (!workspace || workspace_bytes < tree_workspace_bytes(shape, node_cap) || ((uintptr_t)workspace & 15u))
         return LEOAM_E_WORKSPACE;
     return from_hip(tree_refine_dispatch(shape, q, K, abstract, chunk_size, k_tokens, max_rounds, node_cap, ref_off,
@@ -203,6 +209,7 @@ int chunk_score(const leoam_shape* shape, const void* q, const void* abstract, c
     int rc = check_shape(shape);
     if (rc) return rc;
     if (!q || !abstract || !n_chunks || !score_ub) return LEOAM_E_INVALID_ARG;
+    if (misaligned16(q, abstract)) return LEOAM_E_INVALID_ARG;
     return from_hip(chunk_score_dispatch(shape, q, abstract, n_chunks, score_ub, score_lb, (hipStream_t)stream));
 }
 
@@ -237,6 +244,7 @@ int sparse_chunk_attention_decode(const leoam_shape* shape, const void* q, const
     int rc = check_shape(shape);
     if (rc) return rc;
     if (!q || !K || !V || !chunk_off || !n_chunks || !sel_idx || !sel_count || !out) return LEOAM_E_INVALID_ARG;
+    if (misaligned16(q, K, V, qmeta)) return LEOAM_E_INVALID_ARG;
     if (shape->k_max > attention_max_sel()) return LEOAM_E_UNSUPPORTED;
     if (shape->kv_dtype == LEOAM_Q8Q4) {
         if (!qmeta) return LEOAM_E_INVALID_ARG;
@@ -257,6 +265,7 @@ int chunk_select_attention_decode(const leoam_shape* shape, const float* score_u
     if (rc) return rc;
     // (score_ub == NULL: the kept lists are inputs and the call only attends)
     if (!q || !K || !V || !chunk_off || !n_chunks || !sel_idx || !sel_count || !out) return LEOAM_E_INVALID_ARG;
+    if (misaligned16(q, K, V, qmeta)) return LEOAM_E_INVALID_ARG;
     if (shape->k_max > attention_max_sel()) return LEOAM_E_UNSUPPORTED;
     if (shape->kv_dtype == LEOAM_Q8Q4) {
         if (!qmeta) return LEOAM_E_INVALID_ARG;
@@ -278,6 +287,7 @@ int chunk_select_attention_decode_static(const leoam_shape* shape, const float* 
     if (rc) return rc;
     // (score_ub == NULL: the kept lists are inputs and the call only attends)
     if (!q || !K || !V || !chunk_off || !n_chunks || !sel_idx || !sel_count || !out) return LEOAM_E_INVALID_ARG;
+    if (misaligned16(q, K, V, qmeta)) return LEOAM_E_INVALID_ARG;
     if (shape->k_max > attention_max_sel()) return LEOAM_E_UNSUPPORTED;
     if (shape->kv_dtype == LEOAM_Q8Q4) {
         if (!qmeta) return LEOAM_E_INVALID_ARG;
@@ -355,7 +365,7 @@ int kv_chunk_compress(const leoam_shape* shape, const void* K, const void* V, co
     if (rc) return rc;
     if (!K || !V || !chunk_off || !n_chunks || !four_bit || !kblob || !vblob || !qmeta) return LEOAM_E_INVALID_ARG;
     if (shape->kv_dtype != LEOAM_F16 && shape->kv_dtype != LEOAM_BF16) return LEOAM_E_UNSUPPORTED;
-    if (((uintptr_t)kblob & 15u) || ((uintptr_t)vblob & 15u) || ((uintptr_t)qmeta & 15u)) return LEOAM_E_INVALID_ARG;
+    if (misaligned16(K, V, kblob, vblob, qmeta)) return LEOAM_E_INVALID_ARG;
     if (blob_bytes < compressed_bytes_bound(shape)) return LEOAM_E_WORKSPACE;
     return from_hip(compress_dispatch(shape, K, V, chunk_off, n_chunks, four_bit, kblob, vblob, qmeta, blob_bytes,
                                       (long long*)total_bytes, (hipStream_t)stream));
@@ -370,8 +380,7 @@ int kv_chunk_recompress(const leoam_shape* shape, const void* K, const void* V, 
         !used_bytes || !info)
         return LEOAM_E_INVALID_ARG;
     if (shape->kv_dtype != LEOAM_F16 && shape->kv_dtype != LEOAM_BF16) return LEOAM_E_UNSUPPORTED;
-    if (((uintptr_t)kblob & 15u) || ((uintptr_t)vblob & 15u) || ((uintptr_t)qmeta & 15u) || ((uintptr_t)used_bytes & 7u) ||
-        ((uintptr_t)info & 7u))
+    if (misaligned16(K, V, kblob, vblob, qmeta) || ((uintptr_t)used_bytes & 7u) || ((uintptr_t)info & 7u))
         return LEOAM_E_INVALID_ARG;
     return from_hip(recompress_dispatch(shape, K, V, chunk_off, n_chunks, four_bit_old, four_bit_new, kblob, vblob, qmeta,
                                         blob_bytes, (long long*)used_bytes, (long long*)info, (hipStream_t)stream));

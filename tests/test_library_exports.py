@@ -43,6 +43,13 @@ def test_host_side_argument_checks_without_gpu():
     assert lib.chunk_score(ctypes.byref(s), None, None, None, None, None, None) == -1
     bad = L.make_shape(1, 32, 8, 128, 131072, 8192, 9000, 2)
     assert lib.chunk_score(ctypes.byref(bad), None, None, None, None, None, None) == -1
+    # q, K, V and the abstract are read with 16-byte loads: a misaligned address is refused
+    ok, odd = ctypes.c_void_p(4096), ctypes.c_void_p(4096 + 8)
+    assert lib.chunk_score(ctypes.byref(s), odd, ok, ok, ok, None, None) == -1
+    assert lib.chunk_score(ctypes.byref(s), ok, odd, ok, ok, None, None) == -1
+    assert lib.kv_chunk_abstract_build(ctypes.byref(s), odd, None, ok, ok, ok, None) == -1
+    assert lib.sparse_chunk_attention_decode(ctypes.byref(s), ok, ok, odd, None, ok, ok, ok, ok, ctypes.c_float(1.0), ok, None,
+                                             ok, 1 << 30, None) == -1
 
 
 def test_host_side_checks_of_the_later_entry_points():
