@@ -192,6 +192,32 @@ def test_score_exact_many_heads_odd_capacity(L, oracle, dtype, G, c_max):
     assert np.array_equal(s_only.cpu().numpy(), ub)
 
 
+@pytest.mark.parametrize("dtype,G,c_max", [("bf16", 4, 5), ("f16", 2, 17), ("bf16", 1, 9)])
+def test_score_exact_tiny_capacity_many_sequences(L, oracle, dtype, G, c_max):
+    """A large launch (thousands of (sequence, kv head) pairs) whose rows hold only one to three row sets:
+    most waves of a workgroup then have nothing of their own to contract, and the abstracts of different
+    pairs start at every 512-byte offset."""
+    rng = np.random.default_rng(100 + c_max)
+    B, Hkv, D = 640, 8, 128
+    counts = rng.integers(0, c_max + 1, size=B).astype(np.int32)
+    counts[:2] = (c_max, 0)
+    a = rng.standard_normal((B, Hkv, c_max, D)).astype(np.float32)
+    b = rng.standard_normal((B, Hkv, c_max, D)).astype(np.float32)
+    ab = torch.from_numpy(np.stack([np.maximum(a, b), np.minimum(a, b)], axis=3)).to(TDT[dtype])
+    q = torch.from_numpy(rng.standard_normal((B, Hkv * G, D)).astype(np.float32)).to(TDT[dtype])
+    ub, lb = oracle.chunk_score(q, ab.to(torch.float64).numpy(), counts, want_lower=True)
+    shape = L.make_shape(B, Hkv * G, Hkv, D, 4096, c_max, 1, TDT[dtype])
+    s_ub = torch.empty(B, Hkv, c_max, dtype=torch.float32, device="cuda")
+    s_lb = torch.empty_like(s_ub)
+    L.chunk_score(shape, dev(q), dev(ab), dev(counts), s_ub, s_lb)
+    s_only = torch.empty_like(s_ub)
+    L.chunk_score(shape, dev(q), dev(ab), dev(counts), s_only, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(s_ub.cpu().numpy(), ub)
+    assert np.array_equal(s_lb.cpu().numpy(), lb)
+    assert np.array_equal(s_only.cpu().numpy(), ub)
+
+
 # ---------------------------------------------------------------------------
 # a3 select
 # ---------------------------------------------------------------------------
