@@ -61,6 +61,7 @@ __device__ __forceinline__ float tree_unkey(uint32_t k) {
 
 struct TreeLds {
     alignas(16) double qpos[kTreeMaxG][LEOAM_D], qneg[kTreeMaxG][LEOAM_D];      // max(q, 0), min(q, 0); order: q_slot()
+    alignas(16) double qall[kTreeMaxG][LEOAM_D];                                 // q itself (single-token nodes)
     uint32_t hist[256];
     uint32_t wave_tot[kTreeWaves];
     uint32_t key_lo, key_hi, digit, rank;
@@ -122,7 +123,8 @@ template <typename T> __device__ __forceinline__ int q_slot(int lane_in_row, int
 // in double, rounded once to float.  A wave evaluates 4 (2) nodes at a time.
 template <typename T>
 __device__ __forceinline__ void tree_eval(const char* rows, int n_rows, const double (*qpos)[LEOAM_D],
-                                          const double (*qneg)[LEOAM_D], int G, float* U, float* L) {
+                                          const double (*qneg)[LEOAM_D], const double (*qall)[LEOAM_D], int G, float* U,
+                                          float* L) {
     constexpr int LPR = Row<T>::kLanesPerRow;
     constexpr int EPL = T::kEpl;
     constexpr int ROWB = Row<T>::kRowBytes;
@@ -157,6 +159,48 @@ __device__ __forceinline__ void tree_eval(const char* rows, int n_rows, const do
     int w_rows = n_rows;
 #pragma unroll
     for (int g = 0; g < LEOAM_WAVE; g += LPR) w_rows = max(w_rows, __builtin_amdgcn_readlane(n_rows, g));
+    if (w_rows == 1) {
+        // Single tokens only: kmax = kmin = the key row, so U = L = max_j q_j.k.  The sums below are the
+        // values the general path gives (there one of max(q,0), min(q,0) is zero in every product and
+        // adds nothing), at a quarter of the multiply-adds and half of the cross-lane reduction.
+        rows_from(0, std::integral_constant<int, 1>{});
+        auto head_dot = [&](int j) {
+            double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+            for (int e = 0; e < EPL; e += 2) {
+                const double2 qq = *reinterpret_cast<const double2*>(&qall[j][q_slot<T>(lane_in_row, e)]);
+                s0 = fma(qq.x, (double)mx[e], s0);
+                s1 = fma(qq.y, (double)mx[e + 1], s1);
+            }
+            return s0 + s1;
+        };
+        float ub = -INFINITY;
+        if (G == 4) {
+            double x[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) x[j] = head_dot(j);
+            const bool b0 = lane_in_row & 1, b1 = lane_in_row & 2;
+            double y[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const double keep = b0 ? x[2 + i] : x[i], send = b0 ? x[i] : x[2 + i];
+                y[i] = keep + dpp_d<kDppXor1>(send);
+            }
+            double z = (b1 ? y[1] : y[0]) + dpp_d<kDppXor2>(b1 ? y[0] : y[1]);
+            z += dpp_d<kDppRor4>(z);
+            z += dpp_d<kDppRor8>(z);
+            if (LPR == 32) z += shfl_xor_d(z, 16);
+            // this lane: head 2 * b0 + b1; the maximum over the quad is the maximum over the heads
+            ub = (float)z + 0.0f;
+            ub = fmaxf(ub, tree_dpp_f<kDppXor1>(ub));
+            ub = fmaxf(ub, tree_dpp_f<kDppXor2>(ub));
+        } else {
+            for (int j = 0; j < G; ++j) ub = fmaxf(ub, (float)group_sum_d<LPR>(head_dot(j)) + 0.0f);
+        }
+        *U = ub;
+        *L = ub;
+        return;
+    }
     if (w_rows <= 2) {          // also an initial chunk: its kmax row and its kmin row
         rows_from(0, std::integral_constant<int, 2>{});
     } else if (w_rows <= 4) {
@@ -271,6 +315,7 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
         for (int e = 0; e < EPL; ++e) {
             S.qpos[j][q_slot<T>(lr, e)] = (double)fmaxf(x[e], 0.f);
             S.qneg[j][q_slot<T>(lr, e)] = (double)fminf(x[e], 0.f);
+            S.qall[j][q_slot<T>(lr, e)] = (double)x[e];
         }
     }
     for (int i = tid; i < 256; i += kTreeThreads) S.hist[i] = 0;
@@ -280,7 +325,7 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
     for (int c0 = wave * (LEOAM_WAVE / LPR); c0 < m0; c0 += kGroups) {      // uniform over the wave
         const int c = min(c0 + gid % (LEOAM_WAVE / LPR), m0 - 1);
         float U, L;
-        tree_eval<T>(Abh + (size_t)c * 2 * ROWB, 2, S.qpos, S.qneg, G, &U, &L);
+        tree_eval<T>(Abh + (size_t)c * 2 * ROWB, 2, S.qpos, S.qneg, S.qall, G, &U, &L);
         if (g_lead) {        // (a clamped group repeats the last chunk's store)
             TreeNode nd;
             nd.start = c * chunk_size;
@@ -339,11 +384,23 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
         uint32_t prefix = (uint32_t)(((uint64_t)hi >> bits) << bits);
         while (bits > 0) {
             const int w = min(bits, 8), shift = bits - w;
+            // (neighbouring nodes often fall into one bin - a desert's chunks have nearly the same bound -
+            // and 64 lanes adding to one LDS word take 64 turns: a thread folds its consecutive nodes of
+            // one bin into a single add)
+            uint32_t run_bin = 0, run_weight = 0;
             for_nodes([&](int, const TreeNode& nd) {
                 const uint32_t k = key_of(nd);
-                if ((uint32_t)((uint64_t)(k ^ prefix) >> bits) == 0)
-                    atomicAdd(&S.hist[(k >> shift) & ((1u << w) - 1u)], (uint32_t)nd.size);
+                if ((uint32_t)((uint64_t)(k ^ prefix) >> bits) == 0) {
+                    const uint32_t bin = (k >> shift) & ((1u << w) - 1u);
+                    if (run_weight != 0 && bin != run_bin) {
+                        atomicAdd(&S.hist[run_bin], run_weight);
+                        run_weight = 0;
+                    }
+                    run_bin = bin;
+                    run_weight += (uint32_t)nd.size;
+                }
             });
+            if (run_weight != 0) atomicAdd(&S.hist[run_bin], run_weight);
             __syncthreads();
             if (wave == 0) {
                 // lane l owns bins 4l..4l+3 (and clears them); walk from the top bin down
@@ -490,7 +547,7 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
                 TreeNode c;
                 c.start = live ? (second ? tk.start + left : tk.start) : 0;
                 c.size = live ? (second ? tk.size - left : left) : 1;
-                tree_eval<T>(Kbh + (size_t)c.start * ROWB, c.size, S.qpos, S.qneg, G, &c.U, &c.L);
+                tree_eval<T>(Kbh + (size_t)c.start * ROWB, c.size, S.qpos, S.qneg, S.qall, G, &c.U, &c.L);
                 if (g_lead && live) nxt[tk.pos + second] = c;
                 tk = nx;
             }
@@ -512,41 +569,61 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
     __syncthreads();
     if (tid == 0) S.carry = 0;
     __syncthreads();
-    for (int base = 0; base < n; base += kTreeThreads) {
-        const int i = base + tid;
-        uint32_t head = 0;
-        TreeNode nd;
-        int kind = 0;
-        if (i < n) {
-            nd = cur[i];
-            kind = kind_of(nd);
-            head = 1;
-            if (i > 0 && kind != 0) {
-                const TreeNode pv = cur[i - 1];
-                if (kind_of(pv) == kind) head = 0;
-            }
+    // a thread takes kTreeCache consecutive nodes: one scan of the threads' head counts per tile
+    for (int base = 0; base < n; base += kTreeTile) {
+        const int i0 = base + tid * kTreeCache;
+        TreeNode nd[kTreeCache];
+#pragma unroll
+        for (int j = 0; j < kTreeCache; ++j) nd[j] = cur[min(i0 + j, n - 1)];
+        int kind_prev = (i0 > 0 && i0 < n) ? kind_of(cur[i0 - 1]) : 0;
+        uint32_t heads_upto[kTreeCache], width = 0;
+        bool head[kTreeCache];
+#pragma unroll
+        for (int j = 0; j < kTreeCache; ++j) {
+            const int i = i0 + j, kind = kind_of(nd[j]);
+            head[j] = i < n && !(i > 0 && kind != 0 && kind == kind_prev);
+            width += head[j] ? 1u : 0u;
+            heads_upto[j] = width;
+            kind_prev = kind;
         }
         uint32_t total;
-        const uint32_t before = tree_block_scan(head, S.wave_tot, &total);
-        const uint32_t carry = S.carry;
-        if (i < n) {
-            const int p = (int)(carry + before) - (head ? 0 : 1);       // the chunk this node belongs to
-            pos[i] = p;
-            if (head) {
-                off[p] = nd.start;
-                keys[p] = tree_key(kind == 1 ? FLT_MAX : nd.U);
+        const uint32_t before = S.carry + tree_block_scan(width, S.wave_tot, &total);
+#pragma unroll
+        for (int j = 0; j < kTreeCache; ++j) {
+            const int i = i0 + j;
+            if (i < n && head[j]) {
+                const int p = (int)(before + heads_upto[j]) - 1;       // the chunk this node opens
+                off[p] = nd[j].start;
+                keys[p] = tree_key(kind_of(nd[j]) == 1 ? FLT_MAX : nd[j].U);
             }
         }
-        __syncthreads();
-        if (tid == 0) S.carry = carry + total;
+        __syncthreads();      // the heads' keys are in place (a run may have begun in an earlier tile)
+        // an unimportant run carries the largest U of its nodes: a thread folds its consecutive nodes of
+        // one run first (most of a thread's nodes share a run: one atomic instead of eight on one address)
+        {
+            int run_p = -1;
+            uint32_t run_key = 0;
+#pragma unroll
+            for (int j = 0; j < kTreeCache; ++j) {
+                const int i = i0 + j;
+                if (i < n && !head[j] && kind_of(nd[j]) == 2) {
+                    const int p = (int)(before + heads_upto[j]) - 1;
+                    const uint32_t k = tree_key(nd[j].U);
+                    if (p != run_p) {
+                        if (run_p >= 0) atomicMax(&keys[run_p], run_key);
+                        run_p = p;
+                        run_key = k;
+                    } else {
+                        run_key = max(run_key, k);
+                    }
+                }
+            }
+            if (run_p >= 0) atomicMax(&keys[run_p], run_key);
+        }
+        if (tid == 0) S.carry += total;
         __syncthreads();
     }
     const int n_out = (int)S.carry;
-    // (a run may cross a tile boundary: the first node of the next tile then is no head and joins it)
-    for (int i = tid; i < n; i += kTreeThreads) {
-        const TreeNode nd = cur[i];
-        if (kind_of(nd) == 2) atomicMax(&keys[pos[i]], tree_key(nd.U));
-    }
     __syncthreads();
     for (int i = tid; i < n_out; i += kTreeThreads) ref_score[bh * (size_t)node_cap + i] = tree_unkey(keys[i]);
     if (tid == 0) {
