@@ -33,7 +33,7 @@ __global__ __launch_bounds__(kScoreWaves* LEOAM_WAVE) void chunk_score_kernel(
     const char* __restrict__ q, const char* __restrict__ abstract, const int32_t* __restrict__ n_chunks,
     float* __restrict__ score_ub, float* __restrict__ score_lb, int c_max, int n_kv_heads) {
     __shared__ ScoreLds<T, G, kLower> lds;
-    score_unit<T, G, kLower, kSingle, false, kUnit>(lds, q, abstract, n_chunks, score_ub, score_lb, c_max, n_kv_heads, blockIdx.z,
+    score_unit<T, G, kLower, kSingle, kUnit>(lds, q, abstract, n_chunks, score_ub, score_lb, c_max, n_kv_heads, blockIdx.z,
                                       blockIdx.y, blockIdx.x, gridDim.x);
 }
 

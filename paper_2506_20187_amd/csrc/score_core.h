@@ -22,13 +22,6 @@ __device__ __forceinline__ double dpp_ror8_d(double v) {
     return __builtin_bit_cast(double, ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
 }
 
-// A score as the kernel stores it.  kCoherent: the row is read later in the SAME launch by a
-// workgroup that may sit on another XCD, so it is written with an agent-scope (write-through) store.
-template <bool kCoherent> __device__ __forceinline__ void store_score(float* p, float v) {
-    if constexpr (kCoherent) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    else *p = v;
-}
-
 // LDS of one score workgroup: the A operands (clamped queries in double) of every MFMA step.
 template <typename T, int G, bool kLower> struct ScoreLds {
     static constexpr int kSteps = (Row<T>::kRowBytes / 64) * T::kEpl;      // 32
@@ -46,7 +39,7 @@ template <typename T, int G, bool kLower> struct ScoreLds {
 // Two at a time is the shape of large launches: a wave then has 8 KiB (16-bit rows) in flight from
 // its first instruction on and a workgroup reads 32 KiB; on MI355X this streamed 6-7 % faster than
 // groups of four sets fetched two at a time.
-template <typename T, int G, bool kLower, bool kSingle, bool kCoherent = false, int kUnit = 1>
+template <typename T, int G, bool kLower, bool kSingle, int kUnit = 1>
 __device__ __forceinline__ void score_unit(ScoreLds<T, G, kLower>& lds, const char* __restrict__ q,
                                            const char* __restrict__ abstract, const int32_t* __restrict__ n_chunks,
                                            float* __restrict__ score_ub, float* __restrict__ score_lb, int c_max,
@@ -105,8 +98,8 @@ __device__ __forceinline__ void score_unit(ScoreLds<T, G, kLower>& lds, const ch
     const int units_here = kSingle ? n_units : (n_sets + lead + 3) >> 2;
     if (bx * kScoreWaves >= units_here) {
         for (int c = C + bx * kThreads + (int)threadIdx.x; c < c_max; c += gx * kThreads) {
-            store_score<kCoherent>(&score_ub[bh * c_max + c], -INFINITY);
-            if (kLower) store_score<kCoherent>(&score_lb[bh * c_max + c], INFINITY);
+            score_ub[bh * c_max + c] = -INFINITY;
+            if (kLower) score_lb[bh * c_max + c] = INFINITY;
         }
         return;
     }
@@ -162,8 +155,8 @@ __device__ __forceinline__ void score_unit(ScoreLds<T, G, kLower>& lds, const ch
         if constexpr (kSingle) {
             const int c = set * kChunksPerSet + lane;
             if (lane < kChunksPerSet && c >= 0 && c < C) {
-                store_score<kCoherent>(&score_ub[bh * c_max + c], (float)ub + 0.0f);
-                if (kLower) store_score<kCoherent>(&score_lb[bh * c_max + c], (float)lb + 0.0f);
+                score_ub[bh * c_max + c] = (float)ub + 0.0f;
+                if (kLower) score_lb[bh * c_max + c] = (float)lb + 0.0f;
             }
             return;
         }
@@ -175,8 +168,8 @@ __device__ __forceinline__ void score_unit(ScoreLds<T, G, kLower>& lds, const ch
         if (slot == 3) {
             const int c = (set - 3) * kChunksPerSet + lane;          // lanes 0..31 <-> the 32 chunks of the group
             if (lane < 4 * kChunksPerSet && c >= 0 && c < C) {
-                store_score<kCoherent>(&score_ub[bh * c_max + c], pend_ub);
-                if (kLower) store_score<kCoherent>(&score_lb[bh * c_max + c], pend_lb);
+                score_ub[bh * c_max + c] = pend_ub;
+                if (kLower) score_lb[bh * c_max + c] = pend_lb;
             }
         }
     };
@@ -257,8 +250,8 @@ __device__ __forceinline__ void score_unit(ScoreLds<T, G, kLower>& lds, const ch
     }
     // tail of the row: chunks that do not exist
     for (int c = C + bx * kThreads + (int)threadIdx.x; c < c_max; c += gx * kThreads) {
-        store_score<kCoherent>(&score_ub[bh * c_max + c], -INFINITY);
-        if (kLower) store_score<kCoherent>(&score_lb[bh * c_max + c], INFINITY);
+        score_ub[bh * c_max + c] = -INFINITY;
+        if (kLower) score_lb[bh * c_max + c] = INFINITY;
     }
 }
 

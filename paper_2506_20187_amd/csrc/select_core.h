@@ -123,17 +123,7 @@ template <int kIpt> struct SelectResult {
     uint64_t kept_total;      // the same over the whole (sequence, kv head)
 };
 
-// A score as the selection reads it.  kCoherent: the row was written earlier in the SAME launch by
-// workgroups on other XCDs (agent-scope write-through stores), so it is read with agent-scope loads.
-template <bool kCoherent> __device__ __forceinline__ float load_score(const float* p) {
-    if constexpr (kCoherent) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    else return *p;
-}
-
-// Every lane of the kThreads-lane workgroup (256 or 1024) must call this (it contains barriers).
-// srow: the (b,h) row of scores, off: the sequence's boundary row (c_max + 1 entries).
-// kIpt * kThreads >= c_max.
-template <int kIpt, int kThreads = kSelThreads, bool kCoherent = false>
+template <int kIpt, int kThreads = kSelThreads>
 __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restrict__ srow,
                                             const int32_t* __restrict__ off, int C, int c_max, int k_max, int n_ctx,
                                             int max_chunks, int token_budget, SelectResult<kIpt>& R) {
@@ -164,7 +154,7 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
 #pragma unroll
         for (int i = 0; i <= kIpt; ++i) offv[i] = off[min(c0 + i, c_max)];
 #pragma unroll
-        for (int i = 0; i < kIpt; ++i) sc[i] = load_score<kCoherent>(srow + min(c0 + i, c_max - 1));
+        for (int i = 0; i < kIpt; ++i) sc[i] = srow[min(c0 + i, c_max - 1)];
     } else {
         // A lane's kIpt consecutive items are 4*kIpt bytes apart from its neighbour's: read
         // directly, every load instruction would touch 64 * kIpt * 4 / 128 cache lines.  The
@@ -179,7 +169,7 @@ __device__ __forceinline__ void select_keep(SelectLds& L, const float* __restric
         int ro_end = off[min(wbase + LEOAM_WAVE * kIpt, c_max)];
 #pragma unroll
         for (int j = 0; j < kIpt; ++j) {
-            rs[j] = load_score<kCoherent>(srow + min(wbase + LEOAM_WAVE * j + lane, c_max - 1));
+            rs[j] = srow[min(wbase + LEOAM_WAVE * j + lane, c_max - 1)];
             ro[j] = off[min(wbase + LEOAM_WAVE * j + lane, c_max)];
         }
         asm volatile("" : "+v"(ro_end));
