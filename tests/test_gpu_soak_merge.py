@@ -10,6 +10,8 @@ re-poisoned with a changing pattern before every launch, and every result is com
 first one (which is checked against the oracle).  The loop stops at the first mismatch.
 (Two splits per (sequence, kv head) at batch sizes that reserve exchange words are combined differently - one
 atomic exchange per output element carries the value itself - and are soaked the same way.)"""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -17,7 +19,7 @@ import torch
 import gen
 
 pytestmark = pytest.mark.gpu
-LAUNCHES = 2000
+LAUNCHES = int(os.environ.get("LEOAM_SOAK_LAUNCHES", "2000"))      # per configuration; a longer soak: set the variable
 
 
 @pytest.fixture(scope="module")
