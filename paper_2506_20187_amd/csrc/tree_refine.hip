@@ -286,7 +286,7 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
     const char* __restrict__ q, const char* __restrict__ K, const char* __restrict__ abstract, int chunk_size,
     int k_tokens, int max_rounds, int node_cap, int32_t* __restrict__ ref_off, float* __restrict__ ref_score,
     int32_t* __restrict__ ref_count, int32_t* __restrict__ ref_evals, int32_t* __restrict__ ref_status,
-    TreeNode* nodes_a, TreeNode* nodes_b, int32_t* pos_buf, TreeTask* task_buf, int n_ctx, int c_max, int n_kv_heads, int G) {
+    TreeNode* nodes_a, TreeNode* nodes_b, TreeTask* task_buf, int n_ctx, int c_max, int n_kv_heads, int G) {
     constexpr int ROWB = Row<T>::kRowBytes;
     constexpr int EPL = T::kEpl;
     __shared__ TreeLds S;
@@ -297,7 +297,6 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
     const int m0 = (n_ctx + chunk_size - 1) / chunk_size;
     TreeNode* cur = nodes_a + bh * (size_t)node_cap;
     TreeNode* nxt = nodes_b + bh * (size_t)node_cap;
-    int32_t* pos = pos_buf + bh * (size_t)node_cap;
     TreeTask* task = task_buf + bh * (size_t)((node_cap + 1) / 2);
     constexpr int LPR = Row<T>::kLanesPerRow;
     constexpr int kGroups = kTreeThreads / LPR;              // node evaluations in flight per workgroup
@@ -480,69 +479,75 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
         // ---- which nodes are split, and where everything goes --------------------------
         auto is_split = [&](const TreeNode& nd) { return nd.U >= v && !(nd.L > mu) && nd.size > 1; };
         // (a thread's nodes are consecutive: positions = scan of the threads' widths + a running sum)
-        int my_pos[kTreeCache];
-        uint32_t carry = 0;
-        auto scan_tile = [&](int base, auto&& node_of, auto&& put) {
-            uint32_t local[kTreeCache], width = 0;
+        // Unsplit nodes move to their new place; split nodes are listed as tasks, in two classes: nodes of
+        // two tokens (both halves are single tokens, which the evaluation handles with one dot product
+        // per head) fill the task list from the front, all others from the back, so that a wave's lane
+        // groups work on nodes of one kind.  Everything is written while the tiles are scanned (a position
+        // is final once the tiles before it are counted); should the round turn out not to fit node_cap,
+        // the writes - kept inside the buffers - are simply abandoned.
+        const int task_cap = (node_cap + 1) / 2;
+        uint32_t carry = 0, carry_two = 0;
+        auto scan_tile = [&](int base, auto&& node_of) {
+            uint32_t local[kTreeCache], local_two[kTreeCache], width = 0, n_two = 0;
 #pragma unroll
             for (int j = 0; j < kTreeCache; ++j) {
                 const int i = base + tid * kTreeCache + j;
                 local[j] = width;
-                if (i < n) width += is_split(node_of(i, j)) ? 2u : 1u;
+                local_two[j] = n_two;
+                if (i < n) {
+                    const TreeNode nd = node_of(i, j);
+                    const bool sp = is_split(nd);
+                    width += sp ? 2u : 1u;
+                    n_two += (sp && nd.size == 2) ? 1u : 0u;
+                }
             }
-            uint32_t total;
+            uint32_t total, total_two;
             const uint32_t before = carry + tree_block_scan(width, S.wave_tot, &total);
+            const uint32_t before_two = carry_two + tree_block_scan(n_two, S.wave_tot, &total_two);
 #pragma unroll
-            for (int j = 0; j < kTreeCache; ++j) put(base + tid * kTreeCache + j, j, (int)(before + local[j]));
+            for (int j = 0; j < kTreeCache; ++j) {
+                const int i = base + tid * kTreeCache + j;
+                if (i < n) {
+                    const TreeNode nd = node_of(i, j);
+                    const int p = (int)(before + local[j]);
+                    if (is_split(nd)) {
+                        // (position - index = number of splits before the node)
+                        const int twos = (int)(before_two + local_two[j]), others = (p - i) - twos;
+                        const int slot = nd.size == 2 ? twos : task_cap - 1 - others;
+                        TreeTask tk;
+                        tk.start = nd.start;
+                        tk.size = nd.size;
+                        tk.pos = p;
+                        tk.pad = 0;
+                        if (slot >= 0 && slot < task_cap) task[slot] = tk;
+                    } else if (p < node_cap) {
+                        nxt[p] = nd;
+                    }
+                }
+            }
             carry += total;
+            carry_two += total_two;
         };
-        scan_tile(0, [&](int, int j) -> const TreeNode& { return cn[j]; }, [&](int, int j, int p) { my_pos[j] = p; });
-        for (int base = kTreeTile; base < n; base += kTreeTile)
-            scan_tile(base, [&](int i, int) { return cur[i]; }, [&](int i, int, int p) {
-                if (i < n) pos[i] = p;
-            });
-        const int n_new = (int)carry, n_split = n_new - n;
+        scan_tile(0, [&](int, int j) -> const TreeNode& { return cn[j]; });
+        for (int base = kTreeTile; base < n; base += kTreeTile) scan_tile(base, [&](int i, int) { return cur[i]; });
+        const int n_new = (int)carry, n_split = n_new - n, n_two = (int)carry_two;
         if (n_split == 0) break;
         if (n_new > node_cap) {
             status = 1;
             break;
         }
-        // ---- unsplit nodes move to their new place; split nodes are listed -----------------
-        // (position - index = number of splits before the node = its slot in the list)
-        auto place = [&](int i, int p, const TreeNode& nd) {
-            if (is_split(nd)) {
-                TreeTask tk;
-                tk.start = nd.start;
-                tk.size = nd.size;
-                tk.pos = p;
-                tk.pad = 0;
-                task[p - i] = tk;
-            } else {
-                nxt[p] = nd;
-            }
-        };
-#pragma unroll
-        for (int j = 0; j < kTreeCache; ++j) {
-            const int i = tid * kTreeCache + j;
-            if (i < n) place(i, my_pos[j], cn[j]);
-        }
-        for (int base = kTreeTile; base < n; base += kTreeTile)
-#pragma unroll
-            for (int j = 0; j < kTreeCache; ++j) {
-                const int i = base + tid * kTreeCache + j;
-                if (i < n) place(i, pos[i], cur[i]);      // pos[i]: this thread's own store
-            }
         __syncthreads();
         // ---- a lane group takes one half of a listed node and evaluates it from its keys; the
         // next task's entry is fetched before the evaluation ----------------------------------
-        // (the loop is uniform over the wave: a lane group past the end evaluates row 0 and stores nothing)
-        {
+        // (the loops are uniform over the wave: a lane group past the end evaluates row 0 and stores nothing)
+        auto eval_class = [&](int count, auto&& task_at) {
             constexpr int kGroupsPerWave = LEOAM_WAVE / LPR;
-            TreeTask tk = task[min(gid >> 1, n_split - 1)];
-            for (int t0 = wave * kGroupsPerWave; t0 < 2 * n_split; t0 += kGroups) {
+            if (count == 0) return;
+            TreeTask tk = task_at(min(gid >> 1, count - 1));
+            for (int t0 = wave * kGroupsPerWave; t0 < 2 * count; t0 += kGroups) {
                 const int t = t0 + gid % kGroupsPerWave;
-                const bool live = t < 2 * n_split;
-                const TreeTask nx = task[min((t + kGroups) >> 1, n_split - 1)];
+                const bool live = t < 2 * count;
+                const TreeTask nx = task_at(min((t + kGroups) >> 1, count - 1));
                 const int second = t & 1, left = (tk.size + 1) / 2;
                 TreeNode c;
                 c.start = live ? (second ? tk.start + left : tk.start) : 0;
@@ -551,7 +556,9 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
                 if (g_lead && live) nxt[tk.pos + second] = c;
                 tk = nx;
             }
-        }
+        };
+        eval_class(n_two, [&](int k) { return task[k]; });
+        eval_class(n_split - n_two, [&](int k) { return task[task_cap - 1 - k]; });
         __syncthreads();
         TreeNode* tmp = cur;
         cur = nxt;
@@ -635,9 +642,9 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
 }
 
 size_t tree_workspace_bytes(const leoam_shape* s, int node_cap) {
-    // two node lists, the task list (a split adds a node, so at most node_cap / 2 per round), positions
+    // two node lists and the task list (a split adds a node, so at most node_cap / 2 per round)
     return (size_t)s->batch * s->n_kv_heads *
-           ((size_t)node_cap * (2 * sizeof(TreeNode) + sizeof(int32_t)) + (size_t)((node_cap + 1) / 2) * sizeof(TreeTask));
+           ((size_t)node_cap * 2 * sizeof(TreeNode) + (size_t)((node_cap + 1) / 2) * sizeof(TreeTask));
 }
 
 hipError_t tree_refine_dispatch(const leoam_shape* s, const void* q, const void* K, const void* abstract,
@@ -648,13 +655,12 @@ hipError_t tree_refine_dispatch(const leoam_shape* s, const void* q, const void*
     TreeNode* a = (TreeNode*)workspace;
     TreeNode* b = a + units * (size_t)node_cap;
     TreeTask* task = (TreeTask*)(b + units * (size_t)node_cap);
-    int32_t* pos = (int32_t*)(task + units * (size_t)((node_cap + 1) / 2));
     dim3 grid(s->n_kv_heads, s->batch), block(kTreeThreads);
     const int G = s->n_q_heads / s->n_kv_heads;
 #define LEOAM_TREE(TT)                                                                                           \
     hipLaunchKernelGGL(tree_refine_kernel<TT>, grid, block, 0, stream, (const char*)q, (const char*)K,            \
                        (const char*)abstract, chunk_size, k_tokens, max_rounds, node_cap, ref_off, ref_score,    \
-                       ref_count, ref_evals, ref_status, a, b, pos, task, s->n_ctx, s->c_max, s->n_kv_heads, G)
+                       ref_count, ref_evals, ref_status, a, b, task, s->n_ctx, s->c_max, s->n_kv_heads, G)
     switch (s->kv_dtype) {
     case LEOAM_F32: LEOAM_TREE(F32); break;
     case LEOAM_F16: LEOAM_TREE(F16); break;

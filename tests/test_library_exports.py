@@ -63,7 +63,7 @@ def test_host_side_checks_of_the_later_entry_points():
     assert L.leoam_fused_workspace_bytes(L.make_shape(16, 32, 8, 64, 131072, 4096, 256, 2), 4096) == 0
     # tree refinement: node_cap below the initial chunk count, k outside [1, n_ctx], compressed store
     t = L.make_shape(1, 4, 1, 128, 4096, 64, 1, 2)
-    assert L.leoam_tree_workspace_bytes(t, 1000) == 1 * 1 * (1000 * (2 * 16 + 4) + 500 * 16)
+    assert L.leoam_tree_workspace_bytes(t, 1000) == 1 * 1 * (1000 * 2 * 16 + 500 * 16)
     args = [None] * 3
     def refine(shape, cs, k, rounds, cap):
         return lib.chunk_tree_refine(ctypes.byref(shape), None, None, None, cs, k, rounds, cap, None, None, None, None,
