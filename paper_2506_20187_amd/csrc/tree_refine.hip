@@ -30,13 +30,18 @@
 // key rows (the two abstract rows for an initial chunk), then the bounds in
 // double, rounded once to float - so a wave has 4 (fp32: 2) nodes in flight.
 // For four query heads the lanes of a quad trade partial sums so that the
-// cross-lane reduction handles the eight sums of a node together.  The
+// cross-lane reduction handles the eight sums of a node together.
+// The halves of two-token nodes are single tokens (U = L = max_j q_j.k); with up
+// to four heads per group a wave evaluates sixteen of them at a time on the matrix
+// cores (v_mfma_f64_4x4x4 as in chunk_score.hip: the sixteen B rows are the
+// tokens' key rows, every A block carries the queries), the rows of several
+// such groups in flight.  The
 // evaluation phase dominates: its first rounds are bound by what one compute
 // unit can fetch, the later ones by the double-precision arithmetic.
 #include <cfloat>
 #include <type_traits>
 
-#include "leoam_dev.h"
+#include "score_core.h"
 
 namespace leoam {
 
@@ -67,6 +72,13 @@ struct TreeLds {
     uint32_t key_lo, key_hi, digit, rank;
     uint32_t ge_weight, below_key, below_any;
     uint32_t carry;
+};
+
+// A operands of the single-token evaluation on the matrix cores (groups of up to four heads): the
+// queries in double for each of the 32 steps; lane = 16 * channel quarter + 4 * block + head, every
+// block the same.
+struct TreeTokenLds {
+    double q[32][LEOAM_WAVE];
 };
 
 // A task of the evaluation phase: a node that is split, and where its halves go.
@@ -281,6 +293,37 @@ __device__ __forceinline__ void tree_eval(const char* rows, int n_rows, const do
     *L = lb;
 }
 
+// Sixteen single tokens per wave on the matrix cores.  Lane (r = lane & 15, kq = lane >> 4) holds the
+// four 16-byte pieces 64 i + 16 kq of token r's key row (`v`, fetched by tree_fetch_row); step (i, e)
+// multiplies the four heads' values of its four channels with the sixteen rows' (block = four rows),
+// so that after the 32 steps result lane 16 * head + r holds q_head . k_r; two lane swaps take the
+// maximum over the heads.  Every lane returns the importance of token lane & 15.
+template <typename T>
+__device__ __forceinline__ void tree_fetch_row(const char* row, uint4* v) {
+    constexpr int NLOAD = Row<T>::kRowBytes / 64;
+    const int kq = lane_id() >> 4;
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) v[i] = load16(row, 64 * i + 16 * kq);
+}
+template <typename T>
+__device__ __forceinline__ float tree_tokens16(const uint4* v, const TreeTokenLds& A, int G) {
+    constexpr int EPL = T::kEpl;
+    constexpr int NLOAD = Row<T>::kRowBytes / 64;
+    int q_lane = lane_id();
+    asm volatile("" : "+v"(q_lane));      // keeps the LDS reads of the A operands inside this call
+    double acc[2] = {0.0, 0.0};
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+        float x[EPL];
+        unpack<T>(v[i], x);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e)
+            acc[e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(A.q[i * EPL + e][q_lane], (double)x[e], acc[e & 1], 0, 0, 0);
+    }
+    const bool real = (q_lane >> 4) < G;      // result row group = head
+    return (float)rows_extreme4_d<true>(real ? acc[0] + acc[1] : -INFINITY) + 0.0f;
+}
+
 template <typename T>
 __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
     const char* __restrict__ q, const char* __restrict__ K, const char* __restrict__ abstract, int chunk_size,
@@ -290,6 +333,10 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
     constexpr int ROWB = Row<T>::kRowBytes;
     constexpr int EPL = T::kEpl;
     __shared__ TreeLds S;
+    __shared__ TreeTokenLds A;
+    constexpr int NLOAD = ROWB / 64;
+    constexpr int kTokenPasses = 8 / NLOAD;        // groups of sixteen tokens a wave keeps in flight (8 loads per lane)
+    const bool token_mfma = G <= 4;
 
     const int h = blockIdx.x, b = blockIdx.y;
     const size_t bh = (size_t)b * n_kv_heads + h;
@@ -318,6 +365,14 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
         }
     }
     for (int i = tid; i < 256; i += kTreeThreads) S.hist[i] = 0;
+    if (token_mfma && wave < NLOAD) {
+        // wave i converts the 16-byte pieces i of the queries: lane (head, block, channel quarter)
+        const int a_head = lane & 3, kq = lane >> 4, i = wave;
+        float x[EPL];
+        unpack<T>(load16(q, ((size_t)b * n_kv_heads * G + (size_t)h * G + min(a_head, G - 1)) * ROWB + 64 * i + 16 * kq), x);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) A.q[i * EPL + e][lane] = (a_head < G) ? (double)x[e] : 0.0;
+    }
     __syncthreads();
 
     // ---- initial chunks: bounds from the abstract rows (kmax row, kmin row) ----------
@@ -557,7 +612,34 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
                 tk = nx;
             }
         };
-        eval_class(n_two, [&](int k) { return task[k]; });
+        if (token_mfma) {
+            // the halves of the two-token nodes: token t of the class belongs to task t >> 1
+            const int total = 2 * n_two;
+            for (int t0 = wave * 16 * kTokenPasses; t0 < total; t0 += kTreeWaves * 16 * kTokenPasses) {
+                uint4 v[kTokenPasses][NLOAD];
+                int row[kTokenPasses], put[kTokenPasses];
+#pragma unroll
+                for (int p = 0; p < kTokenPasses; ++p) {
+                    const int t = t0 + 16 * p + (lane & 15);
+                    const TreeTask tk = task[min(t >> 1, n_two - 1)];
+                    row[p] = t < total ? tk.start + (t & 1) : 0;
+                    put[p] = t < total ? tk.pos + (t & 1) : -1;
+                }
+#pragma unroll
+                for (int p = 0; p < kTokenPasses; ++p) tree_fetch_row<T>(Kbh + (size_t)row[p] * ROWB, v[p]);
+#pragma unroll
+                for (int p = 0; p < kTokenPasses; ++p) {
+                    TreeNode c;
+                    c.U = tree_tokens16<T>(v[p], A, G);
+                    c.L = c.U;
+                    c.start = row[p];
+                    c.size = 1;
+                    if (lane < 16 && put[p] >= 0) nxt[put[p]] = c;
+                }
+            }
+        } else {
+            eval_class(n_two, [&](int k) { return task[k]; });
+        }
         eval_class(n_split - n_two, [&](int k) { return task[task_cap - 1 - k]; });
         __syncthreads();
         TreeNode* tmp = cur;
