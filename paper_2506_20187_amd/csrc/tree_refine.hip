@@ -74,11 +74,12 @@ struct TreeLds {
     uint32_t carry;
 };
 
-// A operands of the single-token evaluation on the matrix cores (groups of up to four heads): the
-// queries in double for each of the 32 steps; lane = 16 * channel quarter + 4 * block + head, every
-// block the same.
-struct TreeTokenLds {
-    double q[32][LEOAM_WAVE];
+// A operands of the evaluations on the matrix cores (groups of up to four heads): clamped queries in
+// double for each of the 32 steps; lane = 16 * channel quarter + 4 * block + head.  qa (upper bound):
+// blocks 0-1 carry max(q,0), blocks 2-3 min(q,0); qb (lower bound): the reverse.  qa + qb is the query
+// itself in every block (one of the two is zero), which is what single tokens are multiplied with.
+struct TreeMfmaLds {
+    double qa[32][LEOAM_WAVE], qb[32][LEOAM_WAVE];
 };
 
 // A task of the evaluation phase: a node that is split, and where its halves go.
@@ -306,7 +307,7 @@ __device__ __forceinline__ void tree_fetch_row(const char* row, uint4* v) {
     for (int i = 0; i < NLOAD; ++i) v[i] = load16(row, 64 * i + 16 * kq);
 }
 template <typename T>
-__device__ __forceinline__ float tree_tokens16(const uint4* v, const TreeTokenLds& A, int G) {
+__device__ __forceinline__ float tree_tokens16(const uint4* v, const TreeMfmaLds& A, int G) {
     constexpr int EPL = T::kEpl;
     constexpr int NLOAD = Row<T>::kRowBytes / 64;
     int q_lane = lane_id();
@@ -318,10 +319,69 @@ __device__ __forceinline__ float tree_tokens16(const uint4* v, const TreeTokenLd
         unpack<T>(v[i], x);
 #pragma unroll
         for (int e = 0; e < EPL; ++e)
-            acc[e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(A.q[i * EPL + e][q_lane], (double)x[e], acc[e & 1], 0, 0, 0);
+            acc[e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(A.qa[i * EPL + e][q_lane] + A.qb[i * EPL + e][q_lane], (double)x[e],
+                                                            acc[e & 1], 0, 0, 0);
     }
     const bool real = (q_lane >> 4) < G;      // result row group = head
     return (float)rows_extreme4_d<true>(real ? acc[0] + acc[1] : -INFINITY) + 0.0f;
+}
+
+// Eight nodes of up to kRows key rows per wave on the matrix cores, both bounds.  Lane (r = lane & 15,
+// kq = lane >> 4) works for node r & 7: tree_fetch_node reads its pieces of the node's rows (a row
+// index past the node's end re-reads its last row), tree_nodes8 folds them into their element-wise
+// maximum (r < 8) or minimum (r >= 8) - its B operand - and contracts: B rows 0-7 are the nodes' kmax
+// rows, rows 8-15 their kmin rows, the sums of the two halves are joined by one add and the maximum over
+// the heads by two lane swaps.  Every lane returns U and L of node lane & 7.
+template <typename T, int kRows>
+__device__ __forceinline__ void tree_fetch_node(const char* my_rows, int my_n, uint4 (*v)[Row<T>::kRowBytes / 64]) {
+    constexpr int ROWB = Row<T>::kRowBytes;
+    constexpr int NLOAD = ROWB / 64;
+    const int kq = lane_id() >> 4;
+#pragma unroll
+    for (int t = 0; t < kRows; ++t)
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) v[t][i] = load16(my_rows, (size_t)min(t, my_n - 1) * ROWB + 64 * i + 16 * kq);
+}
+template <typename T, int kRows>
+__device__ __forceinline__ void tree_nodes8(const uint4 (*v)[Row<T>::kRowBytes / 64], const TreeMfmaLds& A, int G, float* U,
+                                            float* L) {
+    constexpr int EPL = T::kEpl;
+    constexpr int NLOAD = Row<T>::kRowBytes / 64;
+    int q_lane = lane_id();
+    asm volatile("" : "+v"(q_lane));
+    // minimum lanes fold -x with max: -max(-x) = min(x), exactly
+    const float sign = (q_lane & 8) ? -1.f : 1.f;
+    double ua[2] = {0.0, 0.0}, la[2] = {0.0, 0.0};
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+        float x[EPL];
+        unpack<T>(v[0][i], x);
+        if constexpr (kRows > 1) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) x[e] *= sign;
+#pragma unroll
+            for (int t = 1; t < kRows; ++t) {
+                float y[EPL];
+                unpack<T>(v[t][i], y);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) x[e] = fmaxf(x[e], y[e] * sign);
+            }
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) x[e] *= sign;
+        }
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+            const double xd = (double)x[e];
+            ua[e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(A.qa[i * EPL + e][q_lane], xd, ua[e & 1], 0, 0, 0);
+            la[e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(A.qb[i * EPL + e][q_lane], xd, la[e & 1], 0, 0, 0);
+        }
+    }
+    // result lane = 16 * head + B row; rows r and r + 8 are the two halves of node r & 7
+    const bool real = (q_lane >> 4) < G;
+    const double u1 = ua[0] + ua[1], l1 = la[0] + la[1];
+    const double ub = u1 + dpp_ror8_d(u1), lb = l1 + dpp_ror8_d(l1);
+    *U = (float)rows_extreme4_d<true>(real ? ub : -INFINITY) + 0.0f;
+    *L = (float)rows_extreme4_d<true>(real ? lb : -INFINITY) + 0.0f;
 }
 
 template <typename T>
@@ -333,10 +393,11 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
     constexpr int ROWB = Row<T>::kRowBytes;
     constexpr int EPL = T::kEpl;
     __shared__ TreeLds S;
-    __shared__ TreeTokenLds A;
+    __shared__ TreeMfmaLds A;
     constexpr int NLOAD = ROWB / 64;
     constexpr int kTokenPasses = 8 / NLOAD;        // groups of sixteen tokens a wave keeps in flight (8 loads per lane)
-    const bool token_mfma = G <= 4;
+    constexpr int kNodePasses = 16 / NLOAD;        // groups of eight one-row nodes in flight (16 loads per lane)
+    const bool mfma = G <= 4;
 
     const int h = blockIdx.x, b = blockIdx.y;
     const size_t bh = (size_t)b * n_kv_heads + h;
@@ -365,17 +426,46 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
         }
     }
     for (int i = tid; i < 256; i += kTreeThreads) S.hist[i] = 0;
-    if (token_mfma && wave < NLOAD) {
+    if (mfma && wave < NLOAD) {
         // wave i converts the 16-byte pieces i of the queries: lane (head, block, channel quarter)
         const int a_head = lane & 3, kq = lane >> 4, i = wave;
+        const bool a_min = ((lane >> 2) & 3) >= 2;
         float x[EPL];
         unpack<T>(load16(q, ((size_t)b * n_kv_heads * G + (size_t)h * G + min(a_head, G - 1)) * ROWB + 64 * i + 16 * kq), x);
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) A.q[i * EPL + e][lane] = (a_head < G) ? (double)x[e] : 0.0;
+        for (int e = 0; e < EPL; ++e) {
+            const float xe = (a_head < G) ? x[e] : 0.f;
+            const float pos = fmaxf(xe, 0.f), neg = fminf(xe, 0.f);
+            A.qa[i * EPL + e][lane] = (double)(a_min ? neg : pos);
+            A.qb[i * EPL + e][lane] = (double)(a_min ? pos : neg);
+        }
     }
     __syncthreads();
 
     // ---- initial chunks: bounds from the abstract rows (kmax row, kmin row) ----------
+    if (mfma) {
+        // eight chunks per wave and pass, kNodePasses passes in flight: lane (r, kq) reads its pieces of
+        // row 2 c + (r >> 3) of chunk c = c0 + 8 p + (r & 7) - the chunk's kmax row or its kmin row
+        for (int c0 = wave * 8 * kNodePasses; c0 < m0; c0 += kTreeWaves * 8 * kNodePasses) {
+            uint4 v[kNodePasses][1][NLOAD];
+#pragma unroll
+            for (int p = 0; p < kNodePasses; ++p) {
+                const int c = min(c0 + 8 * p + (lane & 7), m0 - 1);
+                tree_fetch_node<T, 1>(Abh + ((size_t)2 * c + ((lane >> 3) & 1)) * ROWB, 1, v[p]);
+            }
+#pragma unroll
+            for (int p = 0; p < kNodePasses; ++p) {
+                const int c = c0 + 8 * p + lane;
+                TreeNode nd;
+                tree_nodes8<T, 1>(v[p], A, G, &nd.U, &nd.L);
+                if (lane < 8 && c < m0) {
+                    nd.start = c * chunk_size;
+                    nd.size = min(chunk_size, n_ctx - c * chunk_size);
+                    cur[c] = nd;
+                }
+            }
+        }
+    } else
     for (int c0 = wave * (LEOAM_WAVE / LPR); c0 < m0; c0 += kGroups) {      // uniform over the wave
         const int c = min(c0 + gid % (LEOAM_WAVE / LPR), m0 - 1);
         float U, L;
@@ -612,7 +702,7 @@ __global__ __launch_bounds__(kTreeThreads) void tree_refine_kernel(
                 tk = nx;
             }
         };
-        if (token_mfma) {
+        if (mfma) {
             // the halves of the two-token nodes: token t of the class belongs to task t >> 1
             const int total = 2 * n_two;
             for (int t0 = wave * 16 * kTokenPasses; t0 < total; t0 += kTreeWaves * 16 * kTokenPasses) {
