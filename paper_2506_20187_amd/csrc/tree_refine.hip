@@ -35,9 +35,13 @@
 // to four heads per group a wave evaluates sixteen of them at a time on the matrix
 // cores (v_mfma_f64_4x4x4 as in chunk_score.hip: the sixteen B rows are the
 // tokens' key rows, every A block carries the queries), the rows of several
-// such groups in flight.  The
-// evaluation phase dominates: its first rounds are bound by what one compute
-// unit can fetch, the later ones by the double-precision arithmetic.
+// such groups in flight; the initial chunks are evaluated eight at a time the
+// same way, with both bounds (B rows 0-7 their kmax rows, rows 8-15 their kmin
+// rows).  To bring the single tokens together the split nodes of a round are
+// listed in two classes (two-token nodes from the front of the task list, the
+// others from its back).  The evaluation phase dominates: its first rounds are
+// chains of dependent round trips (large nodes, few of them), the later ones are
+// bound by the double-precision arithmetic.
 #include <cfloat>
 #include <type_traits>
 
