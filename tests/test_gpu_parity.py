@@ -499,6 +499,24 @@ def test_path_c3_reduced_batch(L, oracle, separate):
     check_path(L, oracle, case, separate=separate)
 
 
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_path_random_shapes(L, oracle, seed):
+    """Shapes drawn at random (seeded): workload recipe, dtype, batch, heads and group size, ragged context
+    length, token budget and chunk limit, one-call or separate entry points; every step against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    config = ("c1", "c2", "c3")[int(rng.integers(3))]
+    dtype = ("f32", "f16", "bf16")[int(rng.integers(3))]
+    hkv = int(rng.integers(1, 4))
+    g = (1, 2, 4, 8)[int(rng.integers(4))]
+    batch = int(rng.integers(1, 4))
+    n_ctx = int(rng.integers(300, 6000))
+    budget = int(rng.integers(1, n_ctx))
+    max_chunks = int(rng.integers(0, 40))           # 0: no chunk limit
+    case = gen.make_case(config, layer=int(rng.integers(32)), batch=batch, n_ctx=n_ctx, hq=hkv * g, hkv=hkv, dtype=dtype,
+                         token_budget=budget, max_chunks=max_chunks)
+    check_path(L, oracle, case, separate=bool(rng.integers(2)))
+
+
 def test_path_two_splits_per_head(L, oracle):
     """16 sequences x 8 kv heads: two workgroups per (sequence, kv head), combined through the exchange words of the
     workspace (one atomic exchange per output element); ragged context, small budget."""
