@@ -293,7 +293,7 @@ def make_case(config: str, layer: int = 0, *, device="cpu", seed: int = BASE_SEE
     packed, counts, c_max = pack_boundaries(offs, N, c_max=(most + 31) // 32 * 32)
     smallest = min(int(np.diff(o).min()) for o in offs)
     if cfg["max_chunks"] > 0:
-        k_max = cfg["max_chunks"]
+        k_max = min(c_max, cfg["max_chunks"])
     elif cfg["token_budget"] > 0:
         k_max = min(c_max, cfg["token_budget"] // max(1, smallest))
     else:

@@ -465,7 +465,10 @@ def check_path(L, oracle, case, seqs=None, separate=False):
     out, lse = oracle.sparse_attention(q, K, V, off, sel, cnt)
     err = np.abs(host_f64(layer.out[sl]) - out).max()
     assert err <= TOL[case.dtype], f"attention max-abs error {err}"
-    assert np.abs(host_f64(layer.lse[sl]) - lse).max() <= 1e-3
+    got_lse = host_f64(layer.lse[sl])
+    assert np.array_equal(np.isneginf(got_lse), np.isneginf(lse)), "lse: -inf exactly where nothing is kept"
+    kept = ~np.isneginf(lse)
+    assert not kept.any() or np.abs(got_lse[kept] - lse[kept]).max() <= 1e-3, "lse"
     return dict(err=err, tokens=tok, margin=margin)
 
 
@@ -499,7 +502,7 @@ def test_path_c3_reduced_batch(L, oracle, separate):
     check_path(L, oracle, case, separate=separate)
 
 
-@pytest.mark.parametrize("seed", list(range(12)))
+@pytest.mark.parametrize("seed", list(range(24)))
 def test_path_random_shapes(L, oracle, seed):
     """Shapes drawn at random (seeded): workload recipe, dtype, batch, heads and group size, ragged context
     length, token budget and chunk limit, one-call or separate entry points; every step against the oracle."""
