@@ -799,6 +799,40 @@ def test_tree_refine_exact(L, oracle, dtype, G, N, cs):
         check_tree(L, oracle, dtype, q, K, cs, max(1, k), rounds, cap)
 
 
+@pytest.mark.parametrize("seed", list(range(16)))
+def test_tree_refine_random_shapes(L, oracle, seed):
+    """Shapes and data drawn at random (seeded): dtype, group size, ragged context, initial chunk size, k, round limit,
+    node capacity (sometimes too small: reported), Gaussian keys / hot runs in a desert / small-integer keys with
+    massive ties."""
+    rng = np.random.default_rng(5000 + seed)
+    dtype = ("f32", "f16", "bf16")[int(rng.integers(3))]
+    G = (1, 2, 4, 8)[int(rng.integers(4))]
+    B, Hkv, D = int(rng.integers(1, 3)), int(rng.integers(1, 3)), 128
+    N = int(rng.integers(40, 3000))
+    cs = (4, 8, 16, 32, 64)[int(rng.integers(5))]
+    m0 = -(-N // cs)
+    k = int(rng.integers(1, N + 1)) if rng.integers(4) else int(rng.integers(1, max(2, N // 20)))
+    rounds = (0, 1, 3, 10 ** 6)[int(rng.integers(4))]
+    cap = max(m0, m0 + int(rng.integers(0, N)) if rng.integers(3) else N)
+    kind = int(rng.integers(3))
+    g = torch.Generator().manual_seed(seed)
+    if kind == 0:
+        K = torch.randn(B, Hkv, N, D, generator=g)
+    elif kind == 1:
+        K = torch.randn(B, Hkv, N, D, generator=g) * 0.1
+    else:
+        K = torch.randint(-2, 3, (B, Hkv, N, D), generator=g).float()
+    q = torch.randn(B, Hkv * G, D, generator=g)
+    if kind == 1:
+        for b in range(B):
+            for h in range(Hkv):
+                for s0 in rng.integers(0, max(1, N - 20), size=4):
+                    K[b, h, s0:s0 + int(rng.integers(1, 20))] += 5.0 * (q[b, h * G] / q[b, h * G].norm())
+    if kind == 2:
+        q = torch.randint(-2, 3, (B, Hkv * G, D), generator=g).float()
+    check_tree(L, oracle, dtype, q.to(TDT[dtype]), K.to(TDT[dtype]), cs, k, rounds, cap)
+
+
 def test_tree_refine_ties_and_deserts(L, oracle):
     # all tokens equal: the complete tree, ties resolved by index
     K = torch.ones(1, 2, 64, 128)
