@@ -62,6 +62,26 @@ def test_compress_exact_ragged_chunks(L, oracle, dtype, share):
     check_against_oracle(oracle, gpu_compress(L, K, V, packed, counts, fb), K, V, packed, counts, fb)
 
 
+@pytest.mark.parametrize("seed", list(range(8)))
+def test_compress_random_shapes(L, oracle, seed):
+    """Shapes and value ranges drawn at random (seeded): dtype, batch, heads, ragged context, chunk-size mixes from
+    single tokens to 300 rows, magnitudes over five decades, values on a coarse grid (ties at the code boundaries),
+    any share of 4-bit chunks."""
+    rng = np.random.default_rng(7000 + seed)
+    dtype = (torch.float16, torch.bfloat16)[int(rng.integers(2))]
+    B, Hkv, N = int(rng.integers(1, 6)), int(rng.integers(1, 4)), int(rng.integers(50, 4000))
+    g = torch.Generator().manual_seed(seed)
+    K = (torch.randn(B, Hkv, N, 128, generator=g) * float(10 ** rng.uniform(-3, 2))).to(dtype)
+    V = (torch.randn(B, Hkv, N, 128, generator=g) * float(10 ** rng.uniform(-2, 1))).to(dtype)
+    if rng.integers(3) == 0:
+        K = (torch.randint(-8, 9, (B, Hkv, N, 128), generator=g).float() * 0.25).to(dtype)
+    sizes = [(1, 2, 15, 16, 63, 64, 65, 130, 200), (1, 3, 16, 40, 70), (32, 64), (1,), (7, 300)][int(rng.integers(5))]
+    offs = [gen.make_boundaries(N, rng, sizes=sizes) for _ in range(B)]
+    packed, counts, c_max = gen.pack_boundaries(offs, N)
+    fb = rng.random((B, c_max)) < rng.random()
+    check_against_oracle(oracle, gpu_compress(L, K, V, packed, counts, fb), K, V, packed, counts, fb)
+
+
 def test_compress_many_sequences(L, oracle):
     # more sequences than the layout kernel sums in one round (a wave per earlier sequence, sixteen at a time)
     rng = np.random.default_rng(77)
