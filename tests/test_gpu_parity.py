@@ -218,6 +218,34 @@ def test_score_exact_tiny_capacity_many_sequences(L, oracle, dtype, G, c_max):
     assert np.array_equal(s_only.cpu().numpy(), ub)
 
 
+@pytest.mark.parametrize("seed", list(range(10)))
+def test_score_exact_random_shapes(L, oracle, seed):
+    """Launch shapes drawn at random (seeded): dtype, group size, kv heads, capacity 1 ... 1200 and as many sequences as
+    keep the oracle quick (small and large launches, pairs and groups), ragged chunk counts."""
+    rng = np.random.default_rng(13000 + seed)
+    dtype = ("f32", "f16", "bf16")[int(rng.integers(3))]
+    G = (1, 2, 4, 8)[int(rng.integers(4))]
+    Hkv, D = int(rng.integers(1, 9)), 128
+    c_max = int(rng.integers(1, 1200))
+    B = int(rng.integers(1, max(2, min(700, 1_500_000 // (Hkv * c_max)))))
+    counts = rng.integers(0, c_max + 1, size=B).astype(np.int32)
+    counts[0] = c_max
+    a = rng.standard_normal((B, Hkv, c_max, D)).astype(np.float32)
+    b = rng.standard_normal((B, Hkv, c_max, D)).astype(np.float32)
+    ab = torch.from_numpy(np.stack([np.maximum(a, b), np.minimum(a, b)], axis=3)).to(TDT[dtype])
+    q = torch.from_numpy(rng.standard_normal((B, Hkv * G, D)).astype(np.float32)).to(TDT[dtype])
+    ub, lb = oracle.chunk_score(q, ab.to(torch.float64).numpy(), counts, want_lower=True)
+    shape = L.make_shape(B, Hkv * G, Hkv, D, 4096, c_max, 1, TDT[dtype])
+    s_ub = torch.empty(B, Hkv, c_max, dtype=torch.float32, device="cuda")
+    s_lb, s_only = torch.empty_like(s_ub), torch.empty_like(s_ub)
+    L.chunk_score(shape, dev(q), dev(ab), dev(counts), s_ub, s_lb)
+    L.chunk_score(shape, dev(q), dev(ab), dev(counts), s_only, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(s_ub.cpu().numpy(), ub)
+    assert np.array_equal(s_lb.cpu().numpy(), lb)
+    assert np.array_equal(s_only.cpu().numpy(), ub)
+
+
 # ---------------------------------------------------------------------------
 # a3 select
 # ---------------------------------------------------------------------------
